@@ -1,0 +1,152 @@
+/*
+ * xfp.h - C ABI of the MI355X (gfx950) XFP fused decode library.
+ *
+ * The library computes the decode-time product of an activation with an
+ * XFP-compressed weight matrix
+ *
+ *     y = x * W_hat^T,     W_hat = Codebook[Q_bulk] + W_outlier          (paper eq. 1)
+ *
+ * in one kernel launch that fuses the steps the paper lists at the start of
+ * section 5: depack the N-bit indices, gather codebook entries held on chip,
+ * add the sparse outlier term, multiply-accumulate.  Q_bulk is a dense b-bit
+ * index tensor; the codebook is either V2 (one fp16 codebook of 2^b entries
+ * per output channel) or V2a (a per-layer library of L codebooks plus one
+ * library id per group of 128 weights), paper sections 3.1, 3.2 and 3.4.
+ *
+ * Conventions common to every entry point
+ *  - Every data pointer (inside xfp_weights and x / y / expert_ids / outputs)
+ *    is a DEVICE pointer owned by the caller.  The xfp_weights struct itself
+ *    is HOST memory, read during the call and not retained.
+ *  - Calls are asynchronous on `hip_stream` (a hipStream_t; NULL = the default
+ *    stream).  The library never allocates, frees, copies or synchronises, so
+ *    every entry point may be recorded into a HIP graph.
+ *  - Outputs are overwritten, never accumulated into.
+ *  - Return value: XFP_OK or a negative xfp_status.  Nothing is launched when
+ *    an argument is rejected.  A failed launch returns XFP_ERR_HIP.
+ *  - Only what the host can see is validated (shapes, bit width, mode, NULLs,
+ *    alignment).  Contents of device buffers (expert ids in range, group ids
+ *    below L, CSR row pointers ascending and columns in [0, K)) are the
+ *    caller's contract; violating it is undefined behaviour.
+ *  - No global mutable state; calls from several host threads are safe.
+ *
+ * Data layout (all little-endian)
+ *  - indices: per matrix, N rows of K*bits/32 uint32 words, no row padding.
+ *    Field k of a row is bits [k*bits, (k+1)*bits) of the row's bit stream,
+ *    least significant bit first; the stream fills word 0 from bit 0 upward,
+ *    then word 1, ...  For bits = 2 and 4 this is the paper's table 2 (16 and
+ *    8 values per uint32, no reserve bits).  For bits = 3 the stream is dense
+ *    (3.0 bit per weight, fields cross word boundaries), which is NOT the
+ *    paper's 10-values-per-word form.
+ *  - group: 128 consecutive k of one output row (K % 128 == 0).
+ *  - outliers: CSR over the stacked E*N rows: int32 row_ptr [E*N + 1] holding
+ *    absolute offsets (row_ptr[0] == 0), int32 col [nnz] ascending within a
+ *    row with no duplicates, fp16 val [nnz].  The outlier value is ADDED to
+ *    the codebook value at that position (eq. 1 is a sum).
+ *  - x is fp16; y is fp16 or fp32; accumulation is fp32.
+ */
+#ifndef XFP_H
+#define XFP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    XFP_OK = 0,
+    XFP_ERR_NULL = -1,        /* a required pointer is NULL                         */
+    XFP_ERR_SHAPE = -2,       /* N, K, M, E <= 0, T < 0, K % group != 0, ld too small */
+    XFP_ERR_UNSUPPORTED = -3, /* bits, mode, L, group, dtype, flags, struct_size     */
+    XFP_ERR_ALIGN = -4,       /* a base pointer or a leading dimension is misaligned */
+    XFP_ERR_HIP = -5          /* the HIP runtime refused the launch                  */
+} xfp_status;
+
+typedef enum { XFP_MODE_V2 = 0, XFP_MODE_V2A = 1 } xfp_mode;
+typedef enum { XFP_F16 = 0, XFP_F32 = 1 } xfp_dtype;
+
+#define XFP_GROUP 128
+#define XFP_MAX_LIBRARY 256          /* V2a ids are one byte each */
+
+/* One bank of E matrices of identical shape and format (E = 1: a plain matrix). */
+typedef struct xfp_weights {
+    uint32_t struct_size;       /* sizeof(xfp_weights), checked                              */
+    uint32_t mode;              /* xfp_mode                                                  */
+    uint32_t bits;              /* 2, 3 or 4                                                 */
+    uint32_t group;             /* must be 128                                               */
+    uint32_t N, K;              /* output channels, input channels; K % 128 == 0             */
+    uint32_t L;                 /* V2a: library size, 1..256 (paper default 32); V2: 0       */
+    uint32_t E;                 /* matrices stacked in this bank                             */
+    uint32_t flags;             /* must be 0                                                 */
+    uint32_t reserved;          /* must be 0                                                 */
+    const uint32_t *indices;    /* [E][N][K*bits/32]                                         */
+    const uint16_t *codebooks;  /* fp16: V2 [E][N][1<<bits], V2a [E][L][1<<bits]             */
+    const uint8_t *group_ids;   /* V2a: [E][N][K/128], each < L; V2: NULL                    */
+    const int32_t *out_row_ptr; /* [E*N + 1]                                                 */
+    const int32_t *out_col;     /* [nnz] (may be NULL when nnz == 0)                         */
+    const uint16_t *out_val;    /* fp16 [nnz] (may be NULL when nnz == 0)                    */
+} xfp_weights;
+
+/*
+ * y[m][n] = sum_k x[m][k] * C[n][k] + sum_{j in CSR row n} val[j] * x[m][col[j]]
+ * for m in [0, M), n in [0, N)    (paper eq. 1 and section 5, steps 1-4).
+ *
+ * W      one matrix (W->E must be 1).
+ * x      fp16 [M][ldx], ldx >= K, ldx % 8 == 0, 16-byte aligned.
+ * y      [M][ldy] of y_dtype, ldy >= N, 16-byte aligned base.
+ * M      1 .. 65535.  M = 1 is the decode case; 2 <= M <= 16 takes a
+ *        matrix-core (MFMA) path that reads the weights once.
+ */
+int xfp_gemv(const xfp_weights *W, const void *x, int M, int64_t ldx,
+             void *y, int y_dtype, int64_t ldy, void *hip_stream);
+
+/*
+ * Expert-indexed grouped form for routed-expert layers: for each slot
+ * t in [0, T), y[t][:] = xfp_gemv of matrix expert_ids[t] of the bank applied
+ * to input row t (M = 1 per slot).  The paper applies the fused decode to
+ * routed-expert weights (sections 1 and 6.1) without describing the launch;
+ * this grouped call is this library's reading.  expert_ids is read on the
+ * device, so a router's output can be consumed without a host round trip.
+ *
+ * expert_ids     device int32 [T], each in [0, bank->E); duplicates allowed.
+ * x              fp16; slot t reads x + t * x_slot_stride (in elements).
+ *                x_slot_stride == 0 shares one input row between all slots,
+ *                otherwise it must be >= K and a multiple of 8.
+ * y              [T][ldy], ldy >= N.
+ * T == 0 is a no-op that returns XFP_OK.  T <= 65535.
+ */
+int xfp_gemv_moe(const xfp_weights *bank, const int32_t *expert_ids, int T,
+                 const void *x, int64_t x_slot_stride,
+                 void *y, int y_dtype, int64_t ldy, void *hip_stream);
+
+/*
+ * Parity hooks: the first two fused steps on their own (paper section 5,
+ * steps 1 and 2), so that they can be compared bit for bit.
+ * xfp_unpack_indices writes every index as one byte, idx_out [E*N][K].
+ * xfp_dequant_bulk writes the selected codebook entry's fp16 bit pattern,
+ * w_out [E*N][K]; the outlier term is not included.
+ */
+int xfp_unpack_indices(const xfp_weights *W, uint8_t *idx_out, void *hip_stream);
+int xfp_dequant_bulk(const xfp_weights *W, uint16_t *w_out, void *hip_stream);
+
+/*
+ * Measurement helpers (no paper counterpart): stream `bytes` (a multiple of
+ * 16, 16-byte aligned) once through the chip.  xfp_probe_read sums the words
+ * and writes one uint32 per workgroup to `sink` (at least 4096 uint32);
+ * xfp_probe_copy copies src to dst.  They calibrate achievable HBM bandwidth
+ * and the profiler's byte counters.
+ */
+int xfp_probe_read(const void *src, uint64_t bytes, uint32_t *sink, void *hip_stream);
+int xfp_probe_copy(const void *src, void *dst, uint64_t bytes, void *hip_stream);
+
+/* Text for a status code; never NULL.  For XFP_ERR_HIP the text of the last
+ * HIP error seen by the calling thread is appended. */
+const char *xfp_strerror(int status);
+
+/* (major << 16) | (minor << 8) | patch */
+int xfp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* XFP_H */

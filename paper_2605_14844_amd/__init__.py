@@ -1,0 +1,13 @@
+"""MI355X-native XFP fused decode (dequant-GEMV) library: Python binding.
+
+The arithmetic lives in libxfp.so (hand-written HIP for gfx950, C ABI declared
+in include/xfp.h).  This package only marshals arguments; PyTorch is used for
+device memory and streams.  There is no CPU fallback: if the library cannot
+be loaded, importing the binding's entry points raises.
+"""
+from .binding import (  # noqa: F401
+    XFP_F16, XFP_F32, XFP_MODE_V2, XFP_MODE_V2A, DeviceWeights, XfpError, library_path, load_library,
+    upload, xfp_dequant_bulk, xfp_gemv, xfp_gemv_moe, xfp_probe_copy, xfp_probe_read, xfp_strerror,
+    xfp_unpack_indices, xfp_version,
+)
+from .format import bytes_per_weight, load_xfp, save_xfp  # noqa: F401

@@ -1,0 +1,208 @@
+"""ctypes binding of libxfp.so with the same entry-point names as include/xfp.h.
+
+Argument marshalling only: tensors are passed as raw device pointers and the
+current torch stream as a hipStream_t.  Every computation runs in the HIP
+kernels behind the C ABI.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass, field
+from typing import Optional
+
+import numpy as np
+import torch
+
+XFP_MODE_V2, XFP_MODE_V2A = 0, 1
+XFP_F16, XFP_F32 = 0, 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libxfp.so")
+_lib = None
+
+
+class XfpError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"xfp status {status}: {text}")
+        self.status = status
+
+
+class xfp_weights(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", ctypes.c_uint32), ("mode", ctypes.c_uint32), ("bits", ctypes.c_uint32),
+        ("group", ctypes.c_uint32), ("N", ctypes.c_uint32), ("K", ctypes.c_uint32),
+        ("L", ctypes.c_uint32), ("E", ctypes.c_uint32), ("flags", ctypes.c_uint32),
+        ("reserved", ctypes.c_uint32),
+        ("indices", ctypes.c_void_p), ("codebooks", ctypes.c_void_p), ("group_ids", ctypes.c_void_p),
+        ("out_row_ptr", ctypes.c_void_p), ("out_col", ctypes.c_void_p), ("out_val", ctypes.c_void_p),
+    ]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libxfp.so; build it first only when no built library exists."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from . import build as _build
+        _build.build()
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32, i64, u64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_uint64
+    wp = ctypes.POINTER(xfp_weights)
+    lib.xfp_gemv.argtypes = [wp, vp, i32, i64, vp, i32, i64, vp]
+    lib.xfp_gemv_moe.argtypes = [wp, vp, i32, vp, i64, vp, i32, i64, vp]
+    lib.xfp_unpack_indices.argtypes = [wp, vp, vp]
+    lib.xfp_dequant_bulk.argtypes = [wp, vp, vp]
+    lib.xfp_probe_read.argtypes = [vp, u64, vp, vp]
+    lib.xfp_probe_copy.argtypes = [vp, vp, u64, vp]
+    lib.xfp_strerror.argtypes = [i32]
+    lib.xfp_strerror.restype = ctypes.c_char_p
+    for name in ("xfp_gemv", "xfp_gemv_moe", "xfp_unpack_indices", "xfp_dequant_bulk",
+                 "xfp_probe_read", "xfp_probe_copy", "xfp_version"):
+        getattr(lib, name).restype = i32
+    _lib = lib
+    return lib
+
+
+def xfp_strerror(status: int) -> str:
+    return load_library().xfp_strerror(int(status)).decode()
+
+
+def xfp_version() -> int:
+    return int(load_library().xfp_version())
+
+
+def _check(status: int):
+    if status != 0:
+        raise XfpError(status, xfp_strerror(status))
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, torch.cuda.Stream):
+        return stream.cuda_stream or None
+    return int(stream) or None
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None or t.numel() == 0:
+        return None
+    return t.data_ptr()
+
+
+@dataclass
+class DeviceWeights:
+    """Device-resident bank plus the host descriptor the C ABI takes."""
+    desc: xfp_weights
+    tensors: dict = field(default_factory=dict)
+
+    @property
+    def N(self): return int(self.desc.N)
+    @property
+    def K(self): return int(self.desc.K)
+    @property
+    def E(self): return int(self.desc.E)
+    @property
+    def bits(self): return int(self.desc.bits)
+    @property
+    def mode(self): return int(self.desc.mode)
+
+
+def make_descriptor(mode, bits, N, K, L, E, indices, codebooks, group_ids, out_row_ptr, out_col,
+                    out_val, group=128) -> DeviceWeights:
+    """Wrap device tensors (already laid out as include/xfp.h states) in a descriptor."""
+    d = xfp_weights()
+    d.struct_size = ctypes.sizeof(xfp_weights)
+    d.mode, d.bits, d.group, d.N, d.K, d.L, d.E = mode, bits, group, N, K, L, E
+    d.flags = d.reserved = 0
+    d.indices, d.codebooks, d.group_ids = _ptr(indices), _ptr(codebooks), _ptr(group_ids)
+    d.out_row_ptr, d.out_col, d.out_val = _ptr(out_row_ptr), _ptr(out_col), _ptr(out_val)
+    return DeviceWeights(d, dict(indices=indices, codebooks=codebooks, group_ids=group_ids,
+                                 out_row_ptr=out_row_ptr, out_col=out_col, out_val=out_val))
+
+
+def _to_dev(a: Optional[np.ndarray], device, view=None):
+    if a is None:
+        return None
+    a = np.ascontiguousarray(a)
+    if view is not None:
+        a = a.view(view)
+    return torch.from_numpy(a).to(device)
+
+
+def upload(W, device="cuda") -> DeviceWeights:
+    """Copy host arrays (xfp_inputs.XfpHostWeights or format.load_xfp output) to the GPU."""
+    return make_descriptor(
+        W.mode, W.bits, W.N, W.K, W.L, W.E,
+        _to_dev(W.indices, device, np.int32), _to_dev(W.codebooks, device, np.int16),
+        _to_dev(W.group_ids, device), _to_dev(W.out_row_ptr, device),
+        _to_dev(W.out_col, device), _to_dev(W.out_val, device, np.int16), group=W.group)
+
+
+def _y_code(dtype) -> int:
+    if dtype == torch.float16:
+        return XFP_F16
+    if dtype == torch.float32:
+        return XFP_F32
+    raise XfpError(-3, "y dtype must be torch.float16 or torch.float32")
+
+
+def xfp_gemv(W: DeviceWeights, x: torch.Tensor, y: Optional[torch.Tensor] = None,
+             y_dtype=torch.float16, stream=None) -> torch.Tensor:
+    """y[M, N] = x[M, K] * W_hat^T.  x: fp16 device tensor [M, K] or [K], row stride = ldx."""
+    x2 = x if x.dim() == 2 else x.unsqueeze(0)
+    M = x2.shape[0]
+    if y is None:
+        y = torch.empty((M, W.N), dtype=y_dtype, device=x.device)
+    y2 = y if y.dim() == 2 else y.unsqueeze(0)
+    ldx = x2.stride(0) if M > 1 else max(x2.shape[1], 1)
+    ldy = y2.stride(0) if M > 1 else max(y2.shape[1], 1)
+    _check(load_library().xfp_gemv(ctypes.byref(W.desc), _ptr(x2), M, ldx, _ptr(y2),
+                                   _y_code(y2.dtype), ldy, _stream(stream)))
+    return y
+
+
+def xfp_gemv_moe(bank: DeviceWeights, expert_ids: torch.Tensor, x: torch.Tensor,
+                 y: Optional[torch.Tensor] = None, y_dtype=torch.float16, stream=None) -> torch.Tensor:
+    """y[t, :] = matrix expert_ids[t] applied to x[t] (x [T, K]) or to the shared x (x [K] or [1, K])."""
+    T = int(expert_ids.numel())
+    shared = x.dim() == 1 or x.shape[0] == 1 and T != 1
+    x_slot_stride = 0 if shared else x.stride(0)
+    if y is None:
+        y = torch.empty((T, bank.N), dtype=y_dtype, device=x.device)
+    ldy = y.stride(0) if y.dim() == 2 and T > 1 else bank.N
+    _check(load_library().xfp_gemv_moe(ctypes.byref(bank.desc), _ptr(expert_ids), T, _ptr(x),
+                                       x_slot_stride, _ptr(y) if T else y.data_ptr(),
+                                       _y_code(y.dtype), ldy, _stream(stream)))
+    return y
+
+
+def xfp_unpack_indices(W: DeviceWeights, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    if out is None:
+        out = torch.empty((W.E * W.N, W.K), dtype=torch.uint8, device="cuda")
+    _check(load_library().xfp_unpack_indices(ctypes.byref(W.desc), _ptr(out), _stream(stream)))
+    return out
+
+
+def xfp_dequant_bulk(W: DeviceWeights, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """fp16 bit patterns of Codebook[Q], returned as an int16 tensor [E*N, K]."""
+    if out is None:
+        out = torch.empty((W.E * W.N, W.K), dtype=torch.int16, device="cuda")
+    _check(load_library().xfp_dequant_bulk(ctypes.byref(W.desc), _ptr(out), _stream(stream)))
+    return out
+
+
+def xfp_probe_read(src: torch.Tensor, sink: torch.Tensor, nbytes: Optional[int] = None, stream=None):
+    nbytes = src.numel() * src.element_size() if nbytes is None else nbytes
+    _check(load_library().xfp_probe_read(_ptr(src), nbytes, _ptr(sink), _stream(stream)))
+
+
+def xfp_probe_copy(src: torch.Tensor, dst: torch.Tensor, nbytes: Optional[int] = None, stream=None):
+    nbytes = src.numel() * src.element_size() if nbytes is None else nbytes
+    _check(load_library().xfp_probe_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream)))

@@ -1,0 +1,182 @@
+// Host side of the C ABI: argument validation, kernel selection, launch.
+// Nothing here allocates, copies or synchronises.
+#include "../../include/xfp.h"
+#include "xfp_internal.h"
+
+#include <cstdio>
+#include <cstring>
+
+namespace {
+
+thread_local hipError_t g_last_hip = hipSuccess;
+thread_local char g_msg[256];
+
+inline bool misaligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+
+int check_weights(const xfp_weights *W)
+{
+    if (!W) return XFP_ERR_NULL;
+    if (W->struct_size != sizeof(xfp_weights)) return XFP_ERR_UNSUPPORTED;
+    if (W->mode != XFP_MODE_V2 && W->mode != XFP_MODE_V2A) return XFP_ERR_UNSUPPORTED;
+    if (W->bits < 2 || W->bits > 4) return XFP_ERR_UNSUPPORTED;
+    if (W->group != XFP_GROUP || W->flags != 0 || W->reserved != 0) return XFP_ERR_UNSUPPORTED;
+    if (W->N == 0 || W->K == 0 || W->E == 0) return XFP_ERR_SHAPE;
+    if (W->K % XFP_GROUP != 0) return XFP_ERR_SHAPE;
+    if ((uint64_t)W->E * W->N > 0x7fffffffull) return XFP_ERR_SHAPE;
+    if (W->mode == XFP_MODE_V2A) {
+        if (W->L == 0 || W->L > XFP_MAX_LIBRARY) return XFP_ERR_UNSUPPORTED;
+        if (!W->group_ids) return XFP_ERR_NULL;
+    } else if (W->L != 0) {
+        return XFP_ERR_UNSUPPORTED;
+    }
+    if (!W->indices || !W->codebooks || !W->out_row_ptr) return XFP_ERR_NULL;
+    if (misaligned(W->indices, 16) || misaligned(W->codebooks, 16) || misaligned(W->out_row_ptr, 4) ||
+        misaligned(W->out_col, 4) || misaligned(W->out_val, 2))
+        return XFP_ERR_ALIGN;
+    return XFP_OK;
+}
+
+xfp::DecodeArgs base_args(const xfp_weights *W)
+{
+    xfp::DecodeArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.idx = W->indices;
+    a.cb = W->codebooks;
+    a.gid = W->group_ids;
+    a.rp = W->out_row_ptr;
+    a.col = W->out_col;
+    a.val = W->out_val;
+    a.N = W->N;
+    a.K = W->K;
+    a.L = W->L;
+    return a;
+}
+
+int finish(hipError_t err)
+{
+    if (err == hipSuccess) return XFP_OK;
+    g_last_hip = err;
+    return XFP_ERR_HIP;
+}
+
+int check_io(const xfp_weights *W, const void *x, const void *y, int y_dtype, int64_t ldy)
+{
+    if (!x || !y) return XFP_ERR_NULL;
+    if (y_dtype != XFP_F16 && y_dtype != XFP_F32) return XFP_ERR_UNSUPPORTED;
+    if (ldy < (int64_t)W->N) return XFP_ERR_SHAPE;
+    if (misaligned(x, 16) || misaligned(y, 16)) return XFP_ERR_ALIGN;
+    return XFP_OK;
+}
+
+// Rows one workgroup of the general kernel walks: enough workgroups to cover
+// the chip several times over, few enough that staging x is amortised.
+uint32_t rows_per_block(uint32_t N, int slots)
+{
+    uint64_t total = (uint64_t)N * slots;
+    uint32_t r = 4;
+    while (r < 64 && total / r > 4096) r *= 2;
+    return r;
+}
+
+int decode(const xfp_weights *W, const int32_t *eids, int slots, const void *x, int64_t x_stride,
+           void *y, int y_dtype, int64_t ldy, hipStream_t s)
+{
+    xfp::DecodeArgs a = base_args(W);
+    a.x = static_cast<const uint16_t *>(x);
+    a.y = y;
+    a.eids = eids;
+    a.x_stride = x_stride;
+    a.y_stride = ldy;
+    a.rows_per_block = rows_per_block(W->N, slots);
+    return finish(xfp::launch_decode_rows((int)W->bits, (int)W->mode, y_dtype == XFP_F32, a, slots, s));
+}
+
+}  // namespace
+
+extern "C" {
+
+int xfp_gemv(const xfp_weights *W, const void *x, int M, int64_t ldx, void *y, int y_dtype,
+             int64_t ldy, void *hip_stream)
+{
+    int rc = check_weights(W);
+    if (rc) return rc;
+    if (W->E != 1) return XFP_ERR_SHAPE;
+    if (M <= 0 || M > 65535) return XFP_ERR_SHAPE;
+    rc = check_io(W, x, y, y_dtype, ldy);
+    if (rc) return rc;
+    if (ldx < (int64_t)W->K) return XFP_ERR_SHAPE;
+    if (ldx % 8 != 0) return XFP_ERR_ALIGN;
+    return decode(W, nullptr, M, x, ldx, y, y_dtype, ldy, static_cast<hipStream_t>(hip_stream));
+}
+
+int xfp_gemv_moe(const xfp_weights *bank, const int32_t *expert_ids, int T, const void *x,
+                 int64_t x_slot_stride, void *y, int y_dtype, int64_t ldy, void *hip_stream)
+{
+    int rc = check_weights(bank);
+    if (rc) return rc;
+    if (T < 0 || T > 65535) return XFP_ERR_SHAPE;
+    if (T == 0) return XFP_OK;
+    if (!expert_ids) return XFP_ERR_NULL;
+    rc = check_io(bank, x, y, y_dtype, ldy);
+    if (rc) return rc;
+    if (x_slot_stride != 0 && x_slot_stride < (int64_t)bank->K) return XFP_ERR_SHAPE;
+    if (x_slot_stride % 8 != 0 || misaligned(expert_ids, 4)) return XFP_ERR_ALIGN;
+    return decode(bank, expert_ids, T, x, x_slot_stride, y, y_dtype, ldy,
+                  static_cast<hipStream_t>(hip_stream));
+}
+
+int xfp_unpack_indices(const xfp_weights *W, uint8_t *idx_out, void *hip_stream)
+{
+    int rc = check_weights(W);
+    if (rc) return rc;
+    if (!idx_out) return XFP_ERR_NULL;
+    if (misaligned(idx_out, 16)) return XFP_ERR_ALIGN;
+    return finish(xfp::launch_unpack((int)W->bits, W->indices, (uint64_t)W->E * W->N, W->K, idx_out,
+                                     static_cast<hipStream_t>(hip_stream)));
+}
+
+int xfp_dequant_bulk(const xfp_weights *W, uint16_t *w_out, void *hip_stream)
+{
+    int rc = check_weights(W);
+    if (rc) return rc;
+    if (!w_out) return XFP_ERR_NULL;
+    if (misaligned(w_out, 16)) return XFP_ERR_ALIGN;
+    xfp::DecodeArgs a = base_args(W);
+    return finish(xfp::launch_dequant((int)W->bits, (int)W->mode, a, W->E, w_out,
+                                      static_cast<hipStream_t>(hip_stream)));
+}
+
+int xfp_probe_read(const void *src, uint64_t bytes, uint32_t *sink, void *hip_stream)
+{
+    if (!src || !sink) return XFP_ERR_NULL;
+    if (bytes % 16 != 0) return XFP_ERR_SHAPE;
+    if (misaligned(src, 16) || misaligned(sink, 4)) return XFP_ERR_ALIGN;
+    return finish(xfp::launch_probe_read(src, bytes, sink, static_cast<hipStream_t>(hip_stream)));
+}
+
+int xfp_probe_copy(const void *src, void *dst, uint64_t bytes, void *hip_stream)
+{
+    if (!src || !dst) return XFP_ERR_NULL;
+    if (bytes % 16 != 0) return XFP_ERR_SHAPE;
+    if (misaligned(src, 16) || misaligned(dst, 16)) return XFP_ERR_ALIGN;
+    return finish(xfp::launch_probe_copy(src, dst, bytes, static_cast<hipStream_t>(hip_stream)));
+}
+
+const char *xfp_strerror(int status)
+{
+    switch (status) {
+    case XFP_OK: return "ok";
+    case XFP_ERR_NULL: return "a required pointer is NULL";
+    case XFP_ERR_SHAPE: return "bad shape (sizes must be positive, K a multiple of 128, leading dimensions large enough)";
+    case XFP_ERR_UNSUPPORTED: return "unsupported format (bits must be 2..4, mode V2/V2a, group 128, flags 0, dtype fp16/fp32)";
+    case XFP_ERR_ALIGN: return "a pointer or leading dimension is misaligned";
+    case XFP_ERR_HIP:
+        std::snprintf(g_msg, sizeof(g_msg), "HIP launch failed: %s", hipGetErrorString(g_last_hip));
+        return g_msg;
+    default: return "unknown status";
+    }
+}
+
+int xfp_version(void) { return (0 << 16) | (1 << 8) | 0; }
+
+}  // extern "C"

@@ -1,0 +1,142 @@
+// Parity hooks (depack and codebook gather on their own) and the streaming
+// probes used to calibrate bandwidth figures and profiler byte counters.
+#include "xfp_device.h"
+
+namespace xfp {
+
+template <int BITS, int F>
+__device__ __forceinline__ void emit_fields(const LaneWords<BITS> &lw, uint8_t *q)
+{
+    if constexpr (F < 32) {
+        q[F] = (uint8_t)field<BITS, F>(lw);
+        emit_fields<BITS, F + 1>(lw, q);
+    }
+}
+
+// One thread per 32-weight unit of the flat [rows][K] index stream.
+template <int BITS>
+__global__ __launch_bounds__(256) void unpack_kernel(const uint32_t *idx, uint64_t units, uint8_t *out)
+{
+    uint64_t u = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (u >= units) return;
+    LaneWords<BITS> lw = load_lane_words<BITS>(idx + u * BITS);
+    __align__(16) uint8_t q[32];
+    emit_fields<BITS, 0>(lw, q);
+    uint4 *o = reinterpret_cast<uint4 *>(out + u * 32);
+    o[0] = *reinterpret_cast<uint4 *>(q);
+    o[1] = *reinterpret_cast<uint4 *>(q + 16);
+}
+
+template <int BITS, int MODE>
+__global__ __launch_bounds__(256) void dequant_kernel(DecodeArgs a, uint64_t units, uint16_t *out)
+{
+    constexpr int ENT = 1 << BITS;
+    uint64_t u = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (u >= units) return;
+    const uint32_t upr = a.K / kLaneWeights;             // units per row
+    uint64_t grow = u / upr;                             // row in the stacked [E*N] space
+    uint32_t ur = (uint32_t)(u % upr);
+    LaneWords<BITS> lw = load_lane_words<BITS>(a.idx + u * BITS);
+    const uint16_t *tbl;
+    if constexpr (MODE == 0) {
+        tbl = a.cb + grow * ENT;
+    } else {
+        uint64_t e = grow / a.N;
+        uint32_t g = a.gid[grow * (a.K / kGroup) + ur / (kGroup / kLaneWeights)];
+        tbl = a.cb + (e * a.L + g) * ENT;
+    }
+    __align__(16) uint8_t q[32];
+    emit_fields<BITS, 0>(lw, q);
+    __align__(16) uint16_t w[32];
+#pragma unroll
+    for (int i = 0; i < 32; ++i) w[i] = tbl[q[i]];
+    uint4 *o = reinterpret_cast<uint4 *>(out + u * 32);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o[i] = *reinterpret_cast<uint4 *>(w + 8 * i);
+}
+
+hipError_t launch_unpack(int bits, const uint32_t *idx, uint64_t rows, uint32_t K, uint8_t *out,
+                         hipStream_t s)
+{
+    uint64_t units = rows * (K / kLaneWeights);
+    if (units == 0) return hipSuccess;
+    dim3 grid((unsigned)((units + 255) / 256));
+    switch (bits) {
+    case 2: hipLaunchKernelGGL(unpack_kernel<2>, grid, dim3(256), 0, s, idx, units, out); break;
+    case 3: hipLaunchKernelGGL(unpack_kernel<3>, grid, dim3(256), 0, s, idx, units, out); break;
+    default: hipLaunchKernelGGL(unpack_kernel<4>, grid, dim3(256), 0, s, idx, units, out); break;
+    }
+    return hipGetLastError();
+}
+
+template <int BITS>
+static void launch_dequant_b(int mode, const DecodeArgs &a, uint64_t units, uint16_t *out, dim3 grid,
+                             hipStream_t s)
+{
+    if (mode == 0)
+        hipLaunchKernelGGL((dequant_kernel<BITS, 0>), grid, dim3(256), 0, s, a, units, out);
+    else
+        hipLaunchKernelGGL((dequant_kernel<BITS, 1>), grid, dim3(256), 0, s, a, units, out);
+}
+
+hipError_t launch_dequant(int bits, int mode, const DecodeArgs &a, uint32_t E, uint16_t *out,
+                          hipStream_t s)
+{
+    uint64_t units = (uint64_t)E * a.N * (a.K / kLaneWeights);
+    if (units == 0) return hipSuccess;
+    dim3 grid((unsigned)((units + 255) / 256));
+    switch (bits) {
+    case 2: launch_dequant_b<2>(mode, a, units, out, grid, s); break;
+    case 3: launch_dequant_b<3>(mode, a, units, out, grid, s); break;
+    default: launch_dequant_b<4>(mode, a, units, out, grid, s); break;
+    }
+    return hipGetLastError();
+}
+
+// ---- streaming probes -------------------------------------------------------
+constexpr int kProbeBlocks = 4096;
+
+__global__ __launch_bounds__(256) void probe_read_kernel(const uint4 *src, uint64_t n16, uint32_t *sink)
+{
+    uint32_t acc = 0;
+    for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (uint64_t)gridDim.x * 256) {
+        uint4 v = src[i];
+        acc += v.x ^ v.y ^ v.z ^ v.w;
+    }
+    __shared__ uint32_t part[256];
+    part[threadIdx.x] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t t = 0;
+        for (int i = 0; i < 256; ++i) t ^= part[i];
+        sink[blockIdx.x] = t;                      // keeps the loads alive
+    }
+}
+
+__global__ __launch_bounds__(256) void probe_copy_kernel(const uint4 *src, uint4 *dst, uint64_t n16)
+{
+    for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (uint64_t)gridDim.x * 256)
+        dst[i] = src[i];
+}
+
+hipError_t launch_probe_read(const void *src, uint64_t bytes, uint32_t *sink, hipStream_t s)
+{
+    uint64_t n16 = bytes / 16;
+    if (n16 == 0) return hipSuccess;
+    unsigned blocks = (unsigned)((n16 + 255) / 256 < kProbeBlocks ? (n16 + 255) / 256 : kProbeBlocks);
+    hipLaunchKernelGGL(probe_read_kernel, dim3(blocks), dim3(256), 0, s,
+                       static_cast<const uint4 *>(src), n16, sink);
+    return hipGetLastError();
+}
+
+hipError_t launch_probe_copy(const void *src, void *dst, uint64_t bytes, hipStream_t s)
+{
+    uint64_t n16 = bytes / 16;
+    if (n16 == 0) return hipSuccess;
+    unsigned blocks = (unsigned)((n16 + 255) / 256 < kProbeBlocks ? (n16 + 255) / 256 : kProbeBlocks);
+    hipLaunchKernelGGL(probe_copy_kernel, dim3(blocks), dim3(256), 0, s,
+                       static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), n16);
+    return hipGetLastError();
+}
+
+}  // namespace xfp

@@ -1,0 +1,114 @@
+// Device-side building blocks for the gfx950 decode kernels: index-stream
+// loads, b-bit field extraction, fp16 pair math and wave64 reductions.
+#pragma once
+#include "xfp_internal.h"
+
+namespace xfp {
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+
+// One lane's share of the index stream: 32 consecutive b-bit fields = BITS dwords.
+template <int BITS>
+struct LaneWords {
+    uint32_t w[BITS];
+};
+
+template <int BITS>
+__device__ __forceinline__ LaneWords<BITS> load_lane_words(const uint32_t *p)
+{
+    LaneWords<BITS> r;
+    if constexpr (BITS == 4) {
+        uint4 v = *reinterpret_cast<const uint4 *>(p);
+        r.w[0] = v.x; r.w[1] = v.y; r.w[2] = v.z; r.w[3] = v.w;
+    } else if constexpr (BITS == 2) {
+        uint2 v = *reinterpret_cast<const uint2 *>(p);
+        r.w[0] = v.x; r.w[1] = v.y;
+    } else {
+#pragma unroll
+        for (int i = 0; i < BITS; ++i) r.w[i] = p[i];
+    }
+    return r;
+}
+
+// Field F (0..31) of a lane's words: bits [F*BITS, F*BITS + BITS) of the
+// little-endian stream.  Fields that cross a dword boundary (3-bit only) are
+// taken from the 64-bit window with a funnel shift.
+template <int BITS, int F>
+__device__ __forceinline__ uint32_t field(const LaneWords<BITS> &lw)
+{
+    constexpr int bit = F * BITS;
+    constexpr int word = bit / 32;
+    constexpr int sh = bit % 32;
+    constexpr uint32_t mask = (1u << BITS) - 1u;
+    if constexpr (sh + BITS <= 32) {
+        return (lw.w[word] >> sh) & mask;
+    } else {
+        return __builtin_amdgcn_alignbit(lw.w[word + 1], lw.w[word], sh) & mask;
+    }
+}
+
+__device__ __forceinline__ float dot2(half2_t a, half2_t b, float acc)
+{
+    return __builtin_amdgcn_fdot2(a, b, acc, false);   // v_dot2_f32_f16: fp32 accumulate
+}
+
+__device__ __forceinline__ half2_t as_half2(uint32_t u) { return __builtin_bit_cast(half2_t, u); }
+__device__ __forceinline__ float half_bits_to_float(uint16_t h)
+{
+    return (float)__builtin_bit_cast(_Float16, h);
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v)
+{
+    int t = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true);
+    return v + __builtin_bit_cast(float, t);
+}
+
+// Sum over the 64 lanes in a fixed order (deterministic); every lane gets it.
+__device__ __forceinline__ float wave_sum(float v)
+{
+    v = dpp_add<0xB1>(v);    // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E>(v);    // quad_perm [2,3,0,1]
+    v = dpp_add<0x141>(v);   // row_half_mirror: other quad of the 8
+    v = dpp_add<0x140>(v);   // row_mirror: other half of the 16
+    int b = __builtin_bit_cast(int, v);
+    float s0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0));
+    float s1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16));
+    float s2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32));
+    float s3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48));
+    return (s0 + s1) + (s2 + s3);
+}
+
+// Sum over aligned segments of SEG lanes (SEG = 4, 8, 16, 32, 64); every lane
+// of a segment gets its segment's sum.
+template <int SEG>
+__device__ __forceinline__ float segment_sum(float v)
+{
+    if constexpr (SEG == 64) return wave_sum(v);
+    v = dpp_add<0xB1>(v);
+    v = dpp_add<0x4E>(v);
+    if constexpr (SEG >= 8) v = dpp_add<0x141>(v);
+    if constexpr (SEG >= 16) v = dpp_add<0x140>(v);
+    if constexpr (SEG == 32) {
+        int b = __builtin_bit_cast(int, v);
+        float s0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0));
+        float s1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16));
+        float s2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32));
+        float s3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48));
+        v = (threadIdx.x & 32) ? (s2 + s3) : (s0 + s1);
+    }
+    return v;
+}
+
+template <bool YF32>
+__device__ __forceinline__ void store_y(void *y, int64_t i, float v)
+{
+    if constexpr (YF32) {
+        static_cast<float *>(y)[i] = v;
+    } else {
+        static_cast<_Float16 *>(y)[i] = (_Float16)v;   // round to nearest even
+    }
+}
+
+}  // namespace xfp

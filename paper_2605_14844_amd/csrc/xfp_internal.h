@@ -1,0 +1,40 @@
+// Internal declarations shared by the host dispatcher and the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace xfp {
+
+constexpr int kGroup = 128;
+constexpr int kWave = 64;
+constexpr int kLaneWeights = 32;   // weights one lane decodes per index load (all bit widths)
+
+// Everything a decode kernel needs, passed by value.  gridDim.y enumerates
+// "slots": tokens of a batched call (eids == nullptr) or MoE slots.
+struct DecodeArgs {
+    const uint32_t *idx;   // [E][N][K*bits/32]
+    const uint16_t *cb;    // V2 [E][N][2^b]   V2a [E][L][2^b]
+    const uint8_t *gid;    // V2a [E][N][K/128]
+    const int32_t *rp;     // [E*N+1]
+    const int32_t *col;
+    const uint16_t *val;
+    const uint16_t *x;     // slot s reads x + s * x_stride
+    void *y;               // slot s writes y + s * y_stride (elements of the y dtype)
+    const int32_t *eids;   // device [slots] or nullptr (matrix 0 for every slot)
+    int64_t x_stride;
+    int64_t y_stride;
+    uint32_t N, K, L;
+    uint32_t rows_per_block;
+};
+
+// Launchers, one per kernel family (defined in the .hip files).
+hipError_t launch_decode_rows(int bits, int mode, bool y_f32, const DecodeArgs &a, int slots,
+                              hipStream_t s);
+hipError_t launch_unpack(int bits, const uint32_t *idx, uint64_t rows, uint32_t K, uint8_t *out,
+                         hipStream_t s);
+hipError_t launch_dequant(int bits, int mode, const DecodeArgs &a, uint32_t E, uint16_t *out,
+                          hipStream_t s);
+hipError_t launch_probe_read(const void *src, uint64_t bytes, uint32_t *sink, hipStream_t s);
+hipError_t launch_probe_copy(const void *src, void *dst, uint64_t bytes, hipStream_t s);
+
+}  // namespace xfp

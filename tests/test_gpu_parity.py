@@ -1,0 +1,189 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle.
+
+Bars: bit-exact for unpacked indices and dequantized fp16 patterns; for y,
+max gated relative error <= 1e-3 with fp16 output (the stated bar: fp32
+accumulation against the fp64 oracle) and <= 1e-4 with fp32 output (fp32
+rounding of K <= 8192 terms leaves about 1e-6; 1e-4 is a safe margin that a
+dropped bulk term, about 1e-2 of rms(y), still fails by two orders).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2605_14844_amd as xfp
+import xfp_inputs as xi
+from helpers import gated_rel_err
+
+pytestmark = pytest.mark.gpu
+V2, V2A = xi.MODE_V2, xi.MODE_V2A
+TOL_F16, TOL_F32 = 1e-3, 1e-4
+
+
+def dev_x(x_bits):
+    return torch.from_numpy(np.ascontiguousarray(x_bits).view(np.int16)).cuda().view(torch.float16)
+
+
+def host(y):
+    torch.cuda.synchronize()
+    return y.float().cpu().numpy().astype(np.float64)
+
+
+def check_gemv(W, x_bits, tol16=TOL_F16, tol32=TOL_F32):
+    dW = xfp.upload(W)
+    xd = dev_x(x_bits)
+    ref = oracle.gemv_weights(W, x_bits)
+    e32 = gated_rel_err(host(xfp.xfp_gemv(dW, xd, y_dtype=torch.float32)), ref)
+    e16 = gated_rel_err(host(xfp.xfp_gemv(dW, xd, y_dtype=torch.float16)), ref)
+    print(f"  N={W.N} K={W.K} b={W.bits} mode={W.mode} M={xd.shape[0]}: err f32 {e32:.2e} f16 {e16:.2e}",
+          flush=True)
+    assert e32 <= tol32 and e16 <= tol16
+    return dW, xd, ref
+
+
+# ------------------------------------------------------------------ depack / gather, bit-exact
+@pytest.mark.parametrize("mode,bits,N,K,E", [
+    (V2, 2, 37, 384, 1), (V2, 3, 70, 1024, 1), (V2, 4, 129, 2048, 1), (V2A, 3, 33, 4096, 1),
+    (V2A, 4, 64, 512, 1), (V2A, 2, 19, 128, 1), (V2, 3, 16, 256, 5), (V2A, 4, 12, 384, 3)])
+def test_unpack_and_dequant_bit_exact(mode, bits, N, K, E):
+    W = xi.random_weights(mode, bits, N, K, E=E, density=0.002, seed=bits * 1000 + N)
+    if mode == V2:   # include subnormal, zero, negative-zero and extreme fp16 patterns
+        W.codebooks[0, 0, :4] = np.array([0x0001, 0x8000, 0x83FF, 0x7BFF], dtype=np.uint16)
+    dW = xfp.upload(W)
+    q = xfp.xfp_unpack_indices(dW).cpu().numpy()
+    assert np.array_equal(q, oracle.unpack(W.indices, K, bits).reshape(E * N, K))
+    w = xfp.xfp_dequant_bulk(dW).cpu().numpy().view(np.uint16)
+    for e in range(E):
+        ref, _ = oracle.dequant_bulk(mode, bits, N, K, W.indices[e], W.codebooks[e],
+                                     None if W.group_ids is None else W.group_ids[e], want_double=False)
+        assert np.array_equal(w[e * N:(e + 1) * N], ref)
+
+
+# ------------------------------------------------------------------ y, M = 1
+@pytest.mark.parametrize("mode,bits,N,K", [
+    (V2, 4, 512, 1024), (V2, 4, 37, 128), (V2, 4, 300, 4096), (V2, 4, 131, 8192), (V2, 4, 65, 5120),
+    (V2, 4, 64, 2048), (V2, 4, 50, 16384), (V2, 4, 9, 20480),
+    (V2, 3, 257, 4096), (V2, 3, 100, 1024), (V2, 3, 40, 384), (V2, 3, 33, 2048), (V2, 3, 21, 7168),
+    (V2, 2, 64, 1024), (V2, 2, 31, 4096), (V2, 2, 8, 256),
+    (V2A, 3, 200, 4096), (V2A, 3, 31, 640), (V2A, 4, 130, 2048), (V2A, 2, 66, 1024), (V2A, 4, 17, 8192)])
+def test_gemv_m1_matches_oracle(mode, bits, N, K):
+    W = xi.random_weights(mode, bits, N, K, density=0.003, seed=N + K + bits)
+    x = xi.activations(np.random.default_rng(N), 1, K)
+    check_gemv(W, x)
+
+
+def test_workload_1_full():
+    W = xi.config_weights(1)
+    check_gemv(W, xi.config_x(1, 1, W.K))
+
+
+def test_workload_2_student_t_reduced_rows():
+    W = xi.config_weights(2, N=1024)
+    check_gemv(W, xi.config_x(2, 1, W.K))
+
+
+def test_workload_3_v2a_reduced_rows():
+    W = xi.config_weights(3, N=1024)
+    check_gemv(W, xi.config_x(3, 1, W.K))
+
+
+def test_results_are_run_to_run_deterministic():
+    W = xi.random_weights(V2, 4, 256, 4096, density=0.003, seed=77)
+    dW, xd = xfp.upload(W), dev_x(xi.activations(np.random.default_rng(1), 1, 4096))
+    a = xfp.xfp_gemv(dW, xd, y_dtype=torch.float32).clone()
+    for _ in range(3):
+        assert torch.equal(a, xfp.xfp_gemv(dW, xd, y_dtype=torch.float32))
+
+
+# ------------------------------------------------------------------ edge cases
+def test_no_outliers_with_null_csr_arrays():
+    W = xi.random_weights(V2, 4, 64, 512, density=0.0, seed=5)
+    assert W.nnz == 0
+    check_gemv(W, xi.activations(np.random.default_rng(2), 1, 512))
+
+
+def test_one_row_holds_every_outlier_and_single_row_matrix():
+    K = 1024
+    W = xi.random_weights(V2, 3, 8, K, density=0.0, seed=6)
+    W.out_row_ptr = np.array([0, 0, 0, K, K, K, K, K, K], dtype=np.int32)
+    W.out_col = np.arange(K, dtype=np.int32)
+    W.out_val = xi.activations(np.random.default_rng(3), 1, K).ravel()
+    check_gemv(W, xi.activations(np.random.default_rng(4), 1, K))
+    W1 = xi.random_weights(V2A, 4, 1, 256, density=0.05, seed=7)
+    check_gemv(W1, xi.activations(np.random.default_rng(5), 1, 256))
+
+
+def test_zero_codebooks_isolate_outliers_and_ones_give_row_sums():
+    W = xi.random_weights(V2, 4, 96, 2048, density=0.004, seed=8)
+    W.codebooks[:] = 0
+    check_gemv(W, xi.activations(np.random.default_rng(6), 1, 2048))
+    W.codebooks[:] = np.float16(1.0).view(np.uint16)
+    W.out_row_ptr[:] = 0
+    W.out_col, W.out_val = W.out_col[:0], W.out_val[:0]
+    check_gemv(W, xi.activations(np.random.default_rng(7), 1, 2048))
+
+
+def test_strided_x_and_y():
+    W = xi.random_weights(V2, 4, 100, 1024, density=0.003, seed=9)
+    xb = xi.activations(np.random.default_rng(8), 3, 1024)
+    ref = oracle.gemv_weights(W, xb)
+    dW = xfp.upload(W)
+    xbig = torch.zeros((3, 1024 + 64), dtype=torch.float16, device="cuda")
+    xbig[:, :1024] = dev_x(xb)
+    ybig = torch.full((3, 128), 7.0, dtype=torch.float32, device="cuda")
+    xfp.xfp_gemv(dW, xbig[:, :1024], y=ybig[:, :100])
+    got = host(ybig)
+    assert gated_rel_err(got[:, :100], ref) <= TOL_F32
+    assert np.all(got[:, 100:] == 7.0)                        # nothing written past N
+
+
+# ------------------------------------------------------------------ batched
+@pytest.mark.parametrize("mode,bits,N,K,M", [(V2, 4, 200, 8192, 16), (V2, 4, 77, 1024, 5),
+                                             (V2, 3, 64, 4096, 16), (V2A, 3, 48, 2048, 8),
+                                             (V2, 4, 33, 4096, 2), (V2, 4, 40, 2048, 33)])
+def test_batched_matches_oracle_and_single_calls(mode, bits, N, K, M):
+    W = xi.random_weights(mode, bits, N, K, density=0.003, seed=M + N)
+    x = xi.activations(np.random.default_rng(M), M, K)
+    dW, xd, ref = check_gemv(W, x)
+    yb = host(xfp.xfp_gemv(dW, xd, y_dtype=torch.float32))
+    for m in (0, M - 1):
+        y1 = host(xfp.xfp_gemv(dW, xd[m:m + 1].contiguous(), y_dtype=torch.float32))
+        assert gated_rel_err(yb[m], y1[0]) <= TOL_F32
+
+
+def test_workload_5_reduced_rows():
+    W = xi.config_weights(5, N=2048)
+    check_gemv(W, xi.config_x(5, 16, W.K))
+
+
+# ------------------------------------------------------------------ expert-indexed
+@pytest.mark.parametrize("mode,bits,N,K,E", [(V2, 3, 128, 4096, 6), (V2, 3, 256, 1024, 6),
+                                             (V2A, 4, 65, 512, 4), (V2, 4, 40, 2048, 3)])
+def test_moe_matches_oracle(mode, bits, N, K, E):
+    W = xi.random_weights(mode, bits, N, K, E=E, density=0.002, seed=E + N)
+    ids = np.array([E - 1, 0, E - 1, 1, 2 % E], dtype=np.int32)         # duplicates are legal
+    T = len(ids)
+    dW = xfp.upload(W)
+    ids_d = torch.from_numpy(ids).cuda()
+    xs = xi.activations(np.random.default_rng(11), 1, K)
+    xt = xi.activations(np.random.default_rng(12), T, K)
+    for shared, xb in ((True, xs), (False, xt)):
+        ref = oracle.gemv_moe(W, ids, xb, shared_x=shared)
+        xd = dev_x(xb)
+        y32 = host(xfp.xfp_gemv_moe(dW, ids_d, xd[0] if shared else xd, y_dtype=torch.float32))
+        y16 = host(xfp.xfp_gemv_moe(dW, ids_d, xd[0] if shared else xd, y_dtype=torch.float16))
+        assert gated_rel_err(y32, ref) <= TOL_F32 and gated_rel_err(y16, ref) <= TOL_F16
+    y0 = xfp.xfp_gemv_moe(dW, ids_d[:0], dev_x(xs)[0])
+    assert y0.shape == (0, N)
+
+
+def test_workload_4_reduced_bank():
+    gu, dn = xi.config_weights(4, E=16)
+    ids = xi.config_expert_ids(4, 8, 16)
+    ids_d = torch.from_numpy(ids).cuda()
+    x1 = xi.config_x(4, 1, gu.K)
+    x2 = xi.activations(np.random.default_rng(99), 8, dn.K)
+    y = host(xfp.xfp_gemv_moe(xfp.upload(gu), ids_d, dev_x(x1)[0]))
+    assert gated_rel_err(y, oracle.gemv_moe(gu, ids, x1, shared_x=True)) <= TOL_F16
+    y = host(xfp.xfp_gemv_moe(xfp.upload(dn), ids_d, dev_x(x2)))
+    assert gated_rel_err(y, oracle.gemv_moe(dn, ids, x2, shared_x=False)) <= TOL_F16

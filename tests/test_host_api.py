@@ -1,0 +1,115 @@
+"""Host-side checks that need no GPU: the library loads, exports what the
+header declares, and rejects bad arguments before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2605_14844_amd as xfp
+from paper_2605_14844_amd.binding import xfp_weights
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000          # a non-NULL, 16-byte aligned "device pointer" that is never dereferenced
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "xfp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(xfp_[a-z_]+)\s*\(", text)))
+
+
+def desc(**kw):
+    d = xfp_weights()
+    d.struct_size = ctypes.sizeof(xfp_weights)
+    d.mode, d.bits, d.group, d.N, d.K, d.L, d.E = 0, 4, 128, 64, 256, 0, 1
+    d.indices = d.codebooks = d.out_row_ptr = d.out_col = d.out_val = FAKE
+    for k, v in kw.items():
+        setattr(d, k, v)
+    return d
+
+
+def gemv(d, x=FAKE, M=1, ldx=256, y=FAKE, dt=0, ldy=64):
+    return xfp.load_library().xfp_gemv(ctypes.byref(d), x, M, ldx, y, dt, ldy, None)
+
+
+def moe(d, ids=FAKE, T=2, x=FAKE, xs=0, y=FAKE, dt=0, ldy=64):
+    return xfp.load_library().xfp_gemv_moe(ctypes.byref(d), ids, T, x, xs, y, dt, ldy, None)
+
+
+def test_library_exports_every_declared_symbol():
+    lib = xfp.load_library()
+    names = declared_functions()
+    assert {"xfp_gemv", "xfp_gemv_moe", "xfp_unpack_indices", "xfp_dequant_bulk", "xfp_strerror",
+            "xfp_version", "xfp_probe_read", "xfp_probe_copy"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert xfp.xfp_version() >= 0x100
+    assert ctypes.sizeof(xfp_weights) == 88
+
+
+def test_strerror_texts():
+    assert xfp.xfp_strerror(0) == "ok"
+    for s in (-1, -2, -3, -4):
+        assert xfp.xfp_strerror(s) not in ("ok", "unknown status")
+    assert xfp.xfp_strerror(-99) == "unknown status"
+
+
+def test_null_pointers():
+    assert xfp.load_library().xfp_gemv(None, FAKE, 1, 256, FAKE, 0, 64, None) == -1
+    assert gemv(desc(indices=None)) == -1
+    assert gemv(desc(codebooks=None)) == -1
+    assert gemv(desc(out_row_ptr=None)) == -1
+    assert gemv(desc(), x=None) == -1
+    assert gemv(desc(), y=None) == -1
+    assert gemv(desc(mode=1, L=32)) == -1                     # V2a without group ids
+    assert moe(desc(E=4), ids=None) == -1
+    lib = xfp.load_library()
+    assert lib.xfp_unpack_indices(ctypes.byref(desc()), None, None) == -1
+    assert lib.xfp_dequant_bulk(ctypes.byref(desc()), None, None) == -1
+
+
+def test_shape_errors():
+    assert gemv(desc(K=200)) == -2                             # K % 128
+    assert gemv(desc(N=0)) == -2
+    assert gemv(desc(K=0)) == -2
+    assert gemv(desc(), M=0) == -2
+    assert gemv(desc(), M=-3) == -2
+    assert gemv(desc(), ldx=128) == -2                         # ldx < K
+    assert gemv(desc(), ldy=10) == -2                          # ldy < N
+    assert gemv(desc(E=2)) == -2                               # xfp_gemv takes one matrix
+    assert moe(desc(E=4), T=-1) == -2
+    assert moe(desc(E=4), xs=64) == -2                         # 0 < stride < K
+
+
+def test_unsupported_format():
+    for bits in (0, 1, 5, 6, 7, 8):
+        assert gemv(desc(bits=bits)) == -3
+    assert gemv(desc(mode=2)) == -3
+    assert gemv(desc(group=64)) == -3
+    assert gemv(desc(flags=1)) == -3
+    assert gemv(desc(struct_size=80)) == -3
+    assert gemv(desc(mode=1, L=0, group_ids=FAKE)) == -3
+    assert gemv(desc(mode=1, L=300, group_ids=FAKE)) == -3
+    assert gemv(desc(L=32)) == -3                              # L given for V2
+    assert gemv(desc(), dt=2) == -3                            # bad y dtype
+
+
+def test_alignment_errors():
+    assert gemv(desc(indices=FAKE + 4)) == -4
+    assert gemv(desc(codebooks=FAKE + 2)) == -4
+    assert gemv(desc(out_row_ptr=FAKE + 2)) == -4
+    assert gemv(desc(), x=FAKE + 2) == -4
+    assert gemv(desc(), y=FAKE + 8) == -4
+    assert gemv(desc(), M=2, ldx=260) == -4
+    assert moe(desc(E=4), xs=260) == -4
+
+
+def test_moe_zero_slots_is_a_no_op():
+    assert moe(desc(E=4), T=0, ids=None, x=None, y=None) == 0
+
+
+def test_binding_rejects_bad_y_dtype_without_touching_the_gpu():
+    import torch
+    with pytest.raises(xfp.XfpError):
+        xfp.binding._y_code(torch.bfloat16)
