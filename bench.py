@@ -1,0 +1,224 @@
+#!/usr/bin/env python3
+"""Benchmark of the XFP fused decode path on one MI355X.
+
+A step is one pass of the whole hot path over one batch: one xfp_gemv call
+(workloads 1, 2, 3, 5) or one gate_up + one down xfp_gemv_moe call (workload
+4).  Weights are already resident in HBM; successive steps walk a ring of
+distinct device copies whose total size exceeds the last-level cache, so the
+weights of a step are never cache-resident.  The K timed steps are recorded
+into one HIP graph and replayed once between two events on the launch stream
+(the eager launch rate from Python is reported beside it).
+
+Prints ONE JSON line.  value = algorithmic bytes per step / time per step.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+RING_BYTES = 1 << 30
+
+
+def parse_args():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=2000)
+    p.add_argument("--warmup", type=int, default=200)
+    p.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2, the headline)")
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--no-graph", action="store_true", help="time eager launches instead of a graph")
+    p.add_argument("--ring-bytes", type=int, default=RING_BYTES)
+    return p.parse_args()
+
+
+def build_workload(cfg: int, ring_bytes: int):
+    """Returns dict(name, step(i), bytes, ring, oracle(), launches_per_step, kernel_bytes)."""
+    import numpy as np
+    import torch
+
+    import paper_2605_14844_amd as xfp
+    import xfp_inputs as xi
+
+    def dev_x(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.float16)
+
+    def clone_weights(dW):
+        t = {k: (None if v is None else v.clone()) for k, v in dW.tensors.items()}
+        d = dW.desc
+        return xfp.binding.make_descriptor(d.mode, d.bits, d.N, d.K, d.L, d.E, t["indices"],
+                                           t["codebooks"], t["group_ids"], t["out_row_ptr"],
+                                           t["out_col"], t["out_val"])
+
+    if cfg in (1, 2, 3, 5):
+        M = 16 if cfg == 5 else 1
+        W = xi.config_weights(cfg)
+        xb = xi.config_x(cfg, M, W.K)
+        nbytes = W.algorithmic_bytes(M=M)
+        R = max(1, min(512, -(-ring_bytes // nbytes)))
+        ring = [xfp.upload(W)]
+        for _ in range(R - 1):
+            ring.append(clone_weights(ring[0]))
+        xd = dev_x(xb)
+        y = torch.empty((M, W.N), dtype=torch.float16, device="cuda")
+
+        def step(i):
+            xfp.xfp_gemv(ring[i % R], xd, y=y)
+
+        def oracle_once(threads=None):
+            import oracle
+            return oracle.gemv_weights(W, xb, threads)
+
+        return dict(name=xi.CONFIG_NAMES[cfg], step=step, bytes=nbytes, ring=R, oracle=oracle_once,
+                    launches=1, kernel_bytes=nbytes, keep=(ring, xd, y), M=M, N=W.N, K=W.K,
+                    bits=W.bits, mode=W.mode)
+
+    if cfg == 4:
+        T = 8
+        gu, dn = xi.config_weights(4)
+        dgu, ddn = xfp.upload(gu), xfp.upload(dn)
+        draws = 64
+        ids_host = [xi.config_expert_ids(4, T, gu.E, draw=d) for d in range(draws)]
+        ids_dev = [torch.from_numpy(a).cuda() for a in ids_host]
+        x1b = xi.config_x(4, 1, gu.K)
+        x2b = xi.activations(np.random.default_rng(xi.BASE_SEED + 404), T, dn.K)
+        x1, x2 = dev_x(x1b)[0], dev_x(x2b)
+        y1 = torch.empty((T, gu.N), dtype=torch.float16, device="cuda")
+        y2 = torch.empty((T, dn.N), dtype=torch.float16, device="cuda")
+        b1 = gu.algorithmic_bytes(experts=T, shared_x=True)
+        b2 = dn.algorithmic_bytes(experts=T, shared_x=False)
+
+        def step(i):
+            ids = ids_dev[i % draws]
+            xfp.xfp_gemv_moe(dgu, ids, x1, y=y1)
+            xfp.xfp_gemv_moe(ddn, ids, x2, y=y2)
+
+        def oracle_once(threads=None):
+            import oracle
+            a = oracle.gemv_moe(gu, ids_host[0], x1b, True, threads)
+            b = oracle.gemv_moe(dn, ids_host[0], x2b, False, threads)
+            return a, b
+
+        return dict(name=xi.CONFIG_NAMES[4], step=step, bytes=b1 + b2, ring=draws, oracle=oracle_once,
+                    launches=2, kernel_bytes=b1, keep=(dgu, ddn, ids_dev, x1, x2, y1, y2), M=1,
+                    N=gu.N, K=gu.K, bits=3, mode=0)
+    raise SystemExit(f"no workload {cfg}")
+
+
+def read_traffic(cfg: int):
+    """HBM bytes per launch measured offline with rocprofv3 --pmc (see profiles/), or None."""
+    path = os.path.join(ROOT, "profiles", f"pmc_traffic_workload{cfg}.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build covers the single-GPU decode kernel only; run with --gpus 1 "
+              "(sharding across GPUs is by output rows and is described in DESIGN.md).", file=sys.stderr)
+        raise SystemExit(2)
+    import torch
+
+    import paper_2605_14844_amd as xfp
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    xfp.load_library()
+
+    t0 = time.time()
+    wl = build_workload(args.config, args.ring_bytes)
+    setup_s = time.time() - t0
+    step, K, Wm = wl["step"], args.steps, args.warmup
+    stream = torch.cuda.current_stream()
+
+    for i in range(Wm):
+        step(i)
+    torch.cuda.synchronize()
+
+    # eager launch rate (reported, not the headline): Python + ctypes + hipLaunchKernel per call
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record(stream)
+    for i in range(K):
+        step(Wm + i)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    eager_ms = e0.elapsed_time(e1) / K
+
+    if args.no_graph:
+        ms_per_step, wall_ms = eager_ms, eager_ms
+    else:
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            torch.cuda.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                for i in range(K):
+                    step(Wm + i)
+        torch.cuda.synchronize()
+        graph.replay()                       # untimed: first replay uploads the graph
+        torch.cuda.synchronize()
+        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        w0 = time.perf_counter()
+        g0.record(stream)
+        graph.replay()                       # EXACTLY K steps
+        g1.record(stream)
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - w0) * 1e3 / K
+        ms_per_step = g0.elapsed_time(g1) / K
+
+    gbs = wl["bytes"] / (ms_per_step * 1e-3) / 1e9
+    launch_ms = ms_per_step * wl["kernel_bytes"] / wl["bytes"] if wl["launches"] > 1 else ms_per_step
+    achieved = wl["kernel_bytes"] / (launch_ms * 1e-3) / 1e9
+    traffic = read_traffic(args.config)
+
+    out = {
+        "metric": "achieved HBM GB/s of the fused XFP decode GEMV (algorithmic bytes / time per call)",
+        "value": round(gbs, 2), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": round(ms_per_step, 6), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16 inputs, f32 accumulate", "data": "synthetic",
+        "config": {"workload": wl["name"], "M": wl["M"], "N": wl["N"], "K": wl["K"], "bits": wl["bits"],
+                   "mode": "V2a" if wl["mode"] else "V2", "y_dtype": "f16",
+                   "algorithmic_bytes_per_step": wl["bytes"], "ring_copies": wl["ring"],
+                   "launches_per_step": wl["launches"], "timed_with": "eager" if args.no_graph else "hip graph replay"},
+        "us_per_call": round(ms_per_step * 1e3, 3),
+        "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
+        "eager_us_per_step": round(eager_ms * 1e3, 3),
+        "wall_us_per_step": round(wall_ms * 1e3, 3),
+        "setup_s": round(setup_s, 1),
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic},
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        threads = oracle.max_threads()
+        wl["oracle"](threads)                # page in, build
+        n, t1 = 0, time.perf_counter()
+        while True:
+            wl["oracle"](threads)
+            n += 1
+            dt = time.perf_counter() - t1
+            if dt > 10.0 or n >= 5000:
+                break
+        out["cpu_baseline"] = {"value": round(wl["bytes"] * n / dt / 1e9, 4), "unit": "GB/s",
+                               "cores": threads, "kind": "oracle",
+                               "sample": f"{n} full calls of the same workload, {dt:.1f} s, "
+                                         f"{dt / n * 1e3:.1f} ms per call"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -48,10 +48,11 @@ def load_library():
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_LIB_PATH):
+    path = os.environ.get("XFP_LIBRARY", _LIB_PATH)     # override: A/B runs of another build
+    if path == _LIB_PATH and not os.path.exists(_LIB_PATH):
         from . import build as _build
         _build.build()
-    lib = ctypes.CDLL(_LIB_PATH)
+    lib = ctypes.CDLL(path)
     vp, i32, i64, u64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_uint64
     wp = ctypes.POINTER(xfp_weights)
     lib.xfp_gemv.argtypes = [wp, vp, i32, i64, vp, i32, i64, vp]

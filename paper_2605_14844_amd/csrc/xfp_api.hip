@@ -87,6 +87,8 @@ int decode(const xfp_weights *W, const int32_t *eids, int slots, const void *x, 
     a.eids = eids;
     a.x_stride = x_stride;
     a.y_stride = ldy;
+    if (xfp::stream_supports((int)W->bits, (int)W->mode, W->K))
+        return finish(xfp::launch_decode_stream((int)W->bits, y_dtype == XFP_F32, a, slots, s));
     a.rows_per_block = rows_per_block(W->N, slots);
     return finish(xfp::launch_decode_rows((int)W->bits, (int)W->mode, y_dtype == XFP_F32, a, slots, s));
 }

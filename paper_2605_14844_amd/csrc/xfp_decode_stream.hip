@@ -1,0 +1,471 @@
+// Streaming fused decode kernel for V2 (one codebook per output channel), M = 1
+// per slot.  This is the fast path for the shapes decode actually sees.
+//
+// Work unit: one wave (a single-wave workgroup, so nothing ever waits at a
+// barrier) owns a run of output rows.  Design points, all for gfx950:
+//  - The activation row lives in VGPRs, not LDS: lane l always decodes the
+//    same k range of every row (32 consecutive k per 2048-wide chunk), so its
+//    32 activations per chunk are loaded once per wave and reused for every
+//    row.  This is the paper's activation-row caching (section 5) moved one
+//    level closer to the ALUs; it leaves the LDS pipe to the codebook lookups.
+//  - Index words are streamed with one 16-byte (4-bit), 12-byte (3-bit) or
+//    8-byte (2-bit) load per lane per chunk; a wave issues the loads of a
+//    whole batch of rows before it touches any of them, and no load is
+//    conditional (out-of-range rows and lanes read a clamped address).
+//  - Codebook lookups go to LDS.  4-bit: the row's 16 fp16 entries as they
+//    are (8 dwords = 8 banks, equal addresses broadcast, so no conflicts);
+//    the byte address of an entry is produced by one SDWA shift per index.
+//    3-bit / 2-bit: a pair table (two indices -> two fp16 in one dword) built
+//    per row, so one lookup and one v_dot2_f32_f16 serve two weights.
+//  - Lookups are software-pipelined in groups of eight: the addresses and LDS
+//    reads of group t+1 are issued before the multiply-accumulates of group t.
+//  - fp32 accumulation in a fixed order, DPP reduction, no atomics: results
+//    are run-to-run deterministic.
+//  - The CSR outliers of a batch of rows are contiguous; they are fetched with
+//    one bounds-checked buffer load per lane while the index stream is still
+//    in flight and folded into the owning row's sum before the reduction.
+#include "xfp_device.h"
+
+namespace xfp {
+
+typedef __attribute__((address_space(3))) const uint16_t lds_u16_t;
+typedef __attribute__((address_space(3))) const uint32_t lds_u32_t;
+typedef __attribute__((address_space(3))) uint32_t lds_u32_w_t;
+
+#define XFP_SDWA_BYTE(op, dst, amount, src, J)                                                   \
+    asm(op " %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_" #J     \
+        : "=v"(dst) : "v"(amount), "v"(src))
+
+// (byte j of m) << amount and (byte j of m) >> amount in one VALU op each.
+// j must be a compile-time constant after unrolling.
+__device__ __forceinline__ uint32_t byte_shl(uint32_t m, int j, uint32_t amount)
+{
+    uint32_t r;
+    switch (j) {
+    case 0: XFP_SDWA_BYTE("v_lshlrev_b32_sdwa", r, amount, m, 0); break;
+    case 1: XFP_SDWA_BYTE("v_lshlrev_b32_sdwa", r, amount, m, 1); break;
+    case 2: XFP_SDWA_BYTE("v_lshlrev_b32_sdwa", r, amount, m, 2); break;
+    default: XFP_SDWA_BYTE("v_lshlrev_b32_sdwa", r, amount, m, 3); break;
+    }
+    return r;
+}
+__device__ __forceinline__ uint32_t byte_shr(uint32_t m, int j, uint32_t amount)
+{
+    uint32_t r;
+    switch (j) {
+    case 0: XFP_SDWA_BYTE("v_lshrrev_b32_sdwa", r, amount, m, 0); break;
+    case 1: XFP_SDWA_BYTE("v_lshrrev_b32_sdwa", r, amount, m, 1); break;
+    case 2: XFP_SDWA_BYTE("v_lshrrev_b32_sdwa", r, amount, m, 2); break;
+    default: XFP_SDWA_BYTE("v_lshrrev_b32_sdwa", r, amount, m, 3); break;
+    }
+    return r;
+}
+
+__device__ __forceinline__ float fma_h(_Float16 c, _Float16 x, float acc)
+{
+    return __builtin_fmaf((float)c, (float)x, acc);     // v_fma_mix_f32
+}
+
+// Geometry of the per-row LDS table for each bit width.
+template <int BITS>
+struct TableFmt {
+    static constexpr int kEntries = 1 << BITS;
+    static constexpr bool kPair = BITS != 4;
+    static constexpr int kRowBytes = kPair ? (4 << (2 * BITS)) : 2 * kEntries;   // 64, 256, 32
+    static constexpr int kRawBytes = 2 * kEntries;                              // 8, 16, 32
+    static constexpr int kGroupsPerLaneLoad = BITS == 4 ? 4 : 2;                // groups of 8 lookups
+};
+
+// Eight lookups of one lane-load: compute LDS addresses and issue the reads.
+//   tb    LDS byte address of the table (wave-uniform, folds into the offset field)
+//   bias  per-lane table selector added on top of tb when BIASED: the number of
+//         tables to skip (row of a multi-row chunk, or the all-zero table for
+//         lanes past the end of a short row).  It is OR-ed into the index bytes
+//         (4-/2-bit) or the address (3-bit), which costs no extra instruction.
+template <int BITS, bool BIASED>
+__device__ __forceinline__ void issue_group(const LaneWords<BITS> &lw, int g, uint32_t tb, uint32_t bias,
+                                            uint32_t (&v)[8], uint32_t k1, uint32_t k2, uint32_t k3)
+{
+    if constexpr (BITS == 4) {
+        const uint32_t w = lw.w[g];
+        uint32_t m0, m1;
+        if constexpr (BIASED) {
+            const uint32_t bb = bias * 0x10101010u;
+            m0 = (w & 0x0F0F0F0Fu) | bb;
+            m1 = ((w >> 4) & 0x0F0F0F0Fu) | bb;
+        } else {
+            m0 = w & 0x0F0F0F0Fu;
+            m1 = w & 0xF0F0F0F0u;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t a0 = byte_shl(m0, j, k1);                       // index * 2
+            const uint32_t a1 = BIASED ? byte_shl(m1, j, k1) : byte_shr(m1, j, k3);
+            v[2 * j] = *(lds_u16_t *)(uintptr_t)(tb + a0);
+            v[2 * j + 1] = *(lds_u16_t *)(uintptr_t)(tb + a1);
+        }
+    } else if constexpr (BITS == 3) {
+        const uint32_t ab = BIASED ? bias * TableFmt<3>::kRowBytes : 0u;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int bit = 6 * (g * 8 + i), word = bit / 32, sh = bit % 32;   // pair = 6 stream bits
+            uint32_t t;
+            if (sh + 6 <= 32) t = sh >= 2 ? lw.w[word] >> (sh - 2) : lw.w[word] << (2 - sh);
+            else t = __builtin_amdgcn_alignbit(lw.w[(word + 1) % 3], lw.w[word], sh - 2);
+            const uint32_t a = BIASED ? ((t & 0xFCu) | ab) : (t & 0xFCu);      // pair index * 4
+            v[i] = *(lds_u32_t *)(uintptr_t)(tb + a);
+        }
+    } else {
+        const uint32_t w = lw.w[g];
+        uint32_t m0, m1;
+        if constexpr (BIASED) {
+            const uint32_t bb = bias * 0x10101010u;
+            m0 = (w & 0x0F0F0F0Fu) | bb;
+            m1 = ((w >> 4) & 0x0F0F0F0Fu) | bb;
+        } else {
+            m0 = w & 0x0F0F0F0Fu;
+            m1 = w & 0xF0F0F0F0u;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t a0 = byte_shl(m0, j, k2);                       // nibble (= pair) * 4
+            const uint32_t a1 = BIASED ? byte_shl(m1, j, k2) : byte_shr(m1, j, k2);
+            v[2 * j] = *(lds_u32_t *)(uintptr_t)(tb + a0);
+            v[2 * j + 1] = *(lds_u32_t *)(uintptr_t)(tb + a1);
+        }
+    }
+}
+
+// Multiply-accumulate the eight looked-up values of group g against the
+// matching activations xw[0..15] of the lane-load.
+template <int BITS>
+__device__ __forceinline__ void consume_group(int g, const uint32_t (&v)[8], const uint32_t *xw, float (&acc)[4])
+{
+    if constexpr (BITS == 4) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const half2_t xp = as_half2(xw[g * 4 + j]);
+            acc[(2 * j) & 3] = fma_h(as_half2(v[2 * j]).x, xp.x, acc[(2 * j) & 3]);
+            acc[(2 * j + 1) & 3] = fma_h(as_half2(v[2 * j + 1]).x, xp.y, acc[(2 * j + 1) & 3]);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            acc[i & 3] = dot2(as_half2(v[i]), as_half2(xw[g * 8 + i]), acc[i & 3]);
+    }
+}
+
+// NCH : 2048-wide chunks per row (RPC == 1), K <= NCH * 2048
+// RPC : rows per chunk (K == 2048 / RPC exactly) for short rows; then NCH == 1
+// TAIL: K is not a multiple of 2048 (RPC == 1): lanes past the row's end in the
+//       last chunk read a clamped address, zero activations and the zero table
+template <int BITS, int NCH, int RPC>
+struct StreamCfg {
+    static constexpr int kUnroll = RPC > 1 ? 4 : (NCH >= 8 ? 1 : (NCH >= 3 ? 2 : (NCH == 2 ? 4 : 8)));
+    static constexpr int kBatchRows = kUnroll * RPC;           // rows a wave decodes at once
+    static constexpr int kLanesPerRow = kWave / RPC;
+    static constexpr int kTableBytes = (kBatchRows + 1) * TableFmt<BITS>::kRowBytes;   // + zero table
+    static constexpr int kRawBytes = TableFmt<BITS>::kPair ? kBatchRows * TableFmt<BITS>::kRawBytes : 0;
+    // registers: 16 per chunk for x, BITS per lane-load in flight, ~60 working
+    static constexpr int kRegs = 16 * NCH + BITS * NCH * kUnroll + 60;
+    static constexpr int kWavesPerSimd =
+        RPC > 1 ? (BITS == 3 ? 4 : 3) : (kRegs <= 128 ? 4 : (kRegs <= 168 ? 3 : 2));
+};
+
+template <int BITS, int NCH, int RPC, bool TAIL>
+__global__ __launch_bounds__(kWave, (StreamCfg<BITS, NCH, RPC>::kWavesPerSimd)) void decode_stream_kernel(
+    DecodeArgs a, int y_f32)
+{
+    using Cfg = StreamCfg<BITS, NCH, RPC>;
+    using Fmt = TableFmt<BITS>;
+    constexpr int U = Cfg::kUnroll, B = Cfg::kBatchRows, LPR = Cfg::kLanesPerRow;
+    constexpr int ENT = Fmt::kEntries, GPL = Fmt::kGroupsPerLaneLoad;
+    __shared__ __align__(16) unsigned char lds[Cfg::kTableBytes + Cfg::kRawBytes + 16];
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
+
+    const uint32_t lane = threadIdx.x;
+    const uint32_t seg = RPC > 1 ? lane / LPR : 0u;            // which row of a chunk this lane is in
+    const uint32_t lis = RPC > 1 ? lane % LPR : lane;          // lane within its row
+    const uint32_t slot = blockIdx.y;
+    const uint32_t e = a.eids ? (uint32_t)a.eids[slot] : 0u;
+    const uint32_t N = a.N, K = a.K;
+    const uint32_t wpr = K / 32 * BITS;
+    const uint32_t *idx = a.idx + (size_t)e * N * wpr;
+    const uint32_t *cbw = reinterpret_cast<const uint32_t *>(a.cb) + (size_t)e * N * (ENT / 2);
+    const int32_t *rp = a.rp + (size_t)e * N;
+    const uint16_t *x = a.x + (int64_t)slot * a.x_stride;
+
+    const bool live_last = !TAIL || ((NCH - 1) * kWave + lis) * kLaneWeights < K;
+    const uint32_t unit_last = live_last ? (NCH - 1) * kWave + lis : 0u;
+
+    const uint32_t row_begin = blockIdx.x * a.rows_per_block;
+    const uint32_t row_end = min(N, row_begin + a.rows_per_block);
+    const uint32_t cb_last = row_end * (ENT / 2) - 1;          // last valid codebook dword
+    const uint32_t k1 = 1, k2 = 2, k3 = 3;
+    constexpr int CBW = (B * (ENT / 2) + kWave - 1) / kWave;   // codebook dwords per lane per batch
+
+    // Vector loads complete in issue order, so the order below is the order in
+    // which their consumers can start: row pointers (they gate the outlier
+    // loads), codebooks (they gate the first lookup), activations, index words.
+    // Lanes 0..B hold rp[rb + lane]: the CSR boundaries of the batch.
+    int32_t rpv = rp[min(row_begin + lane, row_end)];
+    uint32_t cbv[CBW];
+#pragma unroll
+    for (int i = 0; i < CBW; ++i) cbv[i] = cbw[min(row_begin * (ENT / 2) + i * kWave + lane, cb_last)];
+    __builtin_amdgcn_sched_barrier(0);
+
+    // a1: this lane's activations, once per wave.
+    uint32_t xr[NCH][16];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        const uint32_t unit = c == NCH - 1 ? unit_last : c * kWave + lis;   // 32-weight unit in the row
+        const uint4 *xp = reinterpret_cast<const uint4 *>(x + (size_t)unit * kLaneWeights);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            uint4 v = xp[i];
+            xr[c][4 * i] = v.x; xr[c][4 * i + 1] = v.y; xr[c][4 * i + 2] = v.z; xr[c][4 * i + 3] = v.w;
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (TAIL) {
+        // the all-zero table that lanes past the end of the row look up
+        if (lane < Fmt::kRowBytes / 4)
+            *(lds_u32_w_t *)(uintptr_t)(lds_base + B * Fmt::kRowBytes + lane * 4) = 0u;
+    }
+
+    for (uint32_t rb = row_begin; rb < row_end; rb += B) {
+        // a3: issue every index load of the batch (rows past the end are clamped
+        // to the last row and never stored).
+        LaneWords<BITS> lw[U][NCH];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t row = min(rb + u * RPC + seg, row_end - 1);
+            const uint32_t *rw = idx + (size_t)row * wpr;
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                const uint32_t unit = c == NCH - 1 ? unit_last : c * kWave + lis;
+                lw[u][c] = load_lane_words<BITS>(rw + (size_t)unit * BITS);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+
+        // a7 (issue): the CSR entries of the batch are contiguous.  Each lane
+        // takes one entry per row group through a bounds-checked buffer load
+        // (offsets past the end read as zero): no loop, no branch.
+        const int32_t ob0 = __builtin_amdgcn_readlane(rpv, 0);       // entry range of the batch
+        const int32_t ob1 = __builtin_amdgcn_readlane(rpv, B);
+        __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)(a.col + ob0), 0, (ob1 - ob0) * 4, 0x00020000);
+        __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)(a.val + ob0), 0, (ob1 - ob0) * 2, 0x00020000);
+        constexpr int OV = RPC > 1 ? U : 1;
+        int32_t orp[RPC > 1 ? 1 : U + 1];    // RPC == 1: row boundaries (uniform)
+        int32_t oj[OV], oj1[OV];             // this lane's entry; RPC > 1: its row's end
+        uint32_t ocol[OV], oval[OV];
+        if constexpr (RPC == 1) {
+#pragma unroll
+            for (int u = 0; u <= U; ++u) orp[u] = __builtin_amdgcn_readlane(rpv, u);
+            oj[0] = ob0 + (int32_t)lane;
+            oj1[0] = ob1;
+            ocol[0] = __builtin_amdgcn_raw_buffer_load_b32(rc, lane * 4, 0, 0);
+            oval[0] = __builtin_amdgcn_raw_buffer_load_b16(rv, lane * 2, 0, 0);
+        } else {
+            orp[0] = 0;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int32_t r0 = __shfl(rpv, u * RPC + seg);
+                oj1[u] = __shfl(rpv, u * RPC + seg + 1);
+                oj[u] = r0 + (int32_t)lis;
+                ocol[u] = __builtin_amdgcn_raw_buffer_load_b32(rc, (oj[u] - ob0) * 4, 0, 0);
+                oval[u] = __builtin_amdgcn_raw_buffer_load_b16(rv, (oj[u] - ob0) * 2, 0, 0);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+
+        // a2: codebooks of the batch -> LDS tables.
+        __builtin_amdgcn_wave_barrier();
+        if constexpr (!Fmt::kPair) {
+#pragma unroll
+            for (int i = 0; i < CBW; ++i)
+                if (CBW * kWave == B * (ENT / 2) || i * kWave + lane < B * (ENT / 2))
+                    *(lds_u32_w_t *)(uintptr_t)(lds_base + (i * kWave + lane) * 4) = cbv[i];
+        } else {
+            const uint32_t raw_base = lds_base + Cfg::kTableBytes;
+            if (lane < B * (ENT / 2)) *(lds_u32_w_t *)(uintptr_t)(raw_base + lane * 4) = cbv[0];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            constexpr int PE = 1 << (2 * BITS);                // pair entries per row (16 or 64)
+            if (PE == 64 || lane < PE) {
+#pragma unroll
+                for (int r = 0; r < B; ++r) {
+                    uint32_t lo = *(lds_u16_t *)(uintptr_t)(raw_base + r * Fmt::kRawBytes + (lane & (ENT - 1)) * 2);
+                    uint32_t hi = *(lds_u16_t *)(uintptr_t)(raw_base + r * Fmt::kRawBytes + (lane >> BITS) * 2);
+                    *(lds_u32_w_t *)(uintptr_t)(lds_base + r * Fmt::kRowBytes + lane * 4) = lo | (hi << 16);
+                }
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        // next batch's row pointers and codebooks: issued now, consumed next pass
+        if (rb + B < row_end) {
+            rpv = rp[min(rb + B + lane, row_end)];
+#pragma unroll
+            for (int i = 0; i < CBW; ++i)
+                cbv[i] = cbw[min((rb + B) * (ENT / 2) + i * kWave + lane, cb_last)];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+
+        // Keep the activations as packed fp16 pairs: without this the compiler
+        // hoists their fp32 conversions out of the loop and doubles the registers.
+#pragma unroll
+        for (int c = 0; c < NCH; ++c)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                if (TAIL && c == NCH - 1) xr[c][i] = live_last ? xr[c][i] : 0u;
+                asm volatile("" : "+v"(xr[c][i]));
+            }
+
+        // a4-a6: depack, gather, multiply-accumulate, software-pipelined over
+        // groups of eight lookups: task t = (row u, chunk c, group g).
+        float sum[U];
+#ifdef XFP_EXP_NO_COMPUTE
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float accx[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int c = 0; c < NCH; ++c)
+#pragma unroll
+                for (int i = 0; i < BITS; ++i) accx[i & 3] += __builtin_bit_cast(float, lw[u][c].w[i] & xr[c][i]);
+            sum[u] = (accx[0] + accx[1]) + (accx[2] + accx[3]);
+        }
+#else
+        {
+            constexpr int TPR = NCH * GPL;                     // tasks per row
+            constexpr int NT = U * TPR;
+            uint32_t val[2][8];
+            float acc[4] = {0.f, 0.f, 0.f, 0.f};
+            auto issue = [&](int t, uint32_t (&v)[8]) {
+                const int u = t / TPR, c = (t % TPR) / GPL, g = t % GPL;
+                const uint32_t tb = lds_base + u * RPC * Fmt::kRowBytes;
+                if (RPC > 1)
+                    issue_group<BITS, true>(lw[u][c], g, tb, seg, v, k1, k2, k3);
+                else if (TAIL && c == NCH - 1)
+                    issue_group<BITS, true>(lw[u][c], g, tb, live_last ? 0u : (uint32_t)(B - u), v, k1, k2, k3);
+                else
+                    issue_group<BITS, false>(lw[u][c], g, tb, 0u, v, k1, k2, k3);
+            };
+            issue(0, val[0]);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const int u = t / TPR, c = (t % TPR) / GPL, g = t % GPL;
+                if (t + 1 < NT) issue(t + 1, val[(t + 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+                consume_group<BITS>(g, val[t & 1], xr[c], acc);
+                if (t % TPR == TPR - 1) {                      // row finished
+                    sum[u] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+                    acc[0] = acc[1] = acc[2] = acc[3] = 0.f;
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+#endif
+
+        // a7 (fold): gather x at the outlier columns and add each product to the
+        // row that owns the entry.
+#ifndef XFP_EXP_NO_OUTLIERS
+        {
+            uint16_t oxv[OV];
+#pragma unroll
+            for (int v = 0; v < OV; ++v) oxv[v] = x[ocol[v]];
+            if constexpr (RPC == 1) {
+                const float p = half_bits_to_float((uint16_t)oval[0]) * half_bits_to_float(oxv[0]);
+#pragma unroll
+                for (int u = 0; u < U; ++u) sum[u] += (oj[0] >= orp[u] && oj[0] < orp[u + 1]) ? p : 0.f;
+                for (int32_t jw = ob0 + kWave; jw < ob1; jw += kWave) {     // > 64 entries: rare
+                    const int32_t jj = jw + (int32_t)lane;
+                    if (jj < ob1) {
+                        const float q = half_bits_to_float(a.val[jj]) * half_bits_to_float(x[a.col[jj]]);
+#pragma unroll
+                        for (int u = 0; u < U; ++u) sum[u] += (jj >= orp[u] && jj < orp[u + 1]) ? q : 0.f;
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const float p = half_bits_to_float((uint16_t)oval[u]) * half_bits_to_float(oxv[u]);
+                    sum[u] += oj[u] < oj1[u] ? p : 0.f;
+                    for (int32_t jj = oj[u] + LPR; jj < oj1[u]; jj += LPR)         // > LPR entries: rare
+                        sum[u] = fmaf(half_bits_to_float(a.val[jj]), half_bits_to_float(x[a.col[jj]]), sum[u]);
+                }
+            }
+        }
+#endif
+        // a8: reduce and store.
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t row = rb + u * RPC + seg;
+            float t = segment_sum<LPR>(sum[u]);
+            if (lis == 0 && row < row_end) {
+                const int64_t o = (int64_t)slot * a.y_stride + row;
+                if (y_f32) static_cast<float *>(a.y)[o] = t;
+                else static_cast<_Float16 *>(a.y)[o] = (_Float16)t;
+            }
+        }
+    }
+}
+
+// rows per wave: a multiple of the batch, sized so that the grid is a few
+// thousand waves (about 16 per CU) when the problem is large enough.
+template <int BITS, int NCH, int RPC, bool TAIL>
+static hipError_t launch_stream_t(DecodeArgs a, int slots, bool y_f32, hipStream_t s)
+{
+    constexpr int B = StreamCfg<BITS, NCH, RPC>::kBatchRows;
+    const uint64_t total_rows = (uint64_t)a.N * slots;
+    uint32_t rpw = B;
+    while ((total_rows + rpw - 1) / rpw > 6144 && rpw < 64 * B) rpw += B;
+    a.rows_per_block = rpw;
+    dim3 grid((a.N + rpw - 1) / rpw, slots);
+    hipLaunchKernelGGL((decode_stream_kernel<BITS, NCH, RPC, TAIL>), grid, dim3(kWave), 0, s, a, (int)y_f32);
+    return hipGetLastError();
+}
+
+template <int BITS, int NCH>
+static hipError_t launch_stream_n(const DecodeArgs &a, int slots, bool y_f32, hipStream_t s)
+{
+    if (a.K % 2048 == 0) return launch_stream_t<BITS, NCH, 1, false>(a, slots, y_f32, s);
+    return launch_stream_t<BITS, NCH, 1, true>(a, slots, y_f32, s);
+}
+
+template <int BITS>
+static hipError_t launch_stream_b(const DecodeArgs &a, int slots, bool y_f32, hipStream_t s)
+{
+    const uint32_t K = a.K;
+    if (K == 1024) return launch_stream_t<BITS, 1, 2, false>(a, slots, y_f32, s);
+    if (K == 512) return launch_stream_t<BITS, 1, 4, false>(a, slots, y_f32, s);
+    switch ((K + 2047) / 2048) {
+    case 1: return launch_stream_n<BITS, 1>(a, slots, y_f32, s);
+    case 2: return launch_stream_n<BITS, 2>(a, slots, y_f32, s);
+    case 3: return launch_stream_n<BITS, 3>(a, slots, y_f32, s);
+    case 4: return launch_stream_n<BITS, 4>(a, slots, y_f32, s);
+    case 5: return launch_stream_n<BITS, 5>(a, slots, y_f32, s);
+    case 6: return launch_stream_n<BITS, 6>(a, slots, y_f32, s);
+    case 7: return launch_stream_n<BITS, 7>(a, slots, y_f32, s);
+    default: return launch_stream_n<BITS, 8>(a, slots, y_f32, s);
+    }
+}
+
+bool stream_supports(int bits, int mode, uint32_t K)
+{
+    return mode == 0 && bits >= 2 && bits <= 4 && K <= 8 * 2048;
+}
+
+hipError_t launch_decode_stream(int bits, bool y_f32, const DecodeArgs &a, int slots, hipStream_t s)
+{
+    switch (bits) {
+    case 2: return launch_stream_b<2>(a, slots, y_f32, s);
+    case 3: return launch_stream_b<3>(a, slots, y_f32, s);
+    default: return launch_stream_b<4>(a, slots, y_f32, s);
+    }
+}
+
+}  // namespace xfp
