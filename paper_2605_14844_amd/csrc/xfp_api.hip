@@ -87,6 +87,20 @@ int decode(const xfp_weights *W, const int32_t *eids, int slots, const void *x, 
     a.eids = eids;
     a.x_stride = x_stride;
     a.y_stride = ldy;
+    if (!eids && xfp::mfma_supports((int)W->bits, (int)W->mode, W->K, slots)) {
+        // batched tokens: the weights are read once per 16 tokens
+        const size_t ysz = y_dtype == XFP_F32 ? 4 : 2;
+        for (int m0 = 0; m0 < slots; m0 += 16) {
+            xfp::DecodeArgs c = a;
+            c.x = a.x + (int64_t)m0 * x_stride;
+            c.y = static_cast<char *>(y) + (size_t)m0 * (size_t)ldy * ysz;
+            const int mc = slots - m0 < 16 ? slots - m0 : 16;
+            hipError_t err = mc >= 2 ? xfp::launch_decode_mfma(c, mc, y_dtype == XFP_F32, s)
+                                     : xfp::launch_decode_stream((int)W->bits, y_dtype == XFP_F32, c, 1, s);
+            if (err != hipSuccess) return finish(err);
+        }
+        return XFP_OK;
+    }
     if (xfp::stream_supports((int)W->bits, (int)W->mode, W->K))
         return finish(xfp::launch_decode_stream((int)W->bits, y_dtype == XFP_F32, a, slots, s));
     a.rows_per_block = rows_per_block(W->N, slots);

@@ -161,7 +161,11 @@ __device__ __forceinline__ void consume_group(int g, const uint32_t (&v)[8], con
 //       last chunk read a clamped address, zero activations and the zero table
 template <int BITS, int NCH, int RPC>
 struct StreamCfg {
+#ifdef XFP_EXP_U
+    static constexpr int kUnroll = XFP_EXP_U;
+#else
     static constexpr int kUnroll = RPC > 1 ? 4 : (NCH >= 8 ? 1 : (NCH >= 3 ? 2 : (NCH == 2 ? 4 : 8)));
+#endif
     static constexpr int kBatchRows = kUnroll * RPC;           // rows a wave decodes at once
     static constexpr int kLanesPerRow = kWave / RPC;
     static constexpr int kTableBytes = (kBatchRows + 1) * TableFmt<BITS>::kRowBytes;   // + zero table
@@ -222,7 +226,11 @@ __global__ __launch_bounds__(kWave, (StreamCfg<BITS, NCH, RPC>::kWavesPerSimd)) 
         const uint4 *xp = reinterpret_cast<const uint4 *>(x + (size_t)unit * kLaneWeights);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
+#ifdef XFP_EXP_NO_X
+            uint4 v = make_uint4(lane + i, lane, 0x3c003c00u, lane * (uint32_t)(uintptr_t)xp);
+#else
             uint4 v = xp[i];
+#endif
             xr[c][4 * i] = v.x; xr[c][4 * i + 1] = v.y; xr[c][4 * i + 2] = v.z; xr[c][4 * i + 3] = v.w;
         }
     }
