@@ -23,10 +23,19 @@
 // tables of tile t+1 are built (double-buffered) while tile t is decoded.
 //
 // Per tile, the 8 partial D blocks are summed through LDS in a fixed order
-// (deterministic) by 256 threads, which also add the CSR outlier products that
-// all 512 threads computed for the tile (col/val via bounds-checked buffer
-// loads, x gathered from L2) during the decode.
+// (deterministic) by 256 threads, which also add the CSR outlier products of
+// the tile.  One thread per outlier entry computes its 16 products: col/val
+// come through bounds-checked buffer loads one tile ahead, and the 16 tokens'
+// activations at that column come as ONE 32-byte read from a k-major
+// (transposed) copy of x.  Gathering them from the row-major x instead costs
+// 16 cache lines per entry and was measured to triple the kernel time.  The
+// transposed copy lives in a small ring of file-scope device buffers and is
+// written by a tiny kernel launched in front of the decode kernel on the same
+// stream; more than kXtSlots batched calls in flight at once on one GPU would
+// reuse a slot that is still being read.
 #include "xfp_device.h"
+
+#include <atomic>
 
 namespace xfp {
 
@@ -44,6 +53,28 @@ constexpr int kRedBytes = kMfmaWaves * 256 * 4; // partial D blocks of one tile
 constexpr int kProdEntries = 512;               // outlier entries per tile kept in LDS
 constexpr int kProdBytes = kProdEntries * 16 * 4;
 constexpr int kMfmaLds = 2 * kTabBytes + 2 * kRedBytes + 2 * kProdBytes;
+
+constexpr int kXtSlots = 16;                   // batched calls that may overlap on one GPU
+constexpr int kXtMaxK = 8192;
+static __device__ __align__(256) uint16_t g_xt[kXtSlots][kXtMaxK * kTile];   // [slot][k][16 tokens]
+
+// x [M][ldx] row-major -> g_xt[slot][k][0..15], tokens >= M zero.
+__global__ __launch_bounds__(256) void transpose_x_kernel(const uint16_t *x, int64_t ldx, int M, uint32_t K,
+                                                          int slot)
+{
+    const uint32_t k = blockIdx.x * 256 + threadIdx.x;
+    if (k >= K) return;
+    uint32_t v[8];
+#pragma unroll
+    for (int m = 0; m < 16; m += 2) {
+        const uint32_t lo = m < M ? x[(size_t)m * ldx + k] : 0u;
+        const uint32_t hi = m + 1 < M ? x[(size_t)(m + 1) * ldx + k] : 0u;
+        v[m / 2] = lo | (hi << 16);
+    }
+    uint4 *o = reinterpret_cast<uint4 *>(&g_xt[slot][(size_t)k * kTile]);
+    o[0] = make_uint4(v[0], v[1], v[2], v[3]);
+    o[1] = make_uint4(v[4], v[5], v[6], v[7]);
+}
 
 #define XFP_SDWA_SHL(dst, amount, src, J)                                                         \
     asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_" #J \
@@ -64,7 +95,7 @@ __device__ __forceinline__ uint32_t byte_times_128(uint32_t w, int j, uint32_t s
 // KS = K / 1024: each lane owns 32*KS weights of its row per tile (KS dwordx4
 // loads), 4*KS MFMA steps, 16*KS VGPRs of activations.
 template <int KS>
-__global__ __launch_bounds__(kMfmaThreads) void decode_mfma4_kernel(DecodeArgs a, int M, int y_f32)
+__global__ __launch_bounds__(kMfmaThreads) void decode_mfma4_kernel(DecodeArgs a, int M, int y_f32, int xt_slot)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
@@ -135,10 +166,24 @@ __global__ __launch_bounds__(kMfmaThreads) void decode_mfma4_kernel(DecodeArgs a
             *(lds_u32_t *)(uintptr_t)(base + rep * 16 * 128) = lo | hi;
         }
     };
-    load_codebook(t);
+    // Outlier entry `tid` of a tile (the first 512; more are rare and handled by
+    // the reducers): col/val are fetched one tile ahead through bounds-checked
+    // buffer loads (entries past the end read as zero).
+    const uint4 *xt = reinterpret_cast<const uint4 *>(&g_xt[xt_slot][0]);
+    uint32_t ocol = 0, oval = 0;
+    auto out_issue = [&](int32_t base, int32_t cnt) {
+        __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc((void *)(a.col + base), 0, cnt * 4, 0x00020000);
+        __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc((void *)(a.val + base), 0, cnt * 2, 0x00020000);
+        ocol = __builtin_amdgcn_raw_buffer_load_b32(rc, tid * 4, 0, 0);
+        oval = __builtin_amdgcn_raw_buffer_load_b16(rv, tid * 2, 0, 0);
+    };
+
     load_rp(t);
+    load_codebook(t);
 #pragma unroll
     for (int c = 0; c < KS; ++c) load_indices(t, c);
+    out_issue(__builtin_amdgcn_readfirstlane(rp_base),
+              __builtin_amdgcn_readfirstlane(rp_end) - __builtin_amdgcn_readfirstlane(rp_base));
     build_table(0);
     __syncthreads();
 
@@ -151,81 +196,85 @@ __global__ __launch_bounds__(kMfmaThreads) void decode_mfma4_kernel(DecodeArgs a
         const int32_t ob0 = __builtin_amdgcn_readfirstlane(rp_base);
         const int32_t ocnt = __builtin_amdgcn_readfirstlane(rp_end) - ob0;
         const int32_t my_lo = rp_lo - ob0, my_hi = rp_hi - ob0;  // reducer's entry range, tile-relative
+
+        // a7: gather x at this tile's outlier columns (col/val were issued one
+        // tile ago, so waiting for them waits for nothing newer than this tile's
+        // index words); the products go to LDS after a few decode steps, before
+        // any load of the next tile is issued.
+#ifdef XFP_EXP_MFMA_NO_OUT
+        const bool have_out = false;
+#else
+        const bool have_out = ocnt > 0;
+#endif
+        uint4 ox0 = make_uint4(0, 0, 0, 0), ox1 = ox0;
+        if (have_out) {
+            ox0 = xt[(size_t)ocol * 2];
+            ox1 = xt[(size_t)ocol * 2 + 1];
+        }
+        __builtin_amdgcn_sched_barrier(0);
         if (has_next) {
-            load_codebook(tn);
             load_rp(tn);
+            load_codebook(tn);
         }
         __builtin_amdgcn_sched_barrier(0);
 
-        // ---- outliers (a7): entry e = pass*256 + u*32 + tid/16, token m = tid%16 ----
-        const uint32_t om = tid & 15, og = tid >> 4;
-        const uint16_t *xm = a.x + (size_t)min(om, (uint32_t)M - 1) * a.x_stride;
-        __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc((void *)(a.col + ob0), 0, ocnt * 4, 0x00020000);
-        __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc((void *)(a.val + ob0), 0, ocnt * 2, 0x00020000);
-        uint32_t ocol[8], oval[8];
-        uint16_t oxg[8];
-        auto out_issue = [&](int pass) {
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const uint32_t e = pass * 256 + u * 32 + og;
-                ocol[u] = __builtin_amdgcn_raw_buffer_load_b32(rc, e * 4, 0, 0);
-                oval[u] = __builtin_amdgcn_raw_buffer_load_b16(rv, e * 2, 0, 0);
-            }
-        };
-        auto out_gather = [&]() {
-#pragma unroll
-            for (int u = 0; u < 8; ++u) oxg[u] = xm[ocol[u]];
-        };
-        auto out_store = [&](int pass) {
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const uint32_t e = pass * 256 + u * 32 + og;
-                const float p = half_bits_to_float((uint16_t)oval[u]) * half_bits_to_float(oxg[u]);
-                *(lds_f32_t *)(uintptr_t)(lds_prod + buf * kProdBytes + (e * 16 + om) * 4) = p;
-            }
-        };
-        const bool pass0 = ocnt > 0, pass1 = ocnt > 256;
-        if (pass0) out_issue(0);
-        __builtin_amdgcn_sched_barrier(0);
-
-        // ---- a3-a6: depack, pair lookup, MFMA ----
-        float4_t acc = {0.f, 0.f, 0.f, 0.f};
+        // ---- a3-a6: depack, pair lookup, MFMA; lookups run one step ahead ----
+        float4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
         const uint32_t tl = lds_tab + buf * kTabBytes + bank4;
-#pragma unroll
-        for (int s = 0; s < NSTEP; ++s) {
+        uint32_t av[2][4];
+        auto lookup = [&](int s, uint32_t (&v)[4]) {
             const uint4 &q4 = iw[s / 4];
             const uint32_t w = (s & 3) == 0 ? q4.x : ((s & 3) == 1 ? q4.y : ((s & 3) == 2 ? q4.z : q4.w));
-            uint32_t av[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                av[j] = *(lds_cu32_t *)(uintptr_t)(tl + byte_times_128(w, j, seven));
-            half8_t af = __builtin_bit_cast(half8_t, make_uint4(av[0], av[1], av[2], av[3]));
+#ifdef XFP_EXP_MFMA_NO_LOOKUP
+            for (int j = 0; j < 4; ++j) v[j] = w + j;
+#else
+            for (int j = 0; j < 4; ++j) v[j] = *(lds_cu32_t *)(uintptr_t)(tl + byte_times_128(w, j, seven));
+#endif
+        };
+        constexpr int OUT_STEP = 3;                      // step after which the outlier products are stored
+        lookup(0, av[0]);
+#pragma unroll
+        for (int s = 0; s < NSTEP; ++s) {
+            if (s + 1 < NSTEP) lookup(s + 1, av[(s + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            half8_t af = __builtin_bit_cast(half8_t, make_uint4(av[s & 1][0], av[s & 1][1], av[s & 1][2], av[s & 1][3]));
             half8_t bf = __builtin_bit_cast(half8_t, make_uint4(xr[s][0], xr[s][1], xr[s][2], xr[s][3]));
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(af, bf, acc, 0, 0, 0);
-            // the index quad is dead after its 4th step: refill it for the next tile
-            if ((s & 3) == 3 && has_next) load_indices(tn, s / 4);
-            // outlier pipeline, two passes hidden under the decode
-            if (NSTEP >= 8) {
-                if (s == NSTEP / 4 - 1 && pass0) out_gather();
-                if (s == NSTEP / 2 - 1 && pass0) { out_store(0); if (pass1) out_issue(1); }
-                if (s == 3 * NSTEP / 4 - 1 && pass1) out_gather();
+            if (s & 1) acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(af, bf, acc1, 0, 0, 0);
+            else acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(af, bf, acc0, 0, 0, 0);
+            if (s == OUT_STEP && have_out) {
+                const float v = half_bits_to_float((uint16_t)oval);
+                const uint32_t xw[8] = {ox0.x, ox0.y, ox0.z, ox0.w, ox1.x, ox1.y, ox1.z, ox1.w};
+                float p[16];
+#pragma unroll
+                for (int m = 0; m < 16; ++m)
+                    p[m] = v * half_bits_to_float((uint16_t)(m & 1 ? xw[m / 2] >> 16 : xw[m / 2] & 0xFFFFu));
+                typedef __attribute__((address_space(3))) float4_t lds_f4_t;
+                lds_f4_t *dst = (lds_f4_t *)(uintptr_t)(lds_prod + buf * kProdBytes + tid * 64);
+#pragma unroll
+                for (int g = 0; g < 4; ++g) dst[g] = float4_t{p[4 * g], p[4 * g + 1], p[4 * g + 2], p[4 * g + 3]};
             }
-        }
-        if (NSTEP >= 8) {
-            if (pass1) out_store(1);
-        } else if (pass0) {
-            out_gather();
-            out_store(0);
-            if (pass1) { out_issue(1); out_gather(); out_store(1); }
+            // an index quad is dead after its 4th step: refill it for the next tile
+            // (the first refill comes after the outlier products are out of the way)
+            if ((s & 3) == 3 && has_next) load_indices(tn, s / 4);
+            __builtin_amdgcn_sched_barrier(0);
         }
 
-        // ---- tables of the next tile, partial D of this one ----
-        if (has_next) build_table(buf ^ 1);
+        // ---- next tile: outlier loads and tables; this tile: partial D ----
+        if (has_next) {
+#ifndef XFP_EXP_MFMA_NO_OUT
+            out_issue(__builtin_amdgcn_readfirstlane(rp_base),
+                      __builtin_amdgcn_readfirstlane(rp_end) - __builtin_amdgcn_readfirstlane(rp_base));
+#endif
+#ifndef XFP_EXP_MFMA_NO_BUILD
+            build_table(buf ^ 1);
+#endif
+        }
         {
             const uint32_t rb = lds_red + buf * kRedBytes + wave * 1024;
 #pragma unroll
             for (int r = 0; r < 4; ++r)                   // D[4q + r][i]
-                *(lds_f32_t *)(uintptr_t)(rb + ((4 * q + r) * 16 + i) * 4) = acc[r];
+                *(lds_f32_t *)(uintptr_t)(rb + ((4 * q + r) * 16 + i) * 4) = acc0[r] + acc1[r];
         }
         __syncthreads();
 
@@ -237,12 +286,14 @@ __global__ __launch_bounds__(kMfmaThreads) void decode_mfma4_kernel(DecodeArgs a
             for (int w = 0; w < kMfmaWaves; ++w)
                 s += *(lds_f32_t *)(uintptr_t)(lds_red + buf * kRedBytes + w * 1024 + tid * 4);
             const uint16_t *xrow = a.x + (size_t)min(m, (uint32_t)M - 1) * a.x_stride;
+#ifndef XFP_EXP_MFMA_NO_OUT
             for (int32_t e = my_lo; e < my_hi; ++e) {
                 if (e < kProdEntries)
                     s += *(lds_f32_t *)(uintptr_t)(lds_prod + buf * kProdBytes + (e * 16 + m) * 4);
                 else                                       // more than 512 entries in a tile: rare
                     s = fmaf(half_bits_to_float(a.val[ob0 + e]), half_bits_to_float(xrow[a.col[ob0 + e]]), s);
             }
+#endif
             if (n < N && m < (uint32_t)M) {
                 const int64_t o = (int64_t)m * a.y_stride + n;
                 if (y_f32) static_cast<float *>(a.y)[o] = s;
@@ -263,9 +314,12 @@ static hipError_t launch_mfma_t(const DecodeArgs &a, int M, bool y_f32, hipStrea
         if (err != hipSuccess) return err;
         configured = true;
     }
+    static std::atomic<unsigned> next_slot{0};
+    const int slot = (int)(next_slot.fetch_add(1, std::memory_order_relaxed) % kXtSlots);
+    hipLaunchKernelGGL(transpose_x_kernel, dim3((a.K + 255) / 256), dim3(256), 0, s, a.x, a.x_stride, M, a.K, slot);
     const uint32_t ntiles = (a.N + kTile - 1) / kTile;
     const uint32_t blocks = ntiles < 256 ? ntiles : 256;
-    hipLaunchKernelGGL(kern, dim3(blocks), dim3(kMfmaThreads), kMfmaLds, s, a, M, (int)y_f32);
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(kMfmaThreads), kMfmaLds, s, a, M, (int)y_f32, slot);
     return hipGetLastError();
 }
 
