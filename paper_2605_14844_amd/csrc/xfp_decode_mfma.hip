@@ -76,6 +76,22 @@ __global__ __launch_bounds__(256) void transpose_x_kernel(const uint16_t *x, int
     o[1] = make_uint4(v[4], v[5], v[6], v[7]);
 }
 
+#ifdef XFP_EXP_TIMING
+static __device__ unsigned long long g_dbg[8192];
+#define XFP_STAMP(phase) do { if (blockIdx.x == 0 && lane == 0 && it < 8) g_dbg[(it * 8 + (phase)) * 8 + wave] = __builtin_amdgcn_s_memrealtime(); } while (0)
+extern "C" int xfp_exp_read_debug(void *dst, size_t bytes) { return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_dbg), bytes); }
+#else
+#define XFP_STAMP(phase) do { } while (0)
+#endif
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits
+// for every outstanding global load (vmcnt(0)), which would drain the index
+// prefetch of the next tile at every tile boundary.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 #define XFP_SDWA_SHL(dst, amount, src, J)                                                         \
     asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_" #J \
         : "=v"(dst) : "v"(amount), "v"(src))
@@ -132,20 +148,27 @@ __global__ __launch_bounds__(kMfmaThreads) void decode_mfma4_kernel(DecodeArgs a
 
     uint32_t t = blockIdx.x;
     if (t >= ntiles) return;
+    const uint32_t tstep = gridDim.x;
 
-    // ---- prologue: tables, index words and row pointers of the first tile ----
+    // ---- per-tile loaders ----
     uint4 iw[KS];
-    int32_t rp_lo, rp_hi, rp_base, rp_end;
     auto load_indices = [&](uint32_t tile, int c) {
         const uint32_t row = min(tile * kTile + i, N - 1);
         iw[c] = reinterpret_cast<const uint4 *>(a.idx + (size_t)row * wpr + k0 / 8)[c];
     };
+    // Row pointers a thread needs for a tile: the tile's entry range and the
+    // ranges of the two rows it helps reduce (rows `wave` and `wave + 8`).
+    struct TileRp { int32_t base, end, lo1, hi1, lo2, hi2; };
     auto load_rp = [&](uint32_t tile) {
-        const uint32_t n0 = tile * kTile, nl = (tid >> 4) & 15;
-        rp_lo = a.rp[min(n0 + nl, N)];
-        rp_hi = a.rp[min(n0 + nl + 1, N)];
-        rp_base = a.rp[min(n0, N)];
-        rp_end = a.rp[min(n0 + kTile, N)];
+        const uint32_t n0 = tile * kTile;
+        TileRp r;
+        r.base = a.rp[min(n0, N)];
+        r.end = a.rp[min(n0 + kTile, N)];
+        r.lo1 = a.rp[min(n0 + wave, N)];
+        r.hi1 = a.rp[min(n0 + wave + 1, N)];
+        r.lo2 = a.rp[min(n0 + wave + 8, N)];
+        r.hi2 = a.rp[min(n0 + wave + 9, N)];
+        return r;
     };
     uint4 cbr[2];
     uint32_t cblo;
@@ -166,85 +189,95 @@ __global__ __launch_bounds__(kMfmaThreads) void decode_mfma4_kernel(DecodeArgs a
             *(lds_u32_t *)(uintptr_t)(base + rep * 16 * 128) = lo | hi;
         }
     };
-    // Outlier entry `tid` of a tile (the first 512; more are rare and handled by
-    // the reducers): col/val are fetched one tile ahead through bounds-checked
-    // buffer loads (entries past the end read as zero).
+    // Outlier entry `tid` of a tile (the first 512; more are rare and handled in
+    // the reduction): col/val through bounds-checked buffer loads (entries past
+    // the end read as zero), then the 16 tokens' activations at that column as
+    // one 32-byte read of the transposed copy.
     const uint4 *xt = reinterpret_cast<const uint4 *>(&g_xt[xt_slot][0]);
-    uint32_t ocol = 0, oval = 0;
-    auto out_issue = [&](int32_t base, int32_t cnt) {
+    auto out_issue = [&](const TileRp &r, uint32_t &col, uint32_t &val) {
+        const int32_t base = __builtin_amdgcn_readfirstlane(r.base);
+        const int32_t cnt = __builtin_amdgcn_readfirstlane(r.end) - base;
         __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc((void *)(a.col + base), 0, cnt * 4, 0x00020000);
         __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc((void *)(a.val + base), 0, cnt * 2, 0x00020000);
-        ocol = __builtin_amdgcn_raw_buffer_load_b32(rc, tid * 4, 0, 0);
-        oval = __builtin_amdgcn_raw_buffer_load_b16(rv, tid * 2, 0, 0);
+        col = __builtin_amdgcn_raw_buffer_load_b32(rc, tid * 4, 0, 0);
+        val = __builtin_amdgcn_raw_buffer_load_b16(rv, tid * 2, 0, 0);
     };
 
-    load_rp(t);
+    // ---- prologue ----
+    // Pipeline depths: index words, codebooks/tables and outlier col/val run one
+    // tile ahead; row pointers two tiles ahead (they gate the col/val loads).
+    const uint32_t t1 = t + tstep < ntiles ? t + tstep : t;
+    TileRp rp_cur = load_rp(t);
+    TileRp rp_nxt = load_rp(t1);
     load_codebook(t);
 #pragma unroll
     for (int c = 0; c < KS; ++c) load_indices(t, c);
-    out_issue(__builtin_amdgcn_readfirstlane(rp_base),
-              __builtin_amdgcn_readfirstlane(rp_end) - __builtin_amdgcn_readfirstlane(rp_base));
+    uint32_t ocol_n = 0, oval_n = 0, oval_c = 0;
+    uint4 ox0_c, ox1_c;
+    out_issue(rp_cur, ocol_n, oval_n);
     build_table(0);
+    ox0_c = xt[(size_t)ocol_n * 2];
+    ox1_c = xt[(size_t)ocol_n * 2 + 1];
+    oval_c = oval_n;
+    out_issue(rp_nxt, ocol_n, oval_n);               // the second tile's entries, gathered during pass 0
     __syncthreads();
 
-    for (uint32_t it = 0; t < ntiles; t += gridDim.x, ++it) {
+    for (uint32_t it = 0; t < ntiles; t += tstep, ++it) {
         const uint32_t buf = it & 1;
-        const uint32_t tn = t + gridDim.x;               // next tile of this workgroup
-        const bool has_next = tn < ntiles;
+        // Next tile of this workgroup.  The last pass "prefetches" its own tile
+        // again (cache hits, results unused) so that the loop body is one
+        // straight line: conditional loads make the compiler wait for every
+        // outstanding load (vmcnt(0)) where a partial wait would do.
+        const uint32_t tn = t + tstep < ntiles ? t + tstep : t;
         const uint32_t n0 = t * kTile;
-        // metadata of this tile (loaded one iteration ago)
-        const int32_t ob0 = __builtin_amdgcn_readfirstlane(rp_base);
-        const int32_t ocnt = __builtin_amdgcn_readfirstlane(rp_end) - ob0;
-        const int32_t my_lo = rp_lo - ob0, my_hi = rp_hi - ob0;  // reducer's entry range, tile-relative
-
-        // a7: gather x at this tile's outlier columns (col/val were issued one
-        // tile ago, so waiting for them waits for nothing newer than this tile's
-        // index words); the products go to LDS after a few decode steps, before
-        // any load of the next tile is issued.
+        const int32_t ob0 = __builtin_amdgcn_readfirstlane(rp_cur.base);
+        const int32_t ocnt = __builtin_amdgcn_readfirstlane(rp_cur.end) - ob0;
 #ifdef XFP_EXP_MFMA_NO_OUT
         const bool have_out = false;
 #else
-        const bool have_out = ocnt > 0;
+        const bool have_out = true;                      // entries past the end read as zero products
 #endif
-        uint4 ox0 = make_uint4(0, 0, 0, 0), ox1 = ox0;
-        if (have_out) {
-            ox0 = xt[(size_t)ocol * 2];
-            ox1 = xt[(size_t)ocol * 2 + 1];
-        }
+        (void)ocnt;
+        XFP_STAMP(0);
+        // Loads of this pass, oldest first: the row pointers two tiles ahead and
+        // the next tile's codebooks; index refills follow during the decode and
+        // the col/val loads of the tile after next close the pass.
+        TileRp rp_far = load_rp(tn + tstep < ntiles ? tn + tstep : tn);
+        load_codebook(tn);
         __builtin_amdgcn_sched_barrier(0);
-        if (has_next) {
-            load_rp(tn);
-            load_codebook(tn);
-        }
-        __builtin_amdgcn_sched_barrier(0);
+        XFP_STAMP(1);
 
-        // ---- a3-a6: depack, pair lookup, MFMA; lookups run one step ahead ----
+        // ---- a3-a6: depack, pair lookup, MFMA; lookups run two steps ahead ----
         float4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
         const uint32_t tl = lds_tab + buf * kTabBytes + bank4;
-        uint32_t av[2][4];
+        uint32_t av[3][4];
         auto lookup = [&](int s, uint32_t (&v)[4]) {
             const uint4 &q4 = iw[s / 4];
             const uint32_t w = (s & 3) == 0 ? q4.x : ((s & 3) == 1 ? q4.y : ((s & 3) == 2 ? q4.z : q4.w));
 #pragma unroll
-#ifdef XFP_EXP_MFMA_NO_LOOKUP
-            for (int j = 0; j < 4; ++j) v[j] = w + j;
-#else
             for (int j = 0; j < 4; ++j) v[j] = *(lds_cu32_t *)(uintptr_t)(tl + byte_times_128(w, j, seven));
-#endif
         };
-        constexpr int OUT_STEP = 3;                      // step after which the outlier products are stored
+        constexpr int OUT_STEP = 2;                      // after this step the outlier products are stored
+        // From this step on the next tile's loads are issued: first the x gather
+        // at its outlier columns (their col loads are the oldest loads of this
+        // pass), then the index refills of the quads already consumed.
+        constexpr int GATHER_STEP = NSTEP >= 16 ? 11 : NSTEP - 1;
+        uint4 ox0_n = ox0_c, ox1_n = ox1_c;
         lookup(0, av[0]);
+        if (NSTEP > 1) lookup(1, av[1]);
 #pragma unroll
         for (int s = 0; s < NSTEP; ++s) {
-            if (s + 1 < NSTEP) lookup(s + 1, av[(s + 1) & 1]);
+            if (s + 2 < NSTEP) lookup(s + 2, av[(s + 2) % 3]);
             __builtin_amdgcn_sched_barrier(0);
-            half8_t af = __builtin_bit_cast(half8_t, make_uint4(av[s & 1][0], av[s & 1][1], av[s & 1][2], av[s & 1][3]));
+            const uint32_t (&cur)[4] = av[s % 3];
+            half8_t af = __builtin_bit_cast(half8_t, make_uint4(cur[0], cur[1], cur[2], cur[3]));
             half8_t bf = __builtin_bit_cast(half8_t, make_uint4(xr[s][0], xr[s][1], xr[s][2], xr[s][3]));
             if (s & 1) acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(af, bf, acc1, 0, 0, 0);
             else acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(af, bf, acc0, 0, 0, 0);
             if (s == OUT_STEP && have_out) {
-                const float v = half_bits_to_float((uint16_t)oval);
-                const uint32_t xw[8] = {ox0.x, ox0.y, ox0.z, ox0.w, ox1.x, ox1.y, ox1.z, ox1.w};
+                // a7: this entry's 16 products -> LDS (gathered one tile ago)
+                const float v = half_bits_to_float((uint16_t)oval_c);
+                const uint32_t xw[8] = {ox0_c.x, ox0_c.y, ox0_c.z, ox0_c.w, ox1_c.x, ox1_c.y, ox1_c.z, ox1_c.w};
                 float p[16];
 #pragma unroll
                 for (int m = 0; m < 16; ++m)
@@ -254,52 +287,94 @@ __global__ __launch_bounds__(kMfmaThreads) void decode_mfma4_kernel(DecodeArgs a
 #pragma unroll
                 for (int g = 0; g < 4; ++g) dst[g] = float4_t{p[4 * g], p[4 * g + 1], p[4 * g + 2], p[4 * g + 3]};
             }
+            if (s == GATHER_STEP) {                      // next tile's activations at its outlier columns
+                ox0_n = xt[(size_t)ocol_n * 2];
+                ox1_n = xt[(size_t)ocol_n * 2 + 1];
+            }
             // an index quad is dead after its 4th step: refill it for the next tile
-            // (the first refill comes after the outlier products are out of the way)
-            if ((s & 3) == 3 && has_next) load_indices(tn, s / 4);
+#ifndef XFP_EXP_MFMA_NO_REFILL
+            if (s == GATHER_STEP) {
+#pragma unroll
+                for (int c = 0; c < KS; ++c)
+                    if (4 * c + 3 <= GATHER_STEP) load_indices(tn, c);
+            } else if (s > GATHER_STEP && (s & 3) == 3) {
+                load_indices(tn, s / 4);
+            }
+#endif
             __builtin_amdgcn_sched_barrier(0);
         }
+        XFP_STAMP(2);
 
-        // ---- next tile: outlier loads and tables; this tile: partial D ----
-        if (has_next) {
-#ifndef XFP_EXP_MFMA_NO_OUT
-            out_issue(__builtin_amdgcn_readfirstlane(rp_base),
-                      __builtin_amdgcn_readfirstlane(rp_end) - __builtin_amdgcn_readfirstlane(rp_base));
-#endif
-#ifndef XFP_EXP_MFMA_NO_BUILD
-            build_table(buf ^ 1);
-#endif
-        }
+        // ---- tables of the next tile, partial D of this one, col/val two tiles ahead ----
+        build_table(buf ^ 1);
+        oval_c = oval_n;                                 // next tile's values (arrived long ago)
+        out_issue(rp_far, ocol_n, oval_n);
         {
             const uint32_t rb = lds_red + buf * kRedBytes + wave * 1024;
 #pragma unroll
             for (int r = 0; r < 4; ++r)                   // D[4q + r][i]
                 *(lds_f32_t *)(uintptr_t)(rb + ((4 * q + r) * 16 + i) * 4) = acc0[r] + acc1[r];
         }
-        __syncthreads();
+        XFP_STAMP(3);
+        lds_barrier();
+        XFP_STAMP(4);
 
-        // ---- a8: cross-wave reduction, outlier fold, store (256 threads) ----
-        if (tid < 256) {
-            const uint32_t nl = tid >> 4, m = tid & 15, n = n0 + nl;
-            float s = 0.f;
-#pragma unroll
-            for (int w = 0; w < kMfmaWaves; ++w)
-                s += *(lds_f32_t *)(uintptr_t)(lds_red + buf * kRedBytes + w * 1024 + tid * 4);
+        // ---- a8: cross-wave reduction, outlier fold, store ----
+        // Output (row nl, token m) is summed by the 4 lanes of a quad in a fixed
+        // pattern (lane j: waves j and j+4, outlier entries lo+j, lo+j+4, ...) and
+        // a fixed DPP order, so results are deterministic.  Each thread serves
+        // rows `wave` and `wave + 8`.
+        {
+            const uint32_t sub = tid & 3, m = (tid >> 2) & 15;
             const uint16_t *xrow = a.x + (size_t)min(m, (uint32_t)M - 1) * a.x_stride;
+            constexpr int RD = 10;                        // unconditional reads per lane: 4*RD entries per row
+            float part[2], pv[2][RD];
+            int32_t lo[2], hi[2];
+            const uint32_t pbase = lds_prod + buf * kProdBytes + m * 4;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {                 // issue every LDS read of both outputs first
+                const uint32_t o = (wave + 8 * h) * 16 + m;
+                part[h] = *(lds_f32_t *)(uintptr_t)(lds_red + buf * kRedBytes + sub * 1024 + o * 4) +
+                          *(lds_f32_t *)(uintptr_t)(lds_red + buf * kRedBytes + (sub + 4) * 1024 + o * 4);
+                lo[h] = (h ? rp_cur.lo2 : rp_cur.lo1) - ob0;
+                hi[h] = min((h ? rp_cur.hi2 : rp_cur.hi1) - ob0, (int32_t)kProdEntries);
 #ifndef XFP_EXP_MFMA_NO_OUT
-            for (int32_t e = my_lo; e < my_hi; ++e) {
-                if (e < kProdEntries)
-                    s += *(lds_f32_t *)(uintptr_t)(lds_prod + buf * kProdBytes + (e * 16 + m) * 4);
-                else                                       // more than 512 entries in a tile: rare
-                    s = fmaf(half_bits_to_float(a.val[ob0 + e]), half_bits_to_float(xrow[a.col[ob0 + e]]), s);
-            }
+                // Unclamped: a read past the product buffer lands in LDS that is
+                // either allocated or out of range (reads as 0), and is masked below.
+                const uint32_t eb = pbase + (uint32_t)(lo[h] + (int32_t)sub) * 64;
+#pragma unroll
+                for (int j = 0; j < RD; ++j) pv[h][j] = *(lds_f32_t *)(uintptr_t)(eb + j * 256);
 #endif
-            if (n < N && m < (uint32_t)M) {
-                const int64_t o = (int64_t)m * a.y_stride + n;
-                if (y_f32) static_cast<float *>(a.y)[o] = s;
-                else static_cast<_Float16 *>(a.y)[o] = (_Float16)s;
+            }
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint32_t nl = wave + 8 * h, n = n0 + nl;
+                float s = part[h];
+#ifndef XFP_EXP_MFMA_NO_OUT
+#pragma unroll
+                for (int j = 0; j < RD; ++j) s += lo[h] + (int32_t)sub + 4 * j < hi[h] ? pv[h][j] : 0.f;
+                for (int32_t e = lo[h] + (int32_t)sub + 4 * RD; e < hi[h]; e += 4)          // long rows: rare
+                    s += *(lds_f32_t *)(uintptr_t)(pbase + e * 64);
+                const int32_t full_hi = (h ? rp_cur.hi2 : rp_cur.hi1) - ob0;
+                for (int32_t e = max(lo[h], (int32_t)kProdEntries) + (int32_t)sub; e < full_hi; e += 4)   // > 512 per tile: rare
+                    s = fmaf(half_bits_to_float(a.val[ob0 + e]), half_bits_to_float(xrow[a.col[ob0 + e]]), s);
+#endif
+                if (h == 0) XFP_STAMP(6); else XFP_STAMP(7);
+                s = dpp_add<0xB1>(s);                     // quad_perm [1,0,3,2]
+                s = dpp_add<0x4E>(s);                     // quad_perm [2,3,0,1]
+                if (sub == 0 && n < N && m < (uint32_t)M) {
+                    const int64_t oo = (int64_t)m * a.y_stride + n;
+                    if (y_f32) static_cast<float *>(a.y)[oo] = s;
+                    else static_cast<_Float16 *>(a.y)[oo] = (_Float16)s;
+                }
             }
         }
+        XFP_STAMP(5);
+        // rotate the pipelines
+        rp_cur = rp_nxt;
+        rp_nxt = rp_far;
+        ox0_c = ox0_n;
+        ox1_c = ox1_n;
     }
 }
 
