@@ -35,6 +35,9 @@ def parse_args():
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-graph", action="store_true", help="time eager launches instead of a graph")
     p.add_argument("--ring-bytes", type=int, default=RING_BYTES)
+    p.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
+                   help="instead of the benchmark, run xfp_probe_copy over MIB mebibytes 20 times "
+                        "(known traffic, used to scale the profiler's FETCH_SIZE / WRITE_SIZE)")
     return p.parse_args()
 
 
@@ -135,6 +138,16 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     xfp.load_library()
+
+    if args.calibrate_copy:
+        n = args.calibrate_copy << 20
+        src = torch.full((n,), 3, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(20):
+            xfp.xfp_probe_copy(src, dst)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes": n, "launches": 20, "kernel": "probe_copy_kernel"}))
+        return
 
     t0 = time.time()
     wl = build_workload(args.config, args.ring_bytes)
