@@ -66,14 +66,19 @@ __device__ __forceinline__ float fma_h(_Float16 c, _Float16 x, float acc)
     return __builtin_fmaf((float)c, (float)x, acc);     // v_fma_mix_f32
 }
 
-// Geometry of the per-row LDS table for each bit width.
+#ifndef XFP_B4_PAIR
+#define XFP_B4_PAIR 1
+#endif
+
+// Geometry of the per-row LDS table for each bit width.  A pair table maps two
+// adjacent indices (4, 6 or 8 stream bits) to two fp16 values in one dword.
 template <int BITS>
 struct TableFmt {
     static constexpr int kEntries = 1 << BITS;
-    static constexpr bool kPair = BITS != 4;
-    static constexpr int kRowBytes = kPair ? (4 << (2 * BITS)) : 2 * kEntries;   // 64, 256, 32
+    static constexpr bool kPair = BITS != 4 || XFP_B4_PAIR;
+    static constexpr int kRowBytes = kPair ? (4 << (2 * BITS)) : 2 * kEntries;   // 64, 256, 1024 (32 unpaired)
     static constexpr int kRawBytes = 2 * kEntries;                              // 8, 16, 32
-    static constexpr int kGroupsPerLaneLoad = BITS == 4 ? 4 : 2;                // groups of 8 lookups
+    static constexpr int kGroupsPerLaneLoad = kPair ? 2 : 4;                    // groups of 8 lookups
 };
 
 // Eight lookups of one lane-load: compute LDS addresses and issue the reads.
@@ -86,7 +91,15 @@ template <int BITS, bool BIASED>
 __device__ __forceinline__ void issue_group(const LaneWords<BITS> &lw, int g, uint32_t tb, uint32_t bias,
                                             uint32_t (&v)[8], uint32_t k1, uint32_t k2, uint32_t k3)
 {
-    if constexpr (BITS == 4) {
+    if constexpr (BITS == 4 && TableFmt<4>::kPair) {
+        // an index byte (two indices) selects one dword of the row's 256-entry pair table
+        const uint32_t ab = BIASED ? bias * TableFmt<4>::kRowBytes : 0u;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t a = byte_shl(lw.w[2 * g + (i >> 2)], i & 3, k2);   // byte * 4
+            v[i] = *(lds_u32_t *)(uintptr_t)(tb + (BIASED ? (a | ab) : a));
+        }
+    } else if constexpr (BITS == 4) {
         const uint32_t w = lw.w[g];
         uint32_t m0, m1;
         if constexpr (BIASED) {
@@ -141,7 +154,7 @@ __device__ __forceinline__ void issue_group(const LaneWords<BITS> &lw, int g, ui
 template <int BITS>
 __device__ __forceinline__ void consume_group(int g, const uint32_t (&v)[8], const uint32_t *xw, float (&acc)[4])
 {
-    if constexpr (BITS == 4) {
+    if constexpr (BITS == 4 && !TableFmt<4>::kPair) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const half2_t xp = as_half2(xw[g * 4 + j]);
@@ -164,7 +177,7 @@ struct StreamCfg {
 #ifdef XFP_EXP_U
     static constexpr int kUnroll = XFP_EXP_U;
 #else
-    static constexpr int kUnroll = RPC > 1 ? 4 : (NCH >= 8 ? 1 : (NCH >= 3 ? 2 : (NCH == 2 ? 4 : 8)));
+    static constexpr int kUnroll = RPC > 1 ? 2 : (NCH >= 5 ? 1 : (NCH >= 2 ? 2 : 4));
 #endif
     static constexpr int kBatchRows = kUnroll * RPC;           // rows a wave decodes at once
     static constexpr int kLanesPerRow = kWave / RPC;
@@ -237,8 +250,9 @@ __global__ __launch_bounds__(kWave, (StreamCfg<BITS, NCH, RPC>::kWavesPerSimd)) 
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (TAIL) {
         // the all-zero table that lanes past the end of the row look up
-        if (lane < Fmt::kRowBytes / 4)
-            *(lds_u32_w_t *)(uintptr_t)(lds_base + B * Fmt::kRowBytes + lane * 4) = 0u;
+#pragma unroll
+        for (int i = lane; i < Fmt::kRowBytes / 4; i += kWave)
+            *(lds_u32_w_t *)(uintptr_t)(lds_base + B * Fmt::kRowBytes + i * 4) = 0u;
     }
 
     for (uint32_t rb = row_begin; rb < row_end; rb += B) {
@@ -299,16 +313,27 @@ __global__ __launch_bounds__(kWave, (StreamCfg<BITS, NCH, RPC>::kWavesPerSimd)) 
                     *(lds_u32_w_t *)(uintptr_t)(lds_base + (i * kWave + lane) * 4) = cbv[i];
         } else {
             const uint32_t raw_base = lds_base + Cfg::kTableBytes;
-            if (lane < B * (ENT / 2)) *(lds_u32_w_t *)(uintptr_t)(raw_base + lane * 4) = cbv[0];
+#pragma unroll
+            for (int i = 0; i < CBW; ++i)
+                if (CBW * kWave == B * (ENT / 2) || i * kWave + lane < B * (ENT / 2))
+                    *(lds_u32_w_t *)(uintptr_t)(raw_base + (i * kWave + lane) * 4) = cbv[i];
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
-            constexpr int PE = 1 << (2 * BITS);                // pair entries per row (16 or 64)
-            if (PE == 64 || lane < PE) {
+            // entry e = (first index) | (second index) << BITS; this lane builds e = lane, lane+64, ...
+            constexpr int PE = 1 << (2 * BITS);                // pair entries per row (16, 64 or 256)
+            constexpr int PR = PE >= kWave ? PE / kWave : 1;
+            if (PE >= kWave || lane < PE) {
 #pragma unroll
                 for (int r = 0; r < B; ++r) {
-                    uint32_t lo = *(lds_u16_t *)(uintptr_t)(raw_base + r * Fmt::kRawBytes + (lane & (ENT - 1)) * 2);
-                    uint32_t hi = *(lds_u16_t *)(uintptr_t)(raw_base + r * Fmt::kRawBytes + (lane >> BITS) * 2);
-                    *(lds_u32_w_t *)(uintptr_t)(lds_base + r * Fmt::kRowBytes + lane * 4) = lo | (hi << 16);
+                    // 64 is a multiple of the codebook size, so the first index of every
+                    // entry this lane builds is the same
+                    const uint32_t lo = *(lds_u16_t *)(uintptr_t)(raw_base + r * Fmt::kRawBytes + (lane & (ENT - 1)) * 2);
+#pragma unroll
+                    for (int p = 0; p < PR; ++p) {
+                        const uint32_t e = lane + p * kWave;
+                        const uint32_t hi = *(lds_u16_t *)(uintptr_t)(raw_base + r * Fmt::kRawBytes + (e >> BITS) * 2);
+                        *(lds_u32_w_t *)(uintptr_t)(lds_base + r * Fmt::kRowBytes + e * 4) = lo | (hi << 16);
+                    }
                 }
             }
         }
