@@ -96,13 +96,13 @@ int decode(const xfp_weights *W, const int32_t *eids, int slots, const void *x, 
             c.y = static_cast<char *>(y) + (size_t)m0 * (size_t)ldy * ysz;
             const int mc = slots - m0 < 16 ? slots - m0 : 16;
             hipError_t err = mc >= 2 ? xfp::launch_decode_mfma(c, mc, y_dtype == XFP_F32, s)
-                                     : xfp::launch_decode_stream((int)W->bits, y_dtype == XFP_F32, c, 1, s);
+                                     : xfp::launch_decode_stream((int)W->bits, (int)W->mode, y_dtype == XFP_F32, c, 1, s);
             if (err != hipSuccess) return finish(err);
         }
         return XFP_OK;
     }
-    if (xfp::stream_supports((int)W->bits, (int)W->mode, W->K))
-        return finish(xfp::launch_decode_stream((int)W->bits, y_dtype == XFP_F32, a, slots, s));
+    if (xfp::stream_supports((int)W->bits, (int)W->mode, W->K, W->L))
+        return finish(xfp::launch_decode_stream((int)W->bits, (int)W->mode, y_dtype == XFP_F32, a, slots, s));
     a.rows_per_block = rows_per_block(W->N, slots);
     return finish(xfp::launch_decode_rows((int)W->bits, (int)W->mode, y_dtype == XFP_F32, a, slots, s));
 }

@@ -1,8 +1,12 @@
-// Streaming fused decode kernel for V2 (one codebook per output channel), M = 1
-// per slot.  This is the fast path for the shapes decode actually sees.
+// Streaming fused decode kernel, M = 1 per slot, V2 (one codebook per output
+// channel) and V2a (a library of codebooks plus one id per 128-weight group).
+// This is the fast path for the shapes decode actually sees.
 //
-// Work unit: one wave (a single-wave workgroup, so nothing ever waits at a
-// barrier) owns a run of output rows.  Design points, all for gfx950:
+// Work unit: one wave owns a run of output rows.  A workgroup is four such
+// waves that never wait for each other (V2: no barrier at all; V2a: one barrier
+// after the library's tables are built, once per workgroup); four waves per
+// workgroup only keep the number of workgroups the dispatcher has to place
+// low.  Design points, all for gfx950:
 //  - The activation row lives in VGPRs, not LDS: lane l always decodes the
 //    same k range of every row (32 consecutive k per 2048-wide chunk), so its
 //    32 activations per chunk are loaded once per wave and reused for every
@@ -15,8 +19,10 @@
 //  - Codebook lookups go to LDS.  4-bit: the row's 16 fp16 entries as they
 //    are (8 dwords = 8 banks, equal addresses broadcast, so no conflicts);
 //    the byte address of an entry is produced by one SDWA shift per index.
-//    3-bit / 2-bit: a pair table (two indices -> two fp16 in one dword) built
-//    per row, so one lookup and one v_dot2_f32_f16 serve two weights.
+//    A pair table (two indices -> two fp16 in one dword) is built per row
+//    (V2) or per library codebook (V2a, once per workgroup), so one lookup and
+//    one v_dot2_f32_f16 serve two weights.  V2a: the group's library id picks
+//    the table per lane; it is OR-ed into the lookup address.
 //  - Lookups are software-pipelined in groups of eight: the addresses and LDS
 //    reads of group t+1 are issued before the multiply-accumulates of group t.
 //  - fp32 accumulation in a fixed order, DPP reduction, no atomics: results
@@ -25,6 +31,8 @@
 //    one bounds-checked buffer load per lane while the index stream is still
 //    in flight and folded into the owning row's sum before the reduction.
 #include "xfp_device.h"
+
+#include <type_traits>
 
 namespace xfp {
 
@@ -87,7 +95,9 @@ struct TableFmt {
 //         tables to skip (row of a multi-row chunk, or the all-zero table for
 //         lanes past the end of a short row).  It is OR-ed into the index bytes
 //         (4-/2-bit) or the address (3-bit), which costs no extra instruction.
-template <int BITS, bool BIASED>
+//         WIDE: the selector may exceed 15 (a V2a library id); for 2-bit indices
+//         it is then OR-ed into the address instead of the index bytes.
+template <int BITS, bool BIASED, bool WIDE = false>
 __device__ __forceinline__ void issue_group(const LaneWords<BITS> &lw, int g, uint32_t tb, uint32_t bias,
                                             uint32_t (&v)[8], uint32_t k1, uint32_t k2, uint32_t k3)
 {
@@ -131,8 +141,9 @@ __device__ __forceinline__ void issue_group(const LaneWords<BITS> &lw, int g, ui
     } else {
         const uint32_t w = lw.w[g];
         uint32_t m0, m1;
+        const uint32_t ab = (BIASED && WIDE) ? bias * TableFmt<2>::kRowBytes : 0u;
         if constexpr (BIASED) {
-            const uint32_t bb = bias * 0x10101010u;
+            const uint32_t bb = WIDE ? 0u : bias * 0x10101010u;
             m0 = (w & 0x0F0F0F0Fu) | bb;
             m1 = ((w >> 4) & 0x0F0F0F0Fu) | bb;
         } else {
@@ -141,8 +152,9 @@ __device__ __forceinline__ void issue_group(const LaneWords<BITS> &lw, int g, ui
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const uint32_t a0 = byte_shl(m0, j, k2);                       // nibble (= pair) * 4
-            const uint32_t a1 = BIASED ? byte_shl(m1, j, k2) : byte_shr(m1, j, k2);
+            uint32_t a0 = byte_shl(m0, j, k2);                             // nibble (= pair) * 4
+            uint32_t a1 = BIASED ? byte_shl(m1, j, k2) : byte_shr(m1, j, k2);
+            if constexpr (BIASED && WIDE) { a0 |= ab; a1 |= ab; }
             v[2 * j] = *(lds_u32_t *)(uintptr_t)(tb + a0);
             v[2 * j + 1] = *(lds_u32_t *)(uintptr_t)(tb + a1);
         }
@@ -172,6 +184,9 @@ __device__ __forceinline__ void consume_group(int g, const uint32_t (&v)[8], con
 // RPC : rows per chunk (K == 2048 / RPC exactly) for short rows; then NCH == 1
 // TAIL: K is not a multiple of 2048 (RPC == 1): lanes past the row's end in the
 //       last chunk read a clamped address, zero activations and the zero table
+constexpr int kStreamWaves = 4;                                // waves per workgroup
+constexpr int kStreamThreads = kStreamWaves * kWave;
+
 template <int BITS, int NCH, int RPC>
 struct StreamCfg {
 #ifdef XFP_EXP_U
@@ -189,46 +204,80 @@ struct StreamCfg {
         RPC > 1 ? (BITS == 3 ? 4 : 3) : (kRegs <= 128 ? 4 : (kRegs <= 168 ? 3 : 2));
 };
 
-template <int BITS, int NCH, int RPC, bool TAIL>
-__global__ __launch_bounds__(kWave, (StreamCfg<BITS, NCH, RPC>::kWavesPerSimd)) void decode_stream_kernel(
+// MB: a wave owns more than one batch of rows; the index words of the next
+// batch are then loaded while the current one is decoded.
+template <int BITS, int NCH, int RPC, bool TAIL, int MODE, bool MB>
+__global__ __launch_bounds__(kStreamThreads, (StreamCfg<BITS, NCH, RPC>::kWavesPerSimd)) void decode_stream_kernel(
     DecodeArgs a, int y_f32)
 {
     using Cfg = StreamCfg<BITS, NCH, RPC>;
     using Fmt = TableFmt<BITS>;
+    static_assert(Fmt::kPair, "pair tables only");
     constexpr int U = Cfg::kUnroll, B = Cfg::kBatchRows, LPR = Cfg::kLanesPerRow;
     constexpr int ENT = Fmt::kEntries, GPL = Fmt::kGroupsPerLaneLoad;
-    __shared__ __align__(16) unsigned char lds[Cfg::kTableBytes + Cfg::kRawBytes + 16];
-    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
+    constexpr int kWaveLds = Cfg::kTableBytes + Cfg::kRawBytes;    // V2: private to a wave
+    constexpr int NBUF = MB ? 2 : 1;
+    extern __shared__ __align__(16) unsigned char lds[];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
 
-    const uint32_t lane = threadIdx.x;
+    const uint32_t lane = threadIdx.x & (kWave - 1);
+    const uint32_t wv = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const uint32_t lds_base = MODE == 0 ? lds0 + wv * kWaveLds : lds0;
     const uint32_t seg = RPC > 1 ? lane / LPR : 0u;            // which row of a chunk this lane is in
     const uint32_t lis = RPC > 1 ? lane % LPR : lane;          // lane within its row
     const uint32_t slot = blockIdx.y;
     const uint32_t e = a.eids ? (uint32_t)a.eids[slot] : 0u;
     const uint32_t N = a.N, K = a.K;
     const uint32_t wpr = K / 32 * BITS;
+    const uint32_t G = K / kGroup;
     const uint32_t *idx = a.idx + (size_t)e * N * wpr;
-    const uint32_t *cbw = reinterpret_cast<const uint32_t *>(a.cb) + (size_t)e * N * (ENT / 2);
+    const uint32_t *cbw = reinterpret_cast<const uint32_t *>(a.cb) + (size_t)e * (MODE == 0 ? N : a.L) * (ENT / 2);
+    const uint8_t *gid = MODE == 1 ? a.gid + (size_t)e * N * G : nullptr;
     const int32_t *rp = a.rp + (size_t)e * N;
     const uint16_t *x = a.x + (int64_t)slot * a.x_stride;
 
     const bool live_last = !TAIL || ((NCH - 1) * kWave + lis) * kLaneWeights < K;
     const uint32_t unit_last = live_last ? (NCH - 1) * kWave + lis : 0u;
 
-    const uint32_t row_begin = blockIdx.x * a.rows_per_block;
+    // Rows of this wave.  A wave past the end of the matrix still runs the
+    // prologue (every address below is clamped into the matrix) and leaves
+    // before the row loop.
+    const uint32_t row_begin = (blockIdx.x * kStreamWaves + wv) * a.rows_per_block;
     const uint32_t row_end = min(N, row_begin + a.rows_per_block);
-    const uint32_t cb_last = row_end * (ENT / 2) - 1;          // last valid codebook dword
+    const uint32_t cb_last = min(N, max(row_end, 1u)) * (ENT / 2) - 1;   // last valid codebook dword
     const uint32_t k1 = 1, k2 = 2, k3 = 3;
     constexpr int CBW = (B * (ENT / 2) + kWave - 1) / kWave;   // codebook dwords per lane per batch
+
+    // a3: the index words (and V2a library ids) of one batch of rows; rows past
+    // the end are clamped to the last row and never stored.  `on` false: every
+    // lane reads the first word of the matrix instead (a batch that does not exist).
+    LaneWords<BITS> lw[NBUF][U][NCH];
+    uint32_t lib[NBUF][MODE == 1 ? U : 1][MODE == 1 ? NCH : 1];
+    auto load_batch = [&](auto buf, uint32_t rb, bool on) {
+        constexpr int Q = decltype(buf)::value;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t row = min(rb + u * RPC + seg, N - 1);
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                const uint32_t unit = c == NCH - 1 ? unit_last : c * kWave + lis;
+                lw[Q][u][c] = load_lane_words<BITS>(idx + (on ? (size_t)row * wpr + (size_t)unit * BITS : 0));
+                if constexpr (MODE == 1)
+                    lib[Q][u][c] = gid[on ? (size_t)row * G + unit / (kGroup / kLaneWeights) : 0];
+            }
+        }
+    };
 
     // Vector loads complete in issue order, so the order below is the order in
     // which their consumers can start: row pointers (they gate the outlier
     // loads), codebooks (they gate the first lookup), activations, index words.
     // Lanes 0..B hold rp[rb + lane]: the CSR boundaries of the batch.
-    int32_t rpv = rp[min(row_begin + lane, row_end)];
+    int32_t rpv = rp[min(row_begin + lane, N)];
     uint32_t cbv[CBW];
+    if constexpr (MODE == 0) {
 #pragma unroll
-    for (int i = 0; i < CBW; ++i) cbv[i] = cbw[min(row_begin * (ENT / 2) + i * kWave + lane, cb_last)];
+        for (int i = 0; i < CBW; ++i) cbv[i] = cbw[min(row_begin * (ENT / 2) + i * kWave + lane, cb_last)];
+    }
     __builtin_amdgcn_sched_barrier(0);
 
     // a1: this lane's activations, once per wave.
@@ -239,38 +288,47 @@ __global__ __launch_bounds__(kWave, (StreamCfg<BITS, NCH, RPC>::kWavesPerSimd)) 
         const uint4 *xp = reinterpret_cast<const uint4 *>(x + (size_t)unit * kLaneWeights);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-#ifdef XFP_EXP_NO_X
-            uint4 v = make_uint4(lane + i, lane, 0x3c003c00u, lane * (uint32_t)(uintptr_t)xp);
-#else
             uint4 v = xp[i];
-#endif
             xr[c][4 * i] = v.x; xr[c][4 * i + 1] = v.y; xr[c][4 * i + 2] = v.z; xr[c][4 * i + 3] = v.w;
         }
     }
     __builtin_amdgcn_sched_barrier(0);
-    if constexpr (TAIL) {
+    load_batch(std::integral_constant<int, 0>{}, row_begin, true);
+    __builtin_amdgcn_sched_barrier(0);
+
+    if constexpr (MODE == 1) {
+        // a2 (V2a): the library's pair tables, once per workgroup, while the first
+        // loads are in flight.  Table l sits at l * kRowBytes; table L is all zero
+        // (lanes past the end of a short row).
+        const uint32_t L = a.L;
+        const uint32_t raw_base = lds0 + (L + 1) * Fmt::kRowBytes;
+        for (uint32_t i = threadIdx.x; i < L * (ENT / 2); i += kStreamThreads)
+            *(lds_u32_w_t *)(uintptr_t)(raw_base + i * 4) = cbw[i];
+        __syncthreads();
+        constexpr uint32_t PE = 1u << (2 * BITS);              // pair entries per table
+        for (uint32_t i = threadIdx.x; i < (L + 1) * PE; i += kStreamThreads) {
+            const uint32_t l = i / PE, pe = i % PE;
+            uint32_t v = 0u;
+            if (l < L) {
+                const uint32_t lo = *(lds_u16_t *)(uintptr_t)(raw_base + (l * ENT + (pe & (ENT - 1))) * 2);
+                const uint32_t hi = *(lds_u16_t *)(uintptr_t)(raw_base + (l * ENT + (pe >> BITS)) * 2);
+                v = lo | (hi << 16);
+            }
+            *(lds_u32_w_t *)(uintptr_t)(lds0 + i * 4) = v;
+        }
+        __syncthreads();
+    } else if constexpr (TAIL) {
         // the all-zero table that lanes past the end of the row look up
 #pragma unroll
         for (int i = lane; i < Fmt::kRowBytes / 4; i += kWave)
             *(lds_u32_w_t *)(uintptr_t)(lds_base + B * Fmt::kRowBytes + i * 4) = 0u;
     }
+    if (row_begin >= N) return;
 
-    for (uint32_t rb = row_begin; rb < row_end; rb += B) {
-        // a3: issue every index load of the batch (rows past the end are clamped
-        // to the last row and never stored).
-        LaneWords<BITS> lw[U][NCH];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint32_t row = min(rb + u * RPC + seg, row_end - 1);
-            const uint32_t *rw = idx + (size_t)row * wpr;
-#pragma unroll
-            for (int c = 0; c < NCH; ++c) {
-                const uint32_t unit = c == NCH - 1 ? unit_last : c * kWave + lis;
-                lw[u][c] = load_lane_words<BITS>(rw + (size_t)unit * BITS);
-            }
-        }
-        __builtin_amdgcn_sched_barrier(0);
-
+    // One batch of rows.  CUR: register set of its index words; in MB kernels
+    // the other set receives the next batch.
+    auto pass = [&](auto cur, uint32_t rb) {
+        constexpr int CUR = decltype(cur)::value;
         // a7 (issue): the CSR entries of the batch are contiguous.  Each lane
         // takes one entry per row group through a bounds-checked buffer load
         // (offsets past the end read as zero): no loop, no branch.
@@ -303,15 +361,16 @@ __global__ __launch_bounds__(kWave, (StreamCfg<BITS, NCH, RPC>::kWavesPerSimd)) 
             }
         }
         __builtin_amdgcn_sched_barrier(0);
+        // a3 (next batch): unconditional, so that the waits below stay partial
+        const bool more = MB && rb + B < row_end;
+        if constexpr (MB) {
+            load_batch(std::integral_constant<int, CUR ^ 1>{}, rb + B, more);
+            __builtin_amdgcn_sched_barrier(0);
+        }
 
-        // a2: codebooks of the batch -> LDS tables.
-        __builtin_amdgcn_wave_barrier();
-        if constexpr (!Fmt::kPair) {
-#pragma unroll
-            for (int i = 0; i < CBW; ++i)
-                if (CBW * kWave == B * (ENT / 2) || i * kWave + lane < B * (ENT / 2))
-                    *(lds_u32_w_t *)(uintptr_t)(lds_base + (i * kWave + lane) * 4) = cbv[i];
-        } else {
+        // a2 (V2): codebooks of the batch -> LDS tables.
+        if constexpr (MODE == 0) {
+            __builtin_amdgcn_wave_barrier();
             const uint32_t raw_base = lds_base + Cfg::kTableBytes;
 #pragma unroll
             for (int i = 0; i < CBW; ++i)
@@ -336,15 +395,18 @@ __global__ __launch_bounds__(kWave, (StreamCfg<BITS, NCH, RPC>::kWavesPerSimd)) 
                     }
                 }
             }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
         // next batch's row pointers and codebooks: issued now, consumed next pass
-        if (rb + B < row_end) {
-            rpv = rp[min(rb + B + lane, row_end)];
+        if constexpr (MB) {
+            const uint32_t rn = more ? rb + B : rb;
+            rpv = rp[min(rn + lane, N)];
+            if constexpr (MODE == 0) {
 #pragma unroll
-            for (int i = 0; i < CBW; ++i)
-                cbv[i] = cbw[min((rb + B) * (ENT / 2) + i * kWave + lane, cb_last)];
+                for (int i = 0; i < CBW; ++i)
+                    cbv[i] = cbw[min(rn * (ENT / 2) + i * kWave + lane, cb_last)];
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
 
@@ -361,17 +423,7 @@ __global__ __launch_bounds__(kWave, (StreamCfg<BITS, NCH, RPC>::kWavesPerSimd)) 
         // a4-a6: depack, gather, multiply-accumulate, software-pipelined over
         // groups of eight lookups: task t = (row u, chunk c, group g).
         float sum[U];
-#ifdef XFP_EXP_NO_COMPUTE
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            float accx[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int c = 0; c < NCH; ++c)
-#pragma unroll
-                for (int i = 0; i < BITS; ++i) accx[i & 3] += __builtin_bit_cast(float, lw[u][c].w[i] & xr[c][i]);
-            sum[u] = (accx[0] + accx[1]) + (accx[2] + accx[3]);
-        }
-#else
+        uint16_t oxv[OV];
         {
             constexpr int TPR = NCH * GPL;                     // tasks per row
             constexpr int NT = U * TPR;
@@ -380,18 +432,27 @@ __global__ __launch_bounds__(kWave, (StreamCfg<BITS, NCH, RPC>::kWavesPerSimd)) 
             auto issue = [&](int t, uint32_t (&v)[8]) {
                 const int u = t / TPR, c = (t % TPR) / GPL, g = t % GPL;
                 const uint32_t tb = lds_base + u * RPC * Fmt::kRowBytes;
-                if (RPC > 1)
-                    issue_group<BITS, true>(lw[u][c], g, tb, seg, v, k1, k2, k3);
+                if constexpr (MODE == 1) {
+                    const uint32_t dead = TAIL && c == NCH - 1 && !live_last;
+                    issue_group<BITS, true, true>(lw[CUR][u][c], g, lds_base, dead ? a.L : lib[CUR][u][c], v, k1, k2, k3);
+                } else if (RPC > 1)
+                    issue_group<BITS, true>(lw[CUR][u][c], g, tb, seg, v, k1, k2, k3);
                 else if (TAIL && c == NCH - 1)
-                    issue_group<BITS, true>(lw[u][c], g, tb, live_last ? 0u : (uint32_t)(B - u), v, k1, k2, k3);
+                    issue_group<BITS, true>(lw[CUR][u][c], g, tb, live_last ? 0u : (uint32_t)(B - u), v, k1, k2, k3);
                 else
-                    issue_group<BITS, false>(lw[u][c], g, tb, 0u, v, k1, k2, k3);
+                    issue_group<BITS, false>(lw[CUR][u][c], g, tb, 0u, v, k1, k2, k3);
             };
             issue(0, val[0]);
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
                 const int u = t / TPR, c = (t % TPR) / GPL, g = t % GPL;
                 if (t + 1 < NT) issue(t + 1, val[(t + 1) & 1]);
+                if (t == NT / 2) {
+                    // a7 (gather): x at the outlier columns; col arrived with the index
+                    // words, the values are needed after the last multiply-accumulate
+#pragma unroll
+                    for (int v = 0; v < OV; ++v) oxv[v] = x[ocol[v]];
+                }
                 __builtin_amdgcn_sched_barrier(0);
                 consume_group<BITS>(g, val[t & 1], xr[c], acc);
                 if (t % TPR == TPR - 1) {                      // row finished
@@ -401,15 +462,9 @@ __global__ __launch_bounds__(kWave, (StreamCfg<BITS, NCH, RPC>::kWavesPerSimd)) 
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-#endif
 
-        // a7 (fold): gather x at the outlier columns and add each product to the
-        // row that owns the entry.
-#ifndef XFP_EXP_NO_OUTLIERS
+        // a7 (fold): add each outlier product to the row that owns the entry.
         {
-            uint16_t oxv[OV];
-#pragma unroll
-            for (int v = 0; v < OV; ++v) oxv[v] = x[ocol[v]];
             if constexpr (RPC == 1) {
                 const float p = half_bits_to_float((uint16_t)oval[0]) * half_bits_to_float(oxv[0]);
 #pragma unroll
@@ -432,7 +487,6 @@ __global__ __launch_bounds__(kWave, (StreamCfg<BITS, NCH, RPC>::kWavesPerSimd)) 
                 }
             }
         }
-#endif
         // a8: reduce and store.
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -444,60 +498,95 @@ __global__ __launch_bounds__(kWave, (StreamCfg<BITS, NCH, RPC>::kWavesPerSimd)) 
                 else static_cast<_Float16 *>(a.y)[o] = (_Float16)t;
             }
         }
+    };
+
+    if constexpr (!MB) {
+        pass(std::integral_constant<int, 0>{}, row_begin);
+    } else {
+        for (uint32_t rb = row_begin;;) {
+            pass(std::integral_constant<int, 0>{}, rb);
+            rb += B;
+            if (rb >= row_end) break;
+            pass(std::integral_constant<int, 1>{}, rb);
+            rb += B;
+            if (rb >= row_end) break;
+        }
     }
 }
 
 // rows per wave: a multiple of the batch, sized so that the grid is a few
 // thousand waves (about 16 per CU) when the problem is large enough.
-template <int BITS, int NCH, int RPC, bool TAIL>
+template <int BITS, int NCH, int RPC, bool TAIL, int MODE>
 static hipError_t launch_stream_t(DecodeArgs a, int slots, bool y_f32, hipStream_t s)
 {
-    constexpr int B = StreamCfg<BITS, NCH, RPC>::kBatchRows;
+    using Cfg = StreamCfg<BITS, NCH, RPC>;
+    using Fmt = TableFmt<BITS>;
+    constexpr int B = Cfg::kBatchRows;
     const uint64_t total_rows = (uint64_t)a.N * slots;
     uint32_t rpw = B;
     while ((total_rows + rpw - 1) / rpw > 6144 && rpw < 64 * B) rpw += B;
     a.rows_per_block = rpw;
-    dim3 grid((a.N + rpw - 1) / rpw, slots);
-    hipLaunchKernelGGL((decode_stream_kernel<BITS, NCH, RPC, TAIL>), grid, dim3(kWave), 0, s, a, (int)y_f32);
+    const uint32_t waves = (a.N + rpw - 1) / rpw;
+    const size_t smem = MODE == 0 ? (size_t)kStreamWaves * (Cfg::kTableBytes + Cfg::kRawBytes)
+                                  : (size_t)(a.L + 1) * Fmt::kRowBytes + (size_t)a.L * Fmt::kRawBytes;
+    auto kern = rpw > (uint32_t)B ? decode_stream_kernel<BITS, NCH, RPC, TAIL, MODE, true>
+                                  : decode_stream_kernel<BITS, NCH, RPC, TAIL, MODE, false>;
+    if (smem > 48 * 1024) {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (err != hipSuccess) return err;
+    }
+    dim3 grid((waves + kStreamWaves - 1) / kStreamWaves, slots);
+    hipLaunchKernelGGL(kern, grid, dim3(kStreamThreads), smem, s, a, (int)y_f32);
     return hipGetLastError();
 }
 
-template <int BITS, int NCH>
-static hipError_t launch_stream_n(const DecodeArgs &a, int slots, bool y_f32, hipStream_t s)
+template <int BITS, int NCH, int RPC, bool TAIL>
+static hipError_t launch_stream_m(const DecodeArgs &a, int mode, int slots, bool y_f32, hipStream_t s)
 {
-    if (a.K % 2048 == 0) return launch_stream_t<BITS, NCH, 1, false>(a, slots, y_f32, s);
-    return launch_stream_t<BITS, NCH, 1, true>(a, slots, y_f32, s);
+    if (mode == 0) return launch_stream_t<BITS, NCH, RPC, TAIL, 0>(a, slots, y_f32, s);
+    return launch_stream_t<BITS, NCH, RPC, TAIL, 1>(a, slots, y_f32, s);
+}
+
+template <int BITS, int NCH>
+static hipError_t launch_stream_n(const DecodeArgs &a, int mode, int slots, bool y_f32, hipStream_t s)
+{
+    if (a.K % 2048 == 0) return launch_stream_m<BITS, NCH, 1, false>(a, mode, slots, y_f32, s);
+    return launch_stream_m<BITS, NCH, 1, true>(a, mode, slots, y_f32, s);
 }
 
 template <int BITS>
-static hipError_t launch_stream_b(const DecodeArgs &a, int slots, bool y_f32, hipStream_t s)
+static hipError_t launch_stream_b(const DecodeArgs &a, int mode, int slots, bool y_f32, hipStream_t s)
 {
     const uint32_t K = a.K;
-    if (K == 1024) return launch_stream_t<BITS, 1, 2, false>(a, slots, y_f32, s);
-    if (K == 512) return launch_stream_t<BITS, 1, 4, false>(a, slots, y_f32, s);
+    if (K == 1024) return launch_stream_m<BITS, 1, 2, false>(a, mode, slots, y_f32, s);
+    if (K == 512) return launch_stream_m<BITS, 1, 4, false>(a, mode, slots, y_f32, s);
     switch ((K + 2047) / 2048) {
-    case 1: return launch_stream_n<BITS, 1>(a, slots, y_f32, s);
-    case 2: return launch_stream_n<BITS, 2>(a, slots, y_f32, s);
-    case 3: return launch_stream_n<BITS, 3>(a, slots, y_f32, s);
-    case 4: return launch_stream_n<BITS, 4>(a, slots, y_f32, s);
-    case 5: return launch_stream_n<BITS, 5>(a, slots, y_f32, s);
-    case 6: return launch_stream_n<BITS, 6>(a, slots, y_f32, s);
-    case 7: return launch_stream_n<BITS, 7>(a, slots, y_f32, s);
-    default: return launch_stream_n<BITS, 8>(a, slots, y_f32, s);
+    case 1: return launch_stream_n<BITS, 1>(a, mode, slots, y_f32, s);
+    case 2: return launch_stream_n<BITS, 2>(a, mode, slots, y_f32, s);
+    case 3: return launch_stream_n<BITS, 3>(a, mode, slots, y_f32, s);
+    case 4: return launch_stream_n<BITS, 4>(a, mode, slots, y_f32, s);
+    case 5: return launch_stream_n<BITS, 5>(a, mode, slots, y_f32, s);
+    case 6: return launch_stream_n<BITS, 6>(a, mode, slots, y_f32, s);
+    case 7: return launch_stream_n<BITS, 7>(a, mode, slots, y_f32, s);
+    default: return launch_stream_n<BITS, 8>(a, mode, slots, y_f32, s);
     }
 }
 
-bool stream_supports(int bits, int mode, uint32_t K)
+// V2a needs the library's pair tables in LDS: (L + 1) tables of 64 B / 256 B / 1 KB.
+bool stream_supports(int bits, int mode, uint32_t K, uint32_t L)
 {
-    return mode == 0 && bits >= 2 && bits <= 4 && K <= 8 * 2048;
+    if (bits < 2 || bits > 4 || K > 8 * 2048) return false;
+    if (mode == 0) return true;
+    return mode == 1 && (size_t)(L + 1) * (4u << (2 * bits)) + (size_t)L * (2u << bits) <= 64 * 1024;
 }
 
-hipError_t launch_decode_stream(int bits, bool y_f32, const DecodeArgs &a, int slots, hipStream_t s)
+hipError_t launch_decode_stream(int bits, int mode, bool y_f32, const DecodeArgs &a, int slots, hipStream_t s)
 {
     switch (bits) {
-    case 2: return launch_stream_b<2>(a, slots, y_f32, s);
-    case 3: return launch_stream_b<3>(a, slots, y_f32, s);
-    default: return launch_stream_b<4>(a, slots, y_f32, s);
+    case 2: return launch_stream_b<2>(a, mode, slots, y_f32, s);
+    case 3: return launch_stream_b<3>(a, mode, slots, y_f32, s);
+    default: return launch_stream_b<4>(a, mode, slots, y_f32, s);
     }
 }
 

@@ -30,9 +30,10 @@ struct DecodeArgs {
 // Launchers, one per kernel family (defined in the .hip files).
 hipError_t launch_decode_rows(int bits, int mode, bool y_f32, const DecodeArgs &a, int slots,
                               hipStream_t s);
-// Streaming kernel (V2, K <= 16384): x in registers, codebooks in LDS.
-bool stream_supports(int bits, int mode, uint32_t K);
-hipError_t launch_decode_stream(int bits, bool y_f32, const DecodeArgs &a, int slots, hipStream_t s);
+// Streaming kernel (K <= 16384; V2, or V2a whose library tables fit in LDS): x in
+// registers, pair tables in LDS.
+bool stream_supports(int bits, int mode, uint32_t K, uint32_t L);
+hipError_t launch_decode_stream(int bits, int mode, bool y_f32, const DecodeArgs &a, int slots, hipStream_t s);
 // Matrix-core kernel for 2..16 tokens per launch (V2, 4-bit, K % 1024 == 0, K <= 8192).
 bool mfma_supports(int bits, int mode, uint32_t K, int M);
 hipError_t launch_decode_mfma(const DecodeArgs &a, int M, bool y_f32, hipStream_t s);
