@@ -2,11 +2,11 @@
 // channel) and V2a (a library of codebooks plus one id per 128-weight group).
 // This is the fast path for the shapes decode actually sees.
 //
-// Work unit: one wave owns a run of output rows.  A workgroup is four such
-// waves that never wait for each other (V2: no barrier at all; V2a: one barrier
-// after the library's tables are built, once per workgroup); four waves per
-// workgroup only keep the number of workgroups the dispatcher has to place
-// low.  Design points, all for gfx950:
+// Work unit: one wave owns a run of output rows.  V2: a workgroup is a single
+// wave, so nothing ever waits at a barrier and every LDS address is a
+// compile-time constant that folds into the lookups' offset field.  V2a: a
+// workgroup is four waves that share the library's tables (one barrier after
+// they are built, none afterwards).  Design points, all for gfx950:
 //  - The activation row lives in VGPRs, not LDS: lane l always decodes the
 //    same k range of every row (32 consecutive k per 2048-wide chunk), so its
 //    32 activations per chunk are loaded once per wave and reused for every
@@ -184,8 +184,7 @@ __device__ __forceinline__ void consume_group(int g, const uint32_t (&v)[8], con
 // RPC : rows per chunk (K == 2048 / RPC exactly) for short rows; then NCH == 1
 // TAIL: K is not a multiple of 2048 (RPC == 1): lanes past the row's end in the
 //       last chunk read a clamped address, zero activations and the zero table
-constexpr int kStreamWaves = 4;                                // waves per workgroup
-constexpr int kStreamThreads = kStreamWaves * kWave;
+constexpr int stream_waves(int mode) { return mode == 0 ? 1 : 4; }   // waves per workgroup
 
 template <int BITS, int NCH, int RPC>
 struct StreamCfg {
@@ -204,25 +203,38 @@ struct StreamCfg {
         RPC > 1 ? (BITS == 3 ? 4 : 3) : (kRegs <= 128 ? 4 : (kRegs <= 168 ? 3 : 2));
 };
 
-// MB: a wave owns more than one batch of rows; the index words of the next
-// batch are then loaded while the current one is decoded.
-template <int BITS, int NCH, int RPC, bool TAIL, int MODE, bool MB>
-__global__ __launch_bounds__(kStreamThreads, (StreamCfg<BITS, NCH, RPC>::kWavesPerSimd)) void decode_stream_kernel(
-    DecodeArgs a, int y_f32)
+// LDS byte address of a static array of BYTES bytes (one per instantiation).
+template <int BYTES>
+__device__ __forceinline__ uint32_t static_lds()
 {
+    __shared__ __align__(16) unsigned char buf[BYTES];
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)buf;
+}
+
+template <int BITS, int NCH, int RPC, bool TAIL, int MODE>
+__global__ __launch_bounds__(stream_waves(MODE) * kWave, (StreamCfg<BITS, NCH, RPC>::kWavesPerSimd))
+void decode_stream_kernel(DecodeArgs a, int y_f32)
+{
+    constexpr int kStreamWaves = stream_waves(MODE), kStreamThreads = kStreamWaves * kWave;
     using Cfg = StreamCfg<BITS, NCH, RPC>;
     using Fmt = TableFmt<BITS>;
     static_assert(Fmt::kPair, "pair tables only");
     constexpr int U = Cfg::kUnroll, B = Cfg::kBatchRows, LPR = Cfg::kLanesPerRow;
     constexpr int ENT = Fmt::kEntries, GPL = Fmt::kGroupsPerLaneLoad;
-    constexpr int kWaveLds = Cfg::kTableBytes + Cfg::kRawBytes;    // V2: private to a wave
-    constexpr int NBUF = MB ? 2 : 1;
-    extern __shared__ __align__(16) unsigned char lds[];
-    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
+    // V2: the wave's tables, a static array.  V2a: the library's tables fill the
+    // dynamic segment, which starts at LDS address 0 because this instantiation
+    // has no static LDS; a constant base keeps the lookups free of address adds.
+    uint32_t lds_base = 0u;
+    if constexpr (MODE == 0) {
+        lds_base = static_lds<Cfg::kTableBytes + Cfg::kRawBytes + 16>();
+    } else {
+        extern __shared__ __align__(16) unsigned char lds_dyn[];
+        if ((uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds_dyn != 0u) return;
+    }
+    const uint32_t lds0 = lds_base;
 
     const uint32_t lane = threadIdx.x & (kWave - 1);
     const uint32_t wv = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    const uint32_t lds_base = MODE == 0 ? lds0 + wv * kWaveLds : lds0;
     const uint32_t seg = RPC > 1 ? lane / LPR : 0u;            // which row of a chunk this lane is in
     const uint32_t lis = RPC > 1 ? lane % LPR : lane;          // lane within its row
     const uint32_t slot = blockIdx.y;
@@ -249,21 +261,18 @@ __global__ __launch_bounds__(kStreamThreads, (StreamCfg<BITS, NCH, RPC>::kWavesP
     constexpr int CBW = (B * (ENT / 2) + kWave - 1) / kWave;   // codebook dwords per lane per batch
 
     // a3: the index words (and V2a library ids) of one batch of rows; rows past
-    // the end are clamped to the last row and never stored.  `on` false: every
-    // lane reads the first word of the matrix instead (a batch that does not exist).
-    LaneWords<BITS> lw[NBUF][U][NCH];
-    uint32_t lib[NBUF][MODE == 1 ? U : 1][MODE == 1 ? NCH : 1];
-    auto load_batch = [&](auto buf, uint32_t rb, bool on) {
-        constexpr int Q = decltype(buf)::value;
+    // the end are clamped to the last row and never stored.
+    LaneWords<BITS> lw[U][NCH];
+    uint32_t lib[MODE == 1 ? U : 1][MODE == 1 ? NCH : 1];
+    auto load_batch = [&](uint32_t rb) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const uint32_t row = min(rb + u * RPC + seg, N - 1);
 #pragma unroll
             for (int c = 0; c < NCH; ++c) {
                 const uint32_t unit = c == NCH - 1 ? unit_last : c * kWave + lis;
-                lw[Q][u][c] = load_lane_words<BITS>(idx + (on ? (size_t)row * wpr + (size_t)unit * BITS : 0));
-                if constexpr (MODE == 1)
-                    lib[Q][u][c] = gid[on ? (size_t)row * G + unit / (kGroup / kLaneWeights) : 0];
+                lw[u][c] = load_lane_words<BITS>(idx + (size_t)row * wpr + (size_t)unit * BITS);
+                if constexpr (MODE == 1) lib[u][c] = gid[(size_t)row * G + unit / (kGroup / kLaneWeights)];
             }
         }
     };
@@ -293,7 +302,7 @@ __global__ __launch_bounds__(kStreamThreads, (StreamCfg<BITS, NCH, RPC>::kWavesP
         }
     }
     __builtin_amdgcn_sched_barrier(0);
-    load_batch(std::integral_constant<int, 0>{}, row_begin, true);
+    load_batch(row_begin);
     __builtin_amdgcn_sched_barrier(0);
 
     if constexpr (MODE == 1) {
@@ -325,10 +334,12 @@ __global__ __launch_bounds__(kStreamThreads, (StreamCfg<BITS, NCH, RPC>::kWavesP
     }
     if (row_begin >= N) return;
 
-    // One batch of rows.  CUR: register set of its index words; in MB kernels
-    // the other set receives the next batch.
-    auto pass = [&](auto cur, uint32_t rb) {
-        constexpr int CUR = decltype(cur)::value;
+    // One batch of rows.  FIRST: its index words were loaded in the prologue.
+    auto pass = [&](auto first, uint32_t rb) {
+        if constexpr (!decltype(first)::value) {
+            load_batch(rb);
+            __builtin_amdgcn_sched_barrier(0);
+        }
         // a7 (issue): the CSR entries of the batch are contiguous.  Each lane
         // takes one entry per row group through a bounds-checked buffer load
         // (offsets past the end read as zero): no loop, no branch.
@@ -361,12 +372,6 @@ __global__ __launch_bounds__(kStreamThreads, (StreamCfg<BITS, NCH, RPC>::kWavesP
             }
         }
         __builtin_amdgcn_sched_barrier(0);
-        // a3 (next batch): unconditional, so that the waits below stay partial
-        const bool more = MB && rb + B < row_end;
-        if constexpr (MB) {
-            load_batch(std::integral_constant<int, CUR ^ 1>{}, rb + B, more);
-            __builtin_amdgcn_sched_barrier(0);
-        }
 
         // a2 (V2): codebooks of the batch -> LDS tables.
         if constexpr (MODE == 0) {
@@ -399,13 +404,12 @@ __global__ __launch_bounds__(kStreamThreads, (StreamCfg<BITS, NCH, RPC>::kWavesP
             __builtin_amdgcn_wave_barrier();
         }
         // next batch's row pointers and codebooks: issued now, consumed next pass
-        if constexpr (MB) {
-            const uint32_t rn = more ? rb + B : rb;
-            rpv = rp[min(rn + lane, N)];
+        if (rb + B < row_end) {
+            rpv = rp[min(rb + B + lane, N)];
             if constexpr (MODE == 0) {
 #pragma unroll
                 for (int i = 0; i < CBW; ++i)
-                    cbv[i] = cbw[min(rn * (ENT / 2) + i * kWave + lane, cb_last)];
+                    cbv[i] = cbw[min((rb + B) * (ENT / 2) + i * kWave + lane, cb_last)];
             }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -434,13 +438,13 @@ __global__ __launch_bounds__(kStreamThreads, (StreamCfg<BITS, NCH, RPC>::kWavesP
                 const uint32_t tb = lds_base + u * RPC * Fmt::kRowBytes;
                 if constexpr (MODE == 1) {
                     const uint32_t dead = TAIL && c == NCH - 1 && !live_last;
-                    issue_group<BITS, true, true>(lw[CUR][u][c], g, lds_base, dead ? a.L : lib[CUR][u][c], v, k1, k2, k3);
+                    issue_group<BITS, true, true>(lw[u][c], g, lds_base, dead ? a.L : lib[u][c], v, k1, k2, k3);
                 } else if (RPC > 1)
-                    issue_group<BITS, true>(lw[CUR][u][c], g, tb, seg, v, k1, k2, k3);
+                    issue_group<BITS, true>(lw[u][c], g, tb, seg, v, k1, k2, k3);
                 else if (TAIL && c == NCH - 1)
-                    issue_group<BITS, true>(lw[CUR][u][c], g, tb, live_last ? 0u : (uint32_t)(B - u), v, k1, k2, k3);
+                    issue_group<BITS, true>(lw[u][c], g, tb, live_last ? 0u : (uint32_t)(B - u), v, k1, k2, k3);
                 else
-                    issue_group<BITS, false>(lw[CUR][u][c], g, tb, 0u, v, k1, k2, k3);
+                    issue_group<BITS, false>(lw[u][c], g, tb, 0u, v, k1, k2, k3);
             };
             issue(0, val[0]);
 #pragma unroll
@@ -500,18 +504,8 @@ __global__ __launch_bounds__(kStreamThreads, (StreamCfg<BITS, NCH, RPC>::kWavesP
         }
     };
 
-    if constexpr (!MB) {
-        pass(std::integral_constant<int, 0>{}, row_begin);
-    } else {
-        for (uint32_t rb = row_begin;;) {
-            pass(std::integral_constant<int, 0>{}, rb);
-            rb += B;
-            if (rb >= row_end) break;
-            pass(std::integral_constant<int, 1>{}, rb);
-            rb += B;
-            if (rb >= row_end) break;
-        }
-    }
+    pass(std::true_type{}, row_begin);
+    for (uint32_t rb = row_begin + B; rb < row_end; rb += B) pass(std::false_type{}, rb);
 }
 
 // rows per wave: a multiple of the batch, sized so that the grid is a few
@@ -526,11 +520,10 @@ static hipError_t launch_stream_t(DecodeArgs a, int slots, bool y_f32, hipStream
     uint32_t rpw = B;
     while ((total_rows + rpw - 1) / rpw > 6144 && rpw < 64 * B) rpw += B;
     a.rows_per_block = rpw;
+    constexpr int kStreamWaves = stream_waves(MODE), kStreamThreads = kStreamWaves * kWave;
     const uint32_t waves = (a.N + rpw - 1) / rpw;
-    const size_t smem = MODE == 0 ? (size_t)kStreamWaves * (Cfg::kTableBytes + Cfg::kRawBytes)
-                                  : (size_t)(a.L + 1) * Fmt::kRowBytes + (size_t)a.L * Fmt::kRawBytes;
-    auto kern = rpw > (uint32_t)B ? decode_stream_kernel<BITS, NCH, RPC, TAIL, MODE, true>
-                                  : decode_stream_kernel<BITS, NCH, RPC, TAIL, MODE, false>;
+    const size_t smem = MODE == 0 ? 0 : (size_t)(a.L + 1) * Fmt::kRowBytes + (size_t)a.L * Fmt::kRawBytes;
+    auto kern = decode_stream_kernel<BITS, NCH, RPC, TAIL, MODE>;
     if (smem > 48 * 1024) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
