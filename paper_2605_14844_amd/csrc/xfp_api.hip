@@ -87,7 +87,7 @@ int decode(const xfp_weights *W, const int32_t *eids, int slots, const void *x, 
     a.eids = eids;
     a.x_stride = x_stride;
     a.y_stride = ldy;
-    if (!eids && xfp::mfma_supports((int)W->bits, (int)W->mode, W->K, slots)) {
+    if (!eids && xfp::batch_supports((int)W->bits, (int)W->mode, W->K, slots)) {
         // batched tokens: the weights are read once per 16 tokens
         const size_t ysz = y_dtype == XFP_F32 ? 4 : 2;
         for (int m0 = 0; m0 < slots; m0 += 16) {
@@ -95,7 +95,7 @@ int decode(const xfp_weights *W, const int32_t *eids, int slots, const void *x, 
             c.x = a.x + (int64_t)m0 * x_stride;
             c.y = static_cast<char *>(y) + (size_t)m0 * (size_t)ldy * ysz;
             const int mc = slots - m0 < 16 ? slots - m0 : 16;
-            hipError_t err = mc >= 2 ? xfp::launch_decode_mfma(c, mc, y_dtype == XFP_F32, s)
+            hipError_t err = mc >= 2 ? xfp::launch_decode_batch(c, mc, y_dtype == XFP_F32, s)
                                      : xfp::launch_decode_stream((int)W->bits, (int)W->mode, y_dtype == XFP_F32, c, 1, s);
             if (err != hipSuccess) return finish(err);
         }

@@ -1,0 +1,610 @@
+// Small-batch fused decode (2 <= M <= 16 tokens per launch) on the matrix cores:
+// V2 codebooks, 4-bit indices, K a multiple of 128 up to 8192.  The weights are
+// read from HBM once for all tokens.
+//
+// Work unit: a workgroup of 8 waves walks tiles of 16 output rows; wave w owns
+// NL consecutive 128-weight groups of every row (its K slice), so its share of
+// the activations stays in VGPRs for the whole kernel as ready-made MFMA B
+// operands.  v_mfma_f32_16x16x32_f16 contracts 32 k per issue:
+//     A (16 rows x 32 k)   dequantised weights, lane (i, q) supplies 8 consecutive k of row i;
+//     B (32 k x 16 tokens) activations, lane (m, q) supplies the same 8 k of token m;
+//     D (16 x 16 fp32)     partial y of the wave's K slice.
+//
+// Index stream.  Adjacent lanes of the A operand are different ROWS, which is
+// the worst case for a load (64 lanes, 64 cache lines).  So the loads use
+// another mapping: lane l reads row l / 4 of the tile, 16-byte chunk l % 4 of a
+// group, i.e. every quad of lanes reads 64 contiguous bytes, every byte of the
+// stream exactly once.  The four dwords a lane got (chunk b, piece d = 8
+// weights) are then transposed IN REGISTERS to the operand layout by
+// exchanging lane-index bits with register-index bits:
+//     v_permlane32_swap, v_permlane16_swap   lane bits 5, 4  <->  register bits 1, 0
+//     quad-permute DPP + select              lane bits 1, 0  <->  register bits 1, 0
+// after which lane (i, q) holds, in register b, piece q of chunk b of tile row
+// pi(i) = 4 (i % 4) + i / 4.  The row permutation costs nothing: the tables and
+// the epilogue simply use pi.  12 to 20 VALU operations per 32 weights, no LDS.
+// The registers of a group are reloaded for the workgroup's next tile as soon
+// as they are transposed, so one tile of index words is always in flight.
+//
+// Dequantisation is one LDS lookup per PAIR of weights: a per-row table maps an
+// index byte (two 4-bit indices) to two fp16 values, the packed form the A
+// operand wants.  Entry e of slot s lives at byte e*256 + s*4; slot =
+// buffer*32 + i + 16*(q & 1), i.e. every row's table is stored twice so that
+// the 32 lanes the LDS serves per clock hit 32 different banks, and the tables
+// of the next tile are built (other buffer) while this one is decoded.  A
+// lookup address is ONE v_perm_b32 (index byte -> address byte 1).
+//
+// Per tile, the 8 partial D blocks meet in LDS and are summed in a fixed order
+// (deterministic, no atomics) by 256 threads, which also add the CSR outlier
+// products of the tile.  One thread per outlier entry computes its 16
+// products: row pointers come through the scalar cache, col/val through
+// bounds-checked buffer loads one tile ahead, and the 16 tokens' activations at
+// that column come as ONE 32-byte read from a k-major (transposed) copy of x.
+// Gathering them from the row-major x instead costs 16 cache lines per entry.
+// That copy, and a second one in the order the B operands are loaded, live in a
+// small ring of file-scope device buffers and are written by a tiny kernel
+// launched in front of the decode kernel on the same stream; more than
+// kXtSlots batched calls in flight at once on one GPU would reuse a slot that
+// is still being read.
+#include "xfp_device.h"
+
+#include <atomic>
+#include <type_traits>
+
+namespace xfp {
+namespace {
+
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) uint32_t lds_u32_t;
+typedef __attribute__((address_space(3))) const uint32_t lds_cu32_t;
+typedef __attribute__((address_space(3))) float lds_f32_t;
+typedef __attribute__((address_space(3))) float4_t lds_f4_t;
+typedef __attribute__((address_space(4))) const int32_t const_i32_t;   // uniform reads go through the scalar cache
+
+constexpr int kTile = 16;                  // rows per tile = tokens per launch
+constexpr int kProdCap = 448;              // outlier entries of a tile whose products are kept in LDS
+constexpr int kProdPad = 32;               // entries the epilogue may read past the cap (masked)
+constexpr int kRd = 8;                     // product reads per lane issued unconditionally (4 * kRd entries per row)
+static_assert(4 * kRd <= kProdPad, "unmasked reads stay inside the buffer");
+
+// W waves per workgroup (8 or 16), each owning 1/W of K.
+template <int W>
+struct BatchLds {
+    static constexpr int kTabBytes = 256 * 256;                       // [256 entries][2 buffers x 32 slots] dwords
+    static constexpr int kRedOne = W * 256 * 4;                       // partial D blocks of a tile
+    static constexpr int kProdOne = (kProdCap + kProdPad) * 16 * 4;
+    static constexpr int kRed = kTabBytes;
+    static constexpr int kProd = kRed + 2 * kRedOne;
+    static constexpr int kTotal = kProd + 2 * kProdOne;               // 140 KB (W = 8), 156 KB (W = 16)
+};
+
+constexpr int kXtSlots = 16;               // batched calls that may overlap on one GPU
+constexpr int kXtMaxK = 8192;
+// Two re-laid copies of the 16 x K activations of a call, per ring slot:
+//   xt [k][16 tokens]           the outlier products read the 16 tokens of one column as 32 bytes;
+//   xb [k / 8][16 tokens][8 k]  the B operand of lane (m, q) for a k block is 16 contiguous bytes and
+//                               the 64 lanes of a wave read 1 KB contiguous (from the row-major x the
+//                               same load touches 64 different cache lines).
+// Tokens >= M are zero in both.
+struct XCopies {
+    uint16_t xt[kXtMaxK * kTile];
+    uint16_t xb[kXtMaxK * kTile];
+};
+__device__ __align__(256) XCopies g_x[kXtSlots];
+
+// blocks [0, K/256): xt, one thread per k;  blocks [K/256, K/256 + K/128): xb, one thread per (k block, token).
+__global__ __launch_bounds__(256) void relayout_x_kernel(const uint16_t *x, int64_t ldx, int M, uint32_t K, int slot)
+{
+    const uint32_t nb_t = (K + 255) / 256;
+    if (blockIdx.x < nb_t) {
+        const uint32_t k = blockIdx.x * 256 + threadIdx.x;
+        if (k >= K) return;
+        uint32_t v[8];
+#pragma unroll
+        for (int m = 0; m < 16; m += 2) {
+            const uint32_t lo = m < M ? x[(size_t)m * ldx + k] : 0u;
+            const uint32_t hi = m + 1 < M ? x[(size_t)(m + 1) * ldx + k] : 0u;
+            v[m / 2] = lo | (hi << 16);
+        }
+        uint4 *o = reinterpret_cast<uint4 *>(&g_x[slot].xt[(size_t)k * kTile]);
+        o[0] = make_uint4(v[0], v[1], v[2], v[3]);
+        o[1] = make_uint4(v[4], v[5], v[6], v[7]);
+    } else {
+        const uint32_t id = (blockIdx.x - nb_t) * 256 + threadIdx.x;      // = k block * 16 + token
+        const uint32_t kb = id >> 4, m = id & 15;
+        if (kb * 8 >= K) return;
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if ((int)m < M) v = *reinterpret_cast<const uint4 *>(x + (size_t)m * ldx + (size_t)kb * 8);
+        reinterpret_cast<uint4 *>(g_x[slot].xb)[id] = v;
+    }
+}
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits
+// for every outstanding global load, which would drain the index prefetch.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// Exchange a register-index bit with lane-index bit 0 (HIGH = 0, quad_perm
+// [1,0,3,2]) or bit 1 (HIGH = 1, quad_perm [2,3,0,1]) for two register pairs
+// (x0, y0) and (x1, y1): afterwards x holds, in the lanes whose bit is set, what
+// y held in the partner lane, and y holds, in the lanes whose bit is clear, what
+// x held in the partner lane.  One v_cndmask_b32 with a DPP source per output;
+// the two scalar moves in front also cover the wait states a DPP read needs
+// after a vector write.
+#define XFP_EXCHANGE_ASM(QP, MASK)                                                                   \
+    asm volatile("s_nop 1\n\t"                                                                       \
+                 "s_mov_b32 vcc_lo, " MASK "\n\ts_mov_b32 vcc_hi, " MASK "\n\t"                        \
+                 "v_cndmask_b32_dpp %0, %5, %4, vcc quad_perm:" QP " row_mask:0xf bank_mask:0xf\n\t" \
+                 "v_cndmask_b32_dpp %2, %7, %6, vcc quad_perm:" QP " row_mask:0xf bank_mask:0xf\n\t" \
+                 "s_not_b64 vcc, vcc\n\t"                                                            \
+                 "v_cndmask_b32_dpp %1, %4, %5, vcc quad_perm:" QP " row_mask:0xf bank_mask:0xf\n\t" \
+                 "v_cndmask_b32_dpp %3, %6, %7, vcc quad_perm:" QP " row_mask:0xf bank_mask:0xf"      \
+                 : "=&v"(o0), "=&v"(o1), "=&v"(o2), "=&v"(o3)                                        \
+                 : "v"(x0), "v"(y0), "v"(x1), "v"(y1)                                                \
+                 : "vcc", "scc")
+template <int HIGH>
+__device__ __forceinline__ void lane_reg_exchange(uint32_t &x0, uint32_t &y0, uint32_t &x1, uint32_t &y1)
+{
+    uint32_t o0, o1, o2, o3;
+    if constexpr (HIGH) XFP_EXCHANGE_ASM("[2,3,0,1]", "0x33333333");    // vcc: lanes whose bit 1 is clear
+    else XFP_EXCHANGE_ASM("[1,0,3,2]", "0x55555555");                   // vcc: lanes whose bit 0 is clear
+    x0 = o0; y0 = o1; x1 = o2; y1 = o3;
+}
+
+// Lane l = 4a + b holds pieces d = 0..3 (v[d]) of chunk b of tile row a.
+// Afterwards lane (i, q) = i + 16 q holds, in v[b], piece q of chunk b of tile
+// row 4 (i % 4) + i / 4.
+__device__ __forceinline__ void to_operand_layout(uint32_t (&v)[4])
+{
+    // lane bit 5 <-> register bit 1, lane bit 4 <-> register bit 0
+    auto s02 = __builtin_amdgcn_permlane32_swap(v[0], v[2], false, false);
+    auto s13 = __builtin_amdgcn_permlane32_swap(v[1], v[3], false, false);
+    auto s01 = __builtin_amdgcn_permlane16_swap(s02[0], s13[0], false, false);
+    auto s23 = __builtin_amdgcn_permlane16_swap(s02[1], s13[1], false, false);
+    v[0] = s01[0]; v[1] = s01[1]; v[2] = s23[0]; v[3] = s23[1];
+    // lane bit 1 <-> register bit 1, lane bit 0 <-> register bit 0
+    lane_reg_exchange<1>(v[0], v[2], v[1], v[3]);
+    lane_reg_exchange<0>(v[0], v[1], v[2], v[3]);
+}
+
+#ifdef XFP_EXP_TIMING
+// [tile pass 0..7][phase 0..7][wave 0..7] of workgroup 0; every stamp waits for the scalar and LDS queues
+__device__ unsigned long long g_bdbg[8 * 8 * 8 + 2 * 256 * 8];
+#define XFP_BSTAMP(ph) do { if (blockIdx.x == 100 && lane == 0 && npass < 8) g_bdbg[(npass * 8 + (ph)) * 8 + wave] = __builtin_amdgcn_s_memrealtime(); } while (0)
+#define XFP_WGSTAMP(which) do { if (lane == 0 && wave == 0 && blockIdx.x < 256) g_bdbg[512 + ((which) * 8 + (npass & 7)) * 256 + blockIdx.x] = __builtin_amdgcn_s_memrealtime(); } while (0)
+#else
+#define XFP_BSTAMP(ph) do { } while (0)
+#define XFP_WGSTAMP(which) do { } while (0)
+#endif
+
+struct BatchArgs {
+    DecodeArgs a;
+    const uint4 *xt;      // [K][16 tokens] fp16
+    const uint4 *xb;      // [K / 8][16 tokens][8 k] fp16
+    int M;
+    int y_f32;
+};
+
+// NL: groups per wave per tile (K <= NL * 8 * 128).  RAGGED: K < NL * 8 * 128,
+// some waves own groups past the end of the row.
+template <int W, int NL, bool RAGGED>
+__global__ __launch_bounds__(W * kWave) void decode_batch4_kernel(BatchArgs ta)
+{
+    using L = BatchLds<W>;
+    constexpr int kRed = L::kRed, kRedOne = L::kRedOne, kProd = L::kProd, kProdOne = L::kProdOne;
+    constexpr int RPW = kTile / W;                         // rows a wave finishes in the epilogue (2 or 1)
+    constexpr int NS = 4 * NL;                             // MFMA steps per tile per wave
+    extern __shared__ __align__(16) unsigned char smem[];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
+    const DecodeArgs &a = ta.a;
+    const int M = ta.M;
+
+    const uint32_t tid = threadIdx.x, lane = tid & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t i = lane & 15, q = lane >> 4;           // operand layout: A row / token, k block
+    const uint32_t la = lane >> 2, lb = lane & 3;          // load layout: tile row, chunk of a group
+    const uint32_t N = a.N, K = a.K, G = K / kGroup;
+    const uint32_t wpr = K / 8;                            // dwords per row (4-bit)
+    const uint32_t ntiles = (N + kTile - 1) / kTile;
+    const uint32_t tstep = gridDim.x;
+    const_i32_t *rp = (const_i32_t *)(uintptr_t)a.rp;
+    if (lds0 & 0xFFFFu) return;                            // the lookup addresses assume the tables at LDS offset 0
+
+    const uint32_t g0 = wave * NL;                         // first group of this wave's K slice
+
+    // ---------------------------------------------------------------- loaders
+    // Index words of group g0 + c of a tile: this lane's 16 bytes sit at a per-tile
+    // base plus a compile-time offset (RAGGED: groups past the end of the row read
+    // the last group again).  A tile that does not exist reads the matrix's first row.
+    uint4 iw[NL];
+    auto tile_base = [&](uint32_t tile, bool on) {
+        const uint32_t row = min(tile * kTile + la, N - 1);
+        return reinterpret_cast<const uint4 *>(a.idx + (on ? (size_t)row * wpr : 0) + (size_t)(g0 * 4 + lb) * 4);
+    };
+    auto load_group = [&](int c, const uint4 *base) {
+        if constexpr (RAGGED) iw[c] = base[4 * ((int32_t)min(g0 + c, G - 1) - (int32_t)g0)];
+        else iw[c] = base[4 * c];
+    };
+    // CSR bookkeeping of a tile, all wave-uniform (scalar loads): the entry range
+    // of the tile and of the rows this wave finishes (w, and w + 8 when W = 8).
+    struct TileRp { int32_t base, end, lo[RPW], hi[RPW]; };
+    auto load_rp = [&](uint32_t tile) {
+        const uint32_t n0 = tile * kTile;
+        TileRp r;
+        r.base = rp[min(n0, N)];
+        r.end = rp[min(n0 + kTile, N)];
+#pragma unroll
+        for (int h = 0; h < RPW; ++h) {
+            r.lo[h] = rp[min(n0 + wave + W * h, N)];
+            r.hi[h] = rp[min(n0 + wave + W * h + 1, N)];
+        }
+        return r;
+    };
+    // Outlier entry `tid` of a tile: col/val through bounds-checked buffer loads
+    // (entries past the end of the tile read as zero).
+    auto load_colval = [&](const TileRp &r, uint32_t &col, uint32_t &val) {
+        const int32_t cnt = r.end - r.base;
+        __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc((void *)(a.col + r.base), 0, cnt * 4, 0x00020000);
+        __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc((void *)(a.val + r.base), 0, cnt * 2, 0x00020000);
+        col = __builtin_amdgcn_raw_buffer_load_b32(rc, tid * 4, 0, 0);
+        val = __builtin_amdgcn_raw_buffer_load_b16(rv, tid * 2, 0, 0);
+    };
+    // Table builder role of this thread: slot tid % 32 (operand row i = slot % 16,
+    // i.e. tile row pi(i)); with tb = tid / 32 it writes the entries tb + 2W j
+    // (first index tb % 16, second index tb / 16 + (W / 8) j).
+    const uint32_t tb_slot = tid & 31, tb = tid >> 5;
+    const uint32_t tb_row = 4 * (tb_slot & 3) + ((tb_slot & 15) >> 2);
+    uint32_t cbr[8], cblo = 0;
+    auto load_codebook = [&](uint32_t tile) {
+        const uint16_t *p = a.cb + (size_t)min(tile * kTile + tb_row, N - 1) * 16;
+        const uint4 v0 = reinterpret_cast<const uint4 *>(p)[0], v1 = reinterpret_cast<const uint4 *>(p)[1];
+        cbr[0] = v0.x; cbr[1] = v0.y; cbr[2] = v0.z; cbr[3] = v0.w;
+        cbr[4] = v1.x; cbr[5] = v1.y; cbr[6] = v1.z; cbr[7] = v1.w;
+        cblo = p[tb & 15];
+    };
+    auto build_table = [&](uint32_t buf) {
+        const uint32_t base = lds0 + tb * 256 + (buf * 32 + tb_slot) * 4;
+#pragma unroll
+        for (int j = 0; j < 128 / W; ++j) {
+            uint32_t hi;
+            if constexpr (W == 8) hi = (j & 1) ? (cbr[j >> 1] & 0xFFFF0000u) : (cbr[j >> 1] << 16);   // second index j
+            else hi = (tb & 16) ? (cbr[j] & 0xFFFF0000u) : (cbr[j] << 16);                           // second index tb / 16 + 2 j
+            *(lds_u32_t *)(uintptr_t)(base + j * 2 * W * 256) = cblo | hi;
+        }
+    };
+
+    uint32_t t = blockIdx.x;
+    if (t >= ntiles) return;
+    uint32_t npass = 7;
+    (void)npass;
+    XFP_WGSTAMP(0);                                        // kernel entry (slot 7)
+    XFP_BSTAMP(0);
+
+    // ---------------------------------------------------------------- prologue
+    // Codebooks first (they gate the tables), then per group its activations (L2
+    // hits) followed by its index words (HBM): vector loads return in order and a
+    // CU only tracks about a tile's worth of outstanding loads, so this order lets
+    // the first MFMA steps start while the later groups are still streaming in.
+    TileRp rp_c = load_rp(t);
+    const bool have1 = t + tstep < ntiles;
+    TileRp rp_n = load_rp(have1 ? t + tstep : t);
+    XFP_BSTAMP(1);
+    load_codebook(t);
+    // a1: B operands.  Step s = 4 c + b contracts, in k block q, piece q of chunk b
+    // of group g0 + c.
+    uint32_t xr[NS][4];
+    {
+        const uint4 *b0 = tile_base(t, true);
+#pragma unroll
+        for (int c = 0; c < NL; ++c) {
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int s = 4 * c + b;
+                const uint32_t g = g0 + c;
+                const uint32_t kb = min(g, G - 1) * (kGroup / 8) + b * 4 + q;         // k block of this lane
+                const uint4 v = ta.xb[(size_t)kb * kTile + i];
+                const bool on = !RAGGED || g < G;
+                xr[s][0] = on ? v.x : 0u; xr[s][1] = on ? v.y : 0u; xr[s][2] = on ? v.z : 0u; xr[s][3] = on ? v.w : 0u;
+            }
+            load_group(c, b0);
+        }
+    }
+    XFP_BSTAMP(2);
+    XFP_BSTAMP(3);
+    // a2: tables of the first tile.
+    build_table(0);
+    XFP_BSTAMP(4);
+    load_codebook(have1 ? t + tstep : t);
+    uint32_t ocol = 0, oval = 0;
+    load_colval(rp_c, ocol, oval);
+    XFP_BSTAMP(5);
+    lds_barrier();
+    XFP_BSTAMP(6);
+    npass = 0;
+    const uint32_t bank4 = (((q & 1) << 4) | i) * 4;       // this lane's private bank
+
+
+    // ---------------------------------------------------------------- one tile
+    // P = parity of the tile within this workgroup's sequence: table buffer,
+    // reduction and product buffers.
+    auto tile_pass = [&](auto Ptag, uint32_t tile) {
+        constexpr int P = decltype(Ptag)::value;
+        const uint32_t n0 = tile * kTile;
+        const uint32_t t1 = tile + tstep, t2 = tile + 2 * tstep;
+        const bool have_next = t1 < ntiles, have2 = t2 < ntiles;
+        XFP_BSTAMP(0);
+        XFP_WGSTAMP(0);
+        const TileRp rp_f = load_rp(have2 ? t2 : tile);    // two tiles ahead (scalar cache)
+        const uint4 *nbase = tile_base(t1, have_next);
+
+        // ---- a3-a6: transpose, depack, pair lookup, MFMA; lookups run two steps ahead ----
+        float4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+        const uint32_t sel = bank4 + P * 128;
+        uint32_t pw[2][4];                                 // transposed pieces of the current and the next group
+#ifndef XFP_EXP_NO_GATHER
+#define XFP_EXP_NO_GATHER 0
+#endif
+#ifndef XFP_EXP_NO_COLVAL
+#define XFP_EXP_NO_COLVAL 0
+#endif
+#ifndef XFP_EXP_NO_BUILD
+#define XFP_EXP_NO_BUILD 0
+#endif
+#ifndef XFP_EXP_LOOKAHEAD
+#define XFP_EXP_LOOKAHEAD 2
+#endif
+        constexpr int LA = XFP_EXP_LOOKAHEAD;              // steps the lookups run ahead of the MFMAs
+        static_assert(LA >= 1 && LA <= 3, "a group is transposed while the previous one is still being looked up");
+        uint32_t av[LA + 1][4];
+        auto transpose_group = [&](int c) {
+            uint32_t (&v)[4] = pw[c & 1];
+            v[0] = iw[c].x; v[1] = iw[c].y; v[2] = iw[c].z; v[3] = iw[c].w;
+#ifndef XFP_EXP_NO_TRANSPOSE
+            to_operand_layout(v);
+#endif
+            load_group(c, nbase);                          // the registers are free: next tile's words
+        };
+        auto lookup = [&](int s, uint32_t (&v)[4]) {
+            const uint32_t w = pw[(s / 4) & 1][s & 3];
+#ifdef XFP_EXP_NO_LOOKUP
+            v[0] = __builtin_amdgcn_perm(w, sel, 0x0c0c0400u); v[1] = __builtin_amdgcn_perm(w, sel, 0x0c0c0500u);
+            v[2] = __builtin_amdgcn_perm(w, sel, 0x0c0c0600u); v[3] = __builtin_amdgcn_perm(w, sel, 0x0c0c0700u);
+            return;
+#endif
+            v[0] = *(lds_cu32_t *)(uintptr_t)__builtin_amdgcn_perm(w, sel, 0x0c0c0400u);
+            v[1] = *(lds_cu32_t *)(uintptr_t)__builtin_amdgcn_perm(w, sel, 0x0c0c0500u);
+            v[2] = *(lds_cu32_t *)(uintptr_t)__builtin_amdgcn_perm(w, sel, 0x0c0c0600u);
+            v[3] = *(lds_cu32_t *)(uintptr_t)__builtin_amdgcn_perm(w, sel, 0x0c0c0700u);
+        };
+        uint4 ox0 = make_uint4(0u, 0u, 0u, 0u), ox1 = ox0;     // x at this thread's outlier column
+        constexpr int GATHER_STEP = NS >= 8 ? NS / 2 : 0;
+        transpose_group(0);
+        XFP_BSTAMP(1);
+#pragma unroll
+        for (int s = 0; s < LA && s < NS; ++s) lookup(s, av[s]);
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            // group c + 1 must be transposed before the lookup of its first step, 4 (c + 1), is issued
+            if ((s + LA) % 4 == 3 && (s + LA) / 4 + 1 < NL) transpose_group((s + LA) / 4 + 1);
+            if (s + LA < NS) lookup(s + LA, av[(s + LA) % (LA + 1)]);
+            __builtin_amdgcn_sched_barrier(0);
+            const uint32_t (&cur)[4] = av[s % (LA + 1)];
+            half8_t af = __builtin_bit_cast(half8_t, u32x4_t{cur[0], cur[1], cur[2], cur[3]});
+            half8_t bf = __builtin_bit_cast(half8_t, u32x4_t{xr[s][0], xr[s][1], xr[s][2], xr[s][3]});
+#ifdef XFP_EXP_NO_MFMA
+            acc0[0] += (float)af[0] + (float)bf[0];
+#else
+            if (!RAGGED || g0 + s / 4 < G) {
+                if (s & 1) acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(af, bf, acc1, 0, 0, 0);
+                else acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(af, bf, acc0, 0, 0, 0);
+            }
+#endif
+            if (s == GATHER_STEP && !XFP_EXP_NO_GATHER) {  // col of this tile arrived long ago
+                ox0 = ta.xt[(size_t)ocol * 2];
+                ox1 = ta.xt[(size_t)ocol * 2 + 1];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+
+        XFP_BSTAMP(2);
+        // ---- a7: outlier products of the first kProdCap entries -> LDS ----
+        if (W * kWave <= kProdCap || tid < (uint32_t)kProdCap) {
+            const float v = half_bits_to_float((uint16_t)oval);
+            const uint32_t xw[8] = {ox0.x, ox0.y, ox0.z, ox0.w, ox1.x, ox1.y, ox1.z, ox1.w};
+            float p[16];
+#pragma unroll
+            for (int m = 0; m < 16; ++m)
+                p[m] = v * half_bits_to_float((uint16_t)(m & 1 ? xw[m / 2] >> 16 : xw[m / 2] & 0xFFFFu));
+            lds_f4_t *dst = (lds_f4_t *)(uintptr_t)(lds0 + kProd + P * kProdOne + tid * 64);
+#pragma unroll
+            for (int g = 0; g < 4; ++g) dst[g] = float4_t{p[4 * g], p[4 * g + 1], p[4 * g + 2], p[4 * g + 3]};
+        }
+        XFP_BSTAMP(3);
+        // ---- tables of the next tile; loads that run one and two tiles ahead ----
+        if (have_next && !XFP_EXP_NO_BUILD) build_table(P ^ 1);
+        if (!XFP_EXP_NO_BUILD) load_codebook(have2 ? t2 : tile);
+        if (!XFP_EXP_NO_COLVAL) load_colval(rp_n, ocol, oval);   // next tile's entries
+        // ---- partial D of this wave -> LDS, indexed by tile row ----
+        {
+            const float4_t d = acc0 + acc1;                // lane (m, q'), register r: operand row 4q' + r = tile row 4r + q'
+            const uint32_t rb = lds0 + kRed + P * kRedOne + wave * 1024;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) *(lds_f32_t *)(uintptr_t)(rb + ((4 * r + q) * 16 + i) * 4) = d[r];
+        }
+        XFP_BSTAMP(4);
+        lds_barrier();
+        XFP_BSTAMP(5);
+
+        // ---- a8: cross-wave sum, outlier fold, store (fixed order) ----
+        // output (row, token m) is summed by the 4 lanes of a quad: lane j takes waves
+        // j, j+4, ... and entries lo+j, lo+j+4, ...; a wave finishes row w (and w + 8).
+        {
+            const int32_t ob = rp_c.base;
+            const uint32_t pbase = lds0 + kProd + P * kProdOne;
+            const uint32_t rbase = lds0 + kRed + P * kRedOne;
+            const uint32_t sub = lane & 3, m = lane >> 2;
+            const uint16_t *xrow = a.x + (size_t)min(m, (uint32_t)M - 1) * a.x_stride;
+            float part[RPW][W / 4], pv[RPW][kRd];
+            int32_t lo[RPW], hi[RPW], hf[RPW];
+#pragma unroll
+            for (int h = 0; h < RPW; ++h) {                // issue every LDS read first
+                const uint32_t o = (wave + W * h) * 16 + m;
+#pragma unroll
+                for (int j = 0; j < W / 4; ++j)
+                    part[h][j] = *(lds_f32_t *)(uintptr_t)(rbase + (sub + 4 * j) * 1024 + o * 4);
+                lo[h] = rp_c.lo[h] - ob;
+                hf[h] = rp_c.hi[h] - ob;
+                hi[h] = min(hf[h], (int32_t)kProdCap);
+                // reads past the row's entries stay inside the padded buffer and are masked
+                const uint32_t eb = pbase + (uint32_t)(min(lo[h], (int32_t)kProdCap) + (int32_t)sub) * 64 + m * 4;
+#pragma unroll
+                for (int j = 0; j < kRd; ++j) pv[h][j] = *(lds_f32_t *)(uintptr_t)(eb + j * 256);
+            }
+#pragma unroll
+            for (int h = 0; h < RPW; ++h) {
+                const uint32_t n = n0 + wave + W * h;
+                float s = part[h][0];
+#pragma unroll
+                for (int j = 1; j < W / 4; ++j) s += part[h][j];
+                const int32_t nv = hi[h] - lo[h] - (int32_t)sub;       // entry 4 j of this lane is valid iff 4 j < nv
+#pragma unroll
+                for (int j = 0; j < kRd; ++j) s += 4 * j < nv ? pv[h][j] : 0.f;
+                for (int32_t en = lo[h] + (int32_t)sub + 4 * kRd; en < hi[h]; en += 4)                    // long rows: rare
+                    s += *(lds_f32_t *)(uintptr_t)(pbase + en * 64 + m * 4);
+                for (int32_t en = max(lo[h], (int32_t)kProdCap) + (int32_t)sub; en < hf[h]; en += 4)      // > kProdCap per tile: rare
+                    s = fmaf(half_bits_to_float(a.val[ob + en]), half_bits_to_float(xrow[a.col[ob + en]]), s);
+                s = dpp_add<0xB1>(s);                      // quad_perm [1,0,3,2]
+                s = dpp_add<0x4E>(s);                      // quad_perm [2,3,0,1]
+                if (sub == 0 && n < N && m < (uint32_t)M) {
+                    const int64_t oo = (int64_t)m * a.y_stride + n;
+                    if (ta.y_f32) static_cast<float *>(a.y)[oo] = s;
+                    else static_cast<_Float16 *>(a.y)[oo] = (_Float16)s;
+                }
+            }
+        }
+        XFP_BSTAMP(6);
+        XFP_WGSTAMP(1);
+        ++npass;
+        rp_c = rp_n;
+        rp_n = rp_f;
+    };
+
+    for (;;) {
+        tile_pass(std::integral_constant<int, 0>{}, t);
+        t += tstep;
+        if (t >= ntiles) break;
+        tile_pass(std::integral_constant<int, 1>{}, t);
+        t += tstep;
+        if (t >= ntiles) break;
+    }
+}
+
+}  // namespace
+#ifdef XFP_EXP_TIMING
+extern "C" int xfp_exp_read_bdebug(void *dst, size_t bytes) { return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_bdbg), bytes); }
+#endif
+namespace {
+
+int device_cus()
+{
+    static std::atomic<int> cus{0};
+    int c = cus.load(std::memory_order_relaxed);
+    if (c == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 256;
+        c = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+        cus.store(c, std::memory_order_relaxed);
+    }
+    return c;
+}
+
+template <int W, int NL, bool RAGGED>
+hipError_t launch_batch_t(const DecodeArgs &a, int M, bool y_f32, hipStream_t s)
+{
+    constexpr int kBatchLds = BatchLds<W>::kTotal;
+    auto kern = decode_batch4_kernel<W, NL, RAGGED>;
+    static std::atomic<int> configured{0};                 // idempotent attribute, benign race
+    if (!configured.load(std::memory_order_relaxed)) {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kBatchLds);
+        if (err != hipSuccess) return err;
+        configured.store(1, std::memory_order_relaxed);
+    }
+    static std::atomic<void *> ring{nullptr};              // device address of g_x (one GPU per process)
+    void *p = ring.load(std::memory_order_relaxed);
+    if (!p) {
+        hipError_t err = hipGetSymbolAddress(&p, HIP_SYMBOL(g_x));
+        if (err != hipSuccess) return err;
+        ring.store(p, std::memory_order_relaxed);
+    }
+    static std::atomic<unsigned> next_slot{0};
+    const int xs = (int)(next_slot.fetch_add(1, std::memory_order_relaxed) % kXtSlots);
+    hipLaunchKernelGGL(relayout_x_kernel, dim3((a.K + 255) / 256 + (a.K * 2 + 255) / 256), dim3(256), 0, s, a.x,
+                       a.x_stride, M, a.K, xs);
+    BatchArgs ta;
+    ta.a = a;
+    ta.M = M;
+    ta.y_f32 = (int)y_f32;
+    const XCopies *xc = static_cast<const XCopies *>(p) + xs;
+    ta.xt = reinterpret_cast<const uint4 *>(xc->xt);
+    ta.xb = reinterpret_cast<const uint4 *>(xc->xb);
+    const uint32_t ntiles = (a.N + kTile - 1) / kTile;
+    const uint32_t cus = (uint32_t)device_cus();
+    hipLaunchKernelGGL(kern, dim3(ntiles < cus ? ntiles : cus), dim3(W * kWave), kBatchLds, s, ta);
+    return hipGetLastError();
+}
+
+#ifndef XFP_EXP_BATCH_W16_FROM
+#define XFP_EXP_BATCH_W16_FROM 1000        // groups per row from which 16 waves share a tile (never: it spills)
+#endif
+
+template <int W, int NL>
+hipError_t launch_batch_n(const DecodeArgs &a, int M, bool y_f32, hipStream_t s)
+{
+    if (a.K / kGroup == (uint32_t)NL * W) return launch_batch_t<W, NL, false>(a, M, y_f32, s);
+    return launch_batch_t<W, NL, true>(a, M, y_f32, s);
+}
+
+template <int W>
+hipError_t launch_batch_w(const DecodeArgs &a, int M, bool y_f32, hipStream_t s)
+{
+    const uint32_t G = a.K / kGroup;
+    switch ((G + W - 1) / W) {
+    case 1: return launch_batch_n<W, 1>(a, M, y_f32, s);
+    case 2: return launch_batch_n<W, 2>(a, M, y_f32, s);
+    case 3: return launch_batch_n<W, 3>(a, M, y_f32, s);
+    case 4: return launch_batch_n<W, 4>(a, M, y_f32, s);
+    default:
+        if constexpr (W == 8) {
+            switch ((G + W - 1) / W) {
+            case 5: return launch_batch_n<W, 5>(a, M, y_f32, s);
+            case 6: return launch_batch_n<W, 6>(a, M, y_f32, s);
+            case 7: return launch_batch_n<W, 7>(a, M, y_f32, s);
+            default: return launch_batch_n<W, 8>(a, M, y_f32, s);
+            }
+        }
+        return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace
+
+bool batch_supports(int bits, int mode, uint32_t K, int M)
+{
+    return bits == 4 && mode == 0 && M >= 2 && K % kGroup == 0 && K >= kGroup && K <= 8192;
+}
+
+// M <= 16 tokens per launch; the caller loops over chunks of 16.  Long rows are
+// shared by 16 waves (128 registers each, four waves per SIMD hide the lookup
+// latency), short rows by 8.
+hipError_t launch_decode_batch(const DecodeArgs &a, int M, bool y_f32, hipStream_t s)
+{
+    if (a.K / kGroup >= XFP_EXP_BATCH_W16_FROM) return launch_batch_w<16>(a, M, y_f32, s);
+    return launch_batch_w<8>(a, M, y_f32, s);
+}
+
+}  // namespace xfp

@@ -34,9 +34,9 @@ hipError_t launch_decode_rows(int bits, int mode, bool y_f32, const DecodeArgs &
 // registers, pair tables in LDS.
 bool stream_supports(int bits, int mode, uint32_t K, uint32_t L);
 hipError_t launch_decode_stream(int bits, int mode, bool y_f32, const DecodeArgs &a, int slots, hipStream_t s);
-// Matrix-core kernel for 2..16 tokens per launch (V2, 4-bit, K % 1024 == 0, K <= 8192).
-bool mfma_supports(int bits, int mode, uint32_t K, int M);
-hipError_t launch_decode_mfma(const DecodeArgs &a, int M, bool y_f32, hipStream_t s);
+// Matrix-core kernel for 2..16 tokens per launch (V2, 4-bit, K <= 8192).
+bool batch_supports(int bits, int mode, uint32_t K, int M);
+hipError_t launch_decode_batch(const DecodeArgs &a, int M, bool y_f32, hipStream_t s);
 hipError_t launch_unpack(int bits, const uint32_t *idx, uint64_t rows, uint32_t K, uint8_t *out,
                          hipStream_t s);
 hipError_t launch_dequant(int bits, int mode, const DecodeArgs &a, uint32_t E, uint16_t *out,
