@@ -225,8 +225,9 @@ __global__ __launch_bounds__(W * kWave) void decode_batch4_kernel(BatchArgs ta)
         return reinterpret_cast<const uint4 *>(a.idx + (on ? (size_t)row * wpr : 0) + (size_t)(g0 * 4 + lb) * 4);
     };
     auto load_group = [&](int c, const uint4 *base) {
-        if constexpr (RAGGED) iw[c] = base[4 * ((int32_t)min(g0 + c, G - 1) - (int32_t)g0)];
-        else iw[c] = base[4 * c];
+        const uint4 *p = RAGGED ? base + 4 * ((int32_t)min(g0 + c, G - 1) - (int32_t)g0) : base + 4 * c;
+        const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));   // read once: keep L2 for x
+        iw[c] = make_uint4(v.x, v.y, v.z, v.w);
     };
     // CSR bookkeeping of a tile, all wave-uniform (scalar loads): the entry range
     // of the tile and of the rows this wave finishes (w, and w + 8 when W = 8).
@@ -292,6 +293,16 @@ __global__ __launch_bounds__(W * kWave) void decode_batch4_kernel(BatchArgs ta)
     const bool have1 = t + tstep < ntiles;
     TileRp rp_n = load_rp(have1 ? t + tstep : t);
     XFP_BSTAMP(1);
+    // Every workgroup reads the whole operand-ordered copy of x, all in the same
+    // order, so every line would be a (merged) miss for all of them.  The L2 is
+    // per XCD and workgroups are dealt to the 8 XCDs round-robin: wave w of the
+    // j-th workgroup of an XCD touches KB number 8 j + w of the copy first, so
+    // that each XCD has all of it in its L2 after one miss latency.
+    uint4 warm;
+    {
+        const uint32_t kib = ((blockIdx.x >> 3) * W + wave) % (K * kTile * 2 / 1024);
+        warm = ta.xb[(size_t)kib * 64 + lane];
+    }
     load_codebook(t);
     // a1: B operands.  Step s = 4 c + b contracts, in k block q, piece q of chunk b
     // of group g0 + c.
@@ -312,7 +323,7 @@ __global__ __launch_bounds__(W * kWave) void decode_batch4_kernel(BatchArgs ta)
             load_group(c, b0);
         }
     }
-    XFP_BSTAMP(2);
+    asm volatile("" :: "v"(warm.x), "v"(warm.y), "v"(warm.z), "v"(warm.w));
     XFP_BSTAMP(3);
     // a2: tables of the first tile.
     build_table(0);

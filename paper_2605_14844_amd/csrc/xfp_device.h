@@ -13,19 +13,23 @@ struct LaneWords {
     uint32_t w[BITS];
 };
 
+// The index stream is read exactly once: the loads carry the non-temporal hint
+// so that the stream does not displace the activations and codebooks in L2.
 template <int BITS>
 __device__ __forceinline__ LaneWords<BITS> load_lane_words(const uint32_t *p)
 {
     LaneWords<BITS> r;
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
     if constexpr (BITS == 4) {
-        uint4 v = *reinterpret_cast<const uint4 *>(p);
+        u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
         r.w[0] = v.x; r.w[1] = v.y; r.w[2] = v.z; r.w[3] = v.w;
     } else if constexpr (BITS == 2) {
-        uint2 v = *reinterpret_cast<const uint2 *>(p);
+        u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(p));
         r.w[0] = v.x; r.w[1] = v.y;
     } else {
 #pragma unroll
-        for (int i = 0; i < BITS; ++i) r.w[i] = p[i];
+        for (int i = 0; i < BITS; ++i) r.w[i] = __builtin_nontemporal_load(p + i);
     }
     return r;
 }
