@@ -185,22 +185,25 @@ __device__ __forceinline__ void consume_group(int g, const uint32_t (&v)[8], con
 // TAIL: K is not a multiple of 2048 (RPC == 1): lanes past the row's end in the
 //       last chunk read a clamped address, zero activations and the zero table
 constexpr int stream_waves(int mode) { return mode == 0 ? 1 : 4; }   // waves per workgroup
+// waves a launch aims for at most (measured: V2 is fastest with about 16 single-wave
+// workgroups per CU, V2a with about 2 four-wave workgroups)
+constexpr uint32_t stream_max_waves(int mode) { return mode == 0 ? 6144 : 3072; }
 
-template <int BITS, int NCH, int RPC>
+// U: row groups a wave decodes at once (all their loads are issued before the
+// first is touched).  The launcher picks the smallest U that lets every wave
+// finish its rows in ONE batch, so that nothing is loaded late.
+template <int BITS, int NCH, int RPC, int U_>
 struct StreamCfg {
-#ifdef XFP_EXP_U
-    static constexpr int kUnroll = XFP_EXP_U;
-#else
-    static constexpr int kUnroll = RPC > 1 ? 2 : (NCH >= 5 ? 1 : (NCH >= 2 ? 2 : 4));
-#endif
+    static constexpr int kUnroll = U_;
     static constexpr int kBatchRows = kUnroll * RPC;           // rows a wave decodes at once
     static constexpr int kLanesPerRow = kWave / RPC;
     static constexpr int kTableBytes = (kBatchRows + 1) * TableFmt<BITS>::kRowBytes;   // + zero table
     static constexpr int kRawBytes = TableFmt<BITS>::kPair ? kBatchRows * TableFmt<BITS>::kRawBytes : 0;
     // registers: 16 per chunk for x, BITS per lane-load in flight, ~60 working
     static constexpr int kRegs = 16 * NCH + BITS * NCH * kUnroll + 60;
-    static constexpr int kWavesPerSimd =
-        RPC > 1 ? (BITS == 3 ? 4 : 3) : (kRegs <= 128 ? 4 : (kRegs <= 168 ? 3 : 2));
+    static constexpr int kWavesPerSimd = kRegs <= 128 ? 4 : (kRegs <= 168 ? 3 : 2);
+    // largest U the registers allow (x: 16 per chunk; index words: BITS per chunk and row group)
+    static constexpr bool kFits = BITS * NCH * kUnroll <= 64 && kRegs <= 250;
 };
 
 // LDS byte address of a static array of BYTES bytes (one per instantiation).
@@ -211,12 +214,12 @@ __device__ __forceinline__ uint32_t static_lds()
     return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)buf;
 }
 
-template <int BITS, int NCH, int RPC, bool TAIL, int MODE>
-__global__ __launch_bounds__(stream_waves(MODE) * kWave, (StreamCfg<BITS, NCH, RPC>::kWavesPerSimd))
+template <int BITS, int NCH, int RPC, bool TAIL, int MODE, int UNROLL>
+__global__ __launch_bounds__(stream_waves(MODE) * kWave, (StreamCfg<BITS, NCH, RPC, UNROLL>::kWavesPerSimd))
 void decode_stream_kernel(DecodeArgs a, int y_f32)
 {
     constexpr int kStreamWaves = stream_waves(MODE), kStreamThreads = kStreamWaves * kWave;
-    using Cfg = StreamCfg<BITS, NCH, RPC>;
+    using Cfg = StreamCfg<BITS, NCH, RPC, UNROLL>;
     using Fmt = TableFmt<BITS>;
     static_assert(Fmt::kPair, "pair tables only");
     constexpr int U = Cfg::kUnroll, B = Cfg::kBatchRows, LPR = Cfg::kLanesPerRow;
@@ -510,28 +513,46 @@ void decode_stream_kernel(DecodeArgs a, int y_f32)
 
 // rows per wave: a multiple of the batch, sized so that the grid is a few
 // thousand waves (about 16 per CU) when the problem is large enough.
-template <int BITS, int NCH, int RPC, bool TAIL, int MODE>
-static hipError_t launch_stream_t(DecodeArgs a, int slots, bool y_f32, hipStream_t s)
+template <int BITS, int NCH, int RPC, bool TAIL, int MODE, int UNROLL>
+static hipError_t launch_stream_u(DecodeArgs a, int slots, bool y_f32, hipStream_t s)
 {
-    using Cfg = StreamCfg<BITS, NCH, RPC>;
+    using Cfg = StreamCfg<BITS, NCH, RPC, UNROLL>;
     using Fmt = TableFmt<BITS>;
-    constexpr int B = Cfg::kBatchRows;
-    const uint64_t total_rows = (uint64_t)a.N * slots;
-    uint32_t rpw = B;
-    while ((total_rows + rpw - 1) / rpw > 6144 && rpw < 64 * B) rpw += B;
-    a.rows_per_block = rpw;
-    constexpr int kStreamWaves = stream_waves(MODE), kStreamThreads = kStreamWaves * kWave;
-    const uint32_t waves = (a.N + rpw - 1) / rpw;
-    const size_t smem = MODE == 0 ? 0 : (size_t)(a.L + 1) * Fmt::kRowBytes + (size_t)a.L * Fmt::kRawBytes;
-    auto kern = decode_stream_kernel<BITS, NCH, RPC, TAIL, MODE>;
-    if (smem > 48 * 1024) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (err != hipSuccess) return err;
+    if constexpr (!Cfg::kFits) {
+        return hipErrorInvalidValue;
+    } else {
+        constexpr int B = Cfg::kBatchRows;
+        constexpr int kStreamWaves = stream_waves(MODE), kStreamThreads = kStreamWaves * kWave;
+        const uint64_t total_rows = (uint64_t)a.N * slots;
+        uint32_t rpw = B;
+        while ((total_rows + rpw - 1) / rpw > stream_max_waves(MODE) && rpw < 64 * B) rpw += B;
+        a.rows_per_block = rpw;
+        const uint32_t waves = (a.N + rpw - 1) / rpw;
+        const size_t smem = MODE == 0 ? 0 : (size_t)(a.L + 1) * Fmt::kRowBytes + (size_t)a.L * Fmt::kRawBytes;
+        auto kern = decode_stream_kernel<BITS, NCH, RPC, TAIL, MODE, UNROLL>;
+        if (smem > 48 * 1024) {
+            hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+            if (err != hipSuccess) return err;
+        }
+        dim3 grid((waves + kStreamWaves - 1) / kStreamWaves, slots);
+        hipLaunchKernelGGL(kern, grid, dim3(kStreamThreads), smem, s, a, (int)y_f32);
+        return hipGetLastError();
     }
-    dim3 grid((waves + kStreamWaves - 1) / kStreamWaves, slots);
-    hipLaunchKernelGGL(kern, grid, dim3(kStreamThreads), smem, s, a, (int)y_f32);
-    return hipGetLastError();
+}
+
+// Smallest batch (1, 2 or 4 row groups) with which every wave has ONE batch,
+// i.e. all of a wave's loads are issued up front; the largest the registers
+// allow when even that leaves more than the target number of waves.
+template <int BITS, int NCH, int RPC, bool TAIL, int MODE>
+static hipError_t launch_stream_t(const DecodeArgs &a, int slots, bool y_f32, hipStream_t s)
+{
+    const uint64_t groups = ((uint64_t)a.N * slots + RPC - 1) / RPC;
+    constexpr uint32_t W = stream_max_waves(MODE);
+    constexpr bool f2 = StreamCfg<BITS, NCH, RPC, 2>::kFits, f4 = StreamCfg<BITS, NCH, RPC, 4>::kFits;
+    if (groups <= W || !f2) return launch_stream_u<BITS, NCH, RPC, TAIL, MODE, 1>(a, slots, y_f32, s);
+    if (groups <= 2 * W || !f4) return launch_stream_u<BITS, NCH, RPC, TAIL, MODE, 2>(a, slots, y_f32, s);
+    return launch_stream_u<BITS, NCH, RPC, TAIL, MODE, 4>(a, slots, y_f32, s);
 }
 
 template <int BITS, int NCH, int RPC, bool TAIL>
