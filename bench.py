@@ -79,7 +79,8 @@ def build_workload(cfg: int, ring_bytes: int):
             return oracle.gemv_weights(W, xb, threads)
 
         return dict(name=xi.CONFIG_NAMES[cfg], step=step, bytes=nbytes, ring=R, oracle=oracle_once,
-                    launches=1, kernel_bytes=nbytes, keep=(ring, xd, y), M=M, N=W.N, K=W.K,
+                    launches=1 if M == 1 else 2,      # M > 1: x relayout kernel, then the decode kernel
+                    kernel_bytes=nbytes, keep=(ring, xd, y), M=M, N=W.N, K=W.K,
                     bits=W.bits, mode=W.mode)
 
     if cfg == 4:

@@ -170,16 +170,6 @@ __device__ __forceinline__ void to_operand_layout(uint32_t (&v)[4])
     lane_reg_exchange<0>(v[0], v[1], v[2], v[3]);
 }
 
-#ifdef XFP_EXP_TIMING
-// [tile pass 0..7][phase 0..7][wave 0..7] of workgroup 0; every stamp waits for the scalar and LDS queues
-__device__ unsigned long long g_bdbg[8 * 8 * 8 + 2 * 256 * 8];
-#define XFP_BSTAMP(ph) do { if (blockIdx.x == 100 && lane == 0 && npass < 8) g_bdbg[(npass * 8 + (ph)) * 8 + wave] = __builtin_amdgcn_s_memrealtime(); } while (0)
-#define XFP_WGSTAMP(which) do { if (lane == 0 && wave == 0 && blockIdx.x < 256) g_bdbg[512 + ((which) * 8 + (npass & 7)) * 256 + blockIdx.x] = __builtin_amdgcn_s_memrealtime(); } while (0)
-#else
-#define XFP_BSTAMP(ph) do { } while (0)
-#define XFP_WGSTAMP(which) do { } while (0)
-#endif
-
 struct BatchArgs {
     DecodeArgs a;
     const uint4 *xt;      // [K][16 tokens] fp16
@@ -279,10 +269,6 @@ __global__ __launch_bounds__(W * kWave) void decode_batch4_kernel(BatchArgs ta)
 
     uint32_t t = blockIdx.x;
     if (t >= ntiles) return;
-    uint32_t npass = 7;
-    (void)npass;
-    XFP_WGSTAMP(0);                                        // kernel entry (slot 7)
-    XFP_BSTAMP(0);
 
     // ---------------------------------------------------------------- prologue
     // Codebooks first (they gate the tables), then per group its activations (L2
@@ -292,7 +278,6 @@ __global__ __launch_bounds__(W * kWave) void decode_batch4_kernel(BatchArgs ta)
     TileRp rp_c = load_rp(t);
     const bool have1 = t + tstep < ntiles;
     TileRp rp_n = load_rp(have1 ? t + tstep : t);
-    XFP_BSTAMP(1);
     // Every workgroup reads the whole operand-ordered copy of x, all in the same
     // order, so every line would be a (merged) miss for all of them.  The L2 is
     // per XCD and workgroups are dealt to the 8 XCDs round-robin: wave w of the
@@ -324,17 +309,12 @@ __global__ __launch_bounds__(W * kWave) void decode_batch4_kernel(BatchArgs ta)
         }
     }
     asm volatile("" :: "v"(warm.x), "v"(warm.y), "v"(warm.z), "v"(warm.w));
-    XFP_BSTAMP(3);
     // a2: tables of the first tile.
     build_table(0);
-    XFP_BSTAMP(4);
     load_codebook(have1 ? t + tstep : t);
     uint32_t ocol = 0, oval = 0;
     load_colval(rp_c, ocol, oval);
-    XFP_BSTAMP(5);
     lds_barrier();
-    XFP_BSTAMP(6);
-    npass = 0;
     const uint32_t bank4 = (((q & 1) << 4) | i) * 4;       // this lane's private bank
 
 
@@ -346,8 +326,6 @@ __global__ __launch_bounds__(W * kWave) void decode_batch4_kernel(BatchArgs ta)
         const uint32_t n0 = tile * kTile;
         const uint32_t t1 = tile + tstep, t2 = tile + 2 * tstep;
         const bool have_next = t1 < ntiles, have2 = t2 < ntiles;
-        XFP_BSTAMP(0);
-        XFP_WGSTAMP(0);
         const TileRp rp_f = load_rp(have2 ? t2 : tile);    // two tiles ahead (scalar cache)
         const uint4 *nbase = tile_base(t1, have_next);
 
@@ -355,36 +333,17 @@ __global__ __launch_bounds__(W * kWave) void decode_batch4_kernel(BatchArgs ta)
         float4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
         const uint32_t sel = bank4 + P * 128;
         uint32_t pw[2][4];                                 // transposed pieces of the current and the next group
-#ifndef XFP_EXP_NO_GATHER
-#define XFP_EXP_NO_GATHER 0
-#endif
-#ifndef XFP_EXP_NO_COLVAL
-#define XFP_EXP_NO_COLVAL 0
-#endif
-#ifndef XFP_EXP_NO_BUILD
-#define XFP_EXP_NO_BUILD 0
-#endif
-#ifndef XFP_EXP_LOOKAHEAD
-#define XFP_EXP_LOOKAHEAD 2
-#endif
-        constexpr int LA = XFP_EXP_LOOKAHEAD;              // steps the lookups run ahead of the MFMAs
+        constexpr int LA = 2;             // steps the lookups run ahead of the MFMAs
         static_assert(LA >= 1 && LA <= 3, "a group is transposed while the previous one is still being looked up");
         uint32_t av[LA + 1][4];
         auto transpose_group = [&](int c) {
             uint32_t (&v)[4] = pw[c & 1];
             v[0] = iw[c].x; v[1] = iw[c].y; v[2] = iw[c].z; v[3] = iw[c].w;
-#ifndef XFP_EXP_NO_TRANSPOSE
             to_operand_layout(v);
-#endif
             load_group(c, nbase);                          // the registers are free: next tile's words
         };
         auto lookup = [&](int s, uint32_t (&v)[4]) {
             const uint32_t w = pw[(s / 4) & 1][s & 3];
-#ifdef XFP_EXP_NO_LOOKUP
-            v[0] = __builtin_amdgcn_perm(w, sel, 0x0c0c0400u); v[1] = __builtin_amdgcn_perm(w, sel, 0x0c0c0500u);
-            v[2] = __builtin_amdgcn_perm(w, sel, 0x0c0c0600u); v[3] = __builtin_amdgcn_perm(w, sel, 0x0c0c0700u);
-            return;
-#endif
             v[0] = *(lds_cu32_t *)(uintptr_t)__builtin_amdgcn_perm(w, sel, 0x0c0c0400u);
             v[1] = *(lds_cu32_t *)(uintptr_t)__builtin_amdgcn_perm(w, sel, 0x0c0c0500u);
             v[2] = *(lds_cu32_t *)(uintptr_t)__builtin_amdgcn_perm(w, sel, 0x0c0c0600u);
@@ -393,7 +352,6 @@ __global__ __launch_bounds__(W * kWave) void decode_batch4_kernel(BatchArgs ta)
         uint4 ox0 = make_uint4(0u, 0u, 0u, 0u), ox1 = ox0;     // x at this thread's outlier column
         constexpr int GATHER_STEP = NS >= 8 ? NS / 2 : 0;
         transpose_group(0);
-        XFP_BSTAMP(1);
 #pragma unroll
         for (int s = 0; s < LA && s < NS; ++s) lookup(s, av[s]);
 #pragma unroll
@@ -405,22 +363,17 @@ __global__ __launch_bounds__(W * kWave) void decode_batch4_kernel(BatchArgs ta)
             const uint32_t (&cur)[4] = av[s % (LA + 1)];
             half8_t af = __builtin_bit_cast(half8_t, u32x4_t{cur[0], cur[1], cur[2], cur[3]});
             half8_t bf = __builtin_bit_cast(half8_t, u32x4_t{xr[s][0], xr[s][1], xr[s][2], xr[s][3]});
-#ifdef XFP_EXP_NO_MFMA
-            acc0[0] += (float)af[0] + (float)bf[0];
-#else
             if (!RAGGED || g0 + s / 4 < G) {
                 if (s & 1) acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(af, bf, acc1, 0, 0, 0);
                 else acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(af, bf, acc0, 0, 0, 0);
             }
-#endif
-            if (s == GATHER_STEP && !XFP_EXP_NO_GATHER) {  // col of this tile arrived long ago
+            if (s == GATHER_STEP) {                      // col of this tile arrived long ago
                 ox0 = ta.xt[(size_t)ocol * 2];
                 ox1 = ta.xt[(size_t)ocol * 2 + 1];
             }
             __builtin_amdgcn_sched_barrier(0);
         }
 
-        XFP_BSTAMP(2);
         // ---- a7: outlier products of the first kProdCap entries -> LDS ----
         if (W * kWave <= kProdCap || tid < (uint32_t)kProdCap) {
             const float v = half_bits_to_float((uint16_t)oval);
@@ -433,11 +386,10 @@ __global__ __launch_bounds__(W * kWave) void decode_batch4_kernel(BatchArgs ta)
 #pragma unroll
             for (int g = 0; g < 4; ++g) dst[g] = float4_t{p[4 * g], p[4 * g + 1], p[4 * g + 2], p[4 * g + 3]};
         }
-        XFP_BSTAMP(3);
         // ---- tables of the next tile; loads that run one and two tiles ahead ----
-        if (have_next && !XFP_EXP_NO_BUILD) build_table(P ^ 1);
-        if (!XFP_EXP_NO_BUILD) load_codebook(have2 ? t2 : tile);
-        if (!XFP_EXP_NO_COLVAL) load_colval(rp_n, ocol, oval);   // next tile's entries
+        if (have_next) build_table(P ^ 1);
+        load_codebook(have2 ? t2 : tile);
+        load_colval(rp_n, ocol, oval);                     // next tile's entries
         // ---- partial D of this wave -> LDS, indexed by tile row ----
         {
             const float4_t d = acc0 + acc1;                // lane (m, q'), register r: operand row 4q' + r = tile row 4r + q'
@@ -445,9 +397,7 @@ __global__ __launch_bounds__(W * kWave) void decode_batch4_kernel(BatchArgs ta)
 #pragma unroll
             for (int r = 0; r < 4; ++r) *(lds_f32_t *)(uintptr_t)(rb + ((4 * r + q) * 16 + i) * 4) = d[r];
         }
-        XFP_BSTAMP(4);
         lds_barrier();
-        XFP_BSTAMP(5);
 
         // ---- a8: cross-wave sum, outlier fold, store (fixed order) ----
         // output (row, token m) is summed by the 4 lanes of a quad: lane j takes waves
@@ -496,9 +446,6 @@ __global__ __launch_bounds__(W * kWave) void decode_batch4_kernel(BatchArgs ta)
                 }
             }
         }
-        XFP_BSTAMP(6);
-        XFP_WGSTAMP(1);
-        ++npass;
         rp_c = rp_n;
         rp_n = rp_f;
     };
@@ -512,12 +459,6 @@ __global__ __launch_bounds__(W * kWave) void decode_batch4_kernel(BatchArgs ta)
         if (t >= ntiles) break;
     }
 }
-
-}  // namespace
-#ifdef XFP_EXP_TIMING
-extern "C" int xfp_exp_read_bdebug(void *dst, size_t bytes) { return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_bdbg), bytes); }
-#endif
-namespace {
 
 int device_cus()
 {
@@ -569,10 +510,6 @@ hipError_t launch_batch_t(const DecodeArgs &a, int M, bool y_f32, hipStream_t s)
     return hipGetLastError();
 }
 
-#ifndef XFP_EXP_BATCH_W16_FROM
-#define XFP_EXP_BATCH_W16_FROM 1000        // groups per row from which 16 waves share a tile (never: it spills)
-#endif
-
 template <int W, int NL>
 hipError_t launch_batch_n(const DecodeArgs &a, int M, bool y_f32, hipStream_t s)
 {
@@ -609,12 +546,11 @@ bool batch_supports(int bits, int mode, uint32_t K, int M)
     return bits == 4 && mode == 0 && M >= 2 && K % kGroup == 0 && K >= kGroup && K <= 8192;
 }
 
-// M <= 16 tokens per launch; the caller loops over chunks of 16.  Long rows are
-// shared by 16 waves (128 registers each, four waves per SIMD hide the lookup
-// latency), short rows by 8.
+// M <= 16 tokens per launch; the caller loops over chunks of 16.  Eight waves
+// share a tile of 16 rows: with 16 waves (128 registers each) the compiler
+// spills the in-flight index words and the kernel runs at half the speed.
 hipError_t launch_decode_batch(const DecodeArgs &a, int M, bool y_f32, hipStream_t s)
 {
-    if (a.K / kGroup >= XFP_EXP_BATCH_W16_FROM) return launch_batch_w<16>(a, M, y_f32, s);
     return launch_batch_w<8>(a, M, y_f32, s);
 }
 
