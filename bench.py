@@ -34,6 +34,7 @@ def parse_args():
     p.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2, the headline)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-graph", action="store_true", help="time eager launches instead of a graph")
+    p.add_argument("--no-plain-read", action="store_true", help="skip the read-only ceiling measurement")
     p.add_argument("--ring-bytes", type=int, default=RING_BYTES)
     p.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                    help="instead of the benchmark, run xfp_probe_copy over MIB mebibytes 20 times "
@@ -80,7 +81,7 @@ def build_workload(cfg: int, ring_bytes: int):
 
         return dict(name=xi.CONFIG_NAMES[cfg], step=step, bytes=nbytes, ring=R, oracle=oracle_once,
                     launches=1 if M == 1 else 2,      # M > 1: x relayout kernel, then the decode kernel
-                    kernel_bytes=nbytes, keep=(ring, xd, y), M=M, N=W.N, K=W.K,
+                    kernel_bytes=nbytes, launch_bytes=[nbytes], keep=(ring, xd, y), M=M, N=W.N, K=W.K,
                     bits=W.bits, mode=W.mode)
 
     if cfg == 4:
@@ -110,7 +111,7 @@ def build_workload(cfg: int, ring_bytes: int):
             return a, b
 
         return dict(name=xi.CONFIG_NAMES[4], step=step, bytes=b1 + b2, ring=draws, oracle=oracle_once,
-                    launches=2, kernel_bytes=b1, keep=(dgu, ddn, ids_dev, x1, x2, y1, y2), M=1,
+                    launches=2, kernel_bytes=b1, launch_bytes=[b1, b2], keep=(dgu, ddn, ids_dev, x1, x2, y1, y2), M=1,
                     N=gu.N, K=gu.K, bits=3, mode=0)
     raise SystemExit(f"no workload {cfg}")
 
@@ -125,6 +126,46 @@ def read_traffic(cfg: int):
     except OSError:
         pass
     return None
+
+
+def time_plain_read(launch_bytes, K, ring_bytes):
+    """us per step of xfp_probe_read over the same byte counts, one launch per decode launch, walking a
+    buffer of ring_bytes so that no cache holds the data; same graph replay and events as the decode."""
+    import torch
+
+    import paper_2605_14844_amd as xfp
+    buf = torch.empty(ring_bytes + max(launch_bytes) + 4096, dtype=torch.uint8, device="cuda")
+    buf.random_(0, 256)
+    sink = torch.zeros(4096, dtype=torch.int32, device="cuda")
+    state = {"off": 0}
+
+    def step():
+        for nb in launch_bytes:
+            nb16 = nb // 16 * 16
+            if state["off"] + nb16 > ring_bytes:
+                state["off"] = 0
+            xfp.xfp_probe_read(buf[state["off"]:], sink, nbytes=nb16)
+            state["off"] += (nb16 + 4095) // 4096 * 4096
+
+    for _ in range(20):
+        step()
+    stream = torch.cuda.current_stream()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            for _ in range(K):
+                step()
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+    g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    g0.record(stream)
+    graph.replay()
+    g1.record(stream)
+    torch.cuda.synchronize()
+    return g0.elapsed_time(g1) / K * 1e3
 
 
 def main():
@@ -215,6 +256,14 @@ def main():
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic},
     }
+
+    if not args.no_graph and not args.no_plain_read:
+        # practical ceiling: a read-only kernel over the same bytes per launch, in the same harness
+        pr_us = time_plain_read(wl["launch_bytes"], K, args.ring_bytes)
+        out["plain_read"] = {"us_per_step": round(pr_us, 3),
+                             "GB/s": round(sum(b // 16 * 16 for b in wl["launch_bytes"]) / pr_us / 1e3, 2),
+                             "decode_vs_plain_read": round(pr_us / (ms_per_step * 1e3), 4),
+                             "kernel": "probe_read_kernel, one launch per decode launch, same bytes"}
 
     if not args.no_cpu_baseline:
         import oracle

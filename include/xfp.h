@@ -131,9 +131,10 @@ int xfp_dequant_bulk(const xfp_weights *W, uint16_t *w_out, void *hip_stream);
 
 /*
  * Measurement helpers (no paper counterpart): stream `bytes` (a multiple of
- * 16, 16-byte aligned) once through the chip.  xfp_probe_read sums the words
- * and writes one uint32 per workgroup to `sink` (at least 4096 uint32);
- * xfp_probe_copy copies src to dst.  They calibrate achievable HBM bandwidth
+ * 16, 16-byte aligned) once through the chip.  xfp_probe_read only reads
+ * (four independent 16-byte loads per thread; `sink`, at least 4096 uint32,
+ * is written only if the XOR of all words a workgroup read equals one magic
+ * value, which keeps the loads alive); xfp_probe_copy copies src to dst.  They calibrate achievable HBM bandwidth
  * and the profiler's byte counters.
  */
 int xfp_probe_read(const void *src, uint64_t bytes, uint32_t *sink, void *hip_stream);

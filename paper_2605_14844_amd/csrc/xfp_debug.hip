@@ -96,21 +96,31 @@ hipError_t launch_dequant(int bits, int mode, const DecodeArgs &a, uint32_t E, u
 // ---- streaming probes -------------------------------------------------------
 constexpr int kProbeBlocks = 4096;
 
+// Plain streaming read: every thread has four independent 16-byte loads in
+// flight, a workgroup reads a contiguous 16 KB span per trip.  The XOR of the
+// words reaches `sink` only through a branch on its value, so the loads stay
+// alive and the kernel has no other work: this is the shape that read fastest
+// among those tried (one to eight loads per thread, 64 to 1024 threads,
+// persistent loops), and serves as the practical ceiling beside the decode kernels.
+constexpr int kProbeLoads = 4;
+
 __global__ __launch_bounds__(256) void probe_read_kernel(const uint4 *src, uint64_t n16, uint32_t *sink)
 {
+    typedef uint32_t u4 __attribute__((ext_vector_type(4)));
     uint32_t acc = 0;
-    for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (uint64_t)gridDim.x * 256) {
-        uint4 v = src[i];
-        acc += v.x ^ v.y ^ v.z ^ v.w;
+    const uint64_t span = 256ull * kProbeLoads;
+    for (uint64_t b = (uint64_t)blockIdx.x * span; b < n16; b += (uint64_t)gridDim.x * span) {
+        u4 v[kProbeLoads];
+#pragma unroll
+        for (int i = 0; i < kProbeLoads; ++i) {
+            uint64_t o = b + threadIdx.x + (uint64_t)i * 256;
+            o = o < n16 ? o : n16 - 1;
+            v[i] = __builtin_nontemporal_load(reinterpret_cast<const u4 *>(src) + o);
+        }
+#pragma unroll
+        for (int i = 0; i < kProbeLoads; ++i) acc ^= v[i].x ^ v[i].y ^ v[i].z ^ v[i].w;
     }
-    __shared__ uint32_t part[256];
-    part[threadIdx.x] = acc;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t t = 0;
-        for (int i = 0; i < 256; ++i) t ^= part[i];
-        sink[blockIdx.x] = t;                      // keeps the loads alive
-    }
+    if (acc == 0x9e3779b9u) sink[blockIdx.x & (kProbeBlocks - 1)] = acc;
 }
 
 __global__ __launch_bounds__(256) void probe_copy_kernel(const uint4 *src, uint4 *dst, uint64_t n16)
@@ -123,7 +133,8 @@ hipError_t launch_probe_read(const void *src, uint64_t bytes, uint32_t *sink, hi
 {
     uint64_t n16 = bytes / 16;
     if (n16 == 0) return hipSuccess;
-    unsigned blocks = (unsigned)((n16 + 255) / 256 < kProbeBlocks ? (n16 + 255) / 256 : kProbeBlocks);
+    const uint64_t span = 256ull * kProbeLoads, want = (n16 + span - 1) / span;
+    unsigned blocks = (unsigned)(want < 4ull * kProbeBlocks ? want : 4ull * kProbeBlocks);
     hipLaunchKernelGGL(probe_read_kernel, dim3(blocks), dim3(256), 0, s,
                        static_cast<const uint4 *>(src), n16, sink);
     return hipGetLastError();
