@@ -87,6 +87,20 @@ def test_workload_3_v2a_reduced_rows():
     check_gemv(W, xi.config_x(3, 1, W.K))
 
 
+# Full sizes, exactly what the benchmark launches (same generator, same call):
+# the oracle finishes every output of these in well under a minute on the host.
+def test_workload_2_full_size():
+    W = xi.config_weights(2)
+    assert (W.N, W.K, W.bits) == (8192, 4096, 4)
+    check_gemv(W, xi.config_x(2, 1, W.K))
+
+
+def test_workload_3_full_size():
+    W = xi.config_weights(3)
+    assert (W.N, W.K, W.bits, W.L) == (4096, 4096, 3, 32)
+    check_gemv(W, xi.config_x(3, 1, W.K))
+
+
 def test_results_are_run_to_run_deterministic():
     W = xi.random_weights(V2, 4, 256, 4096, density=0.003, seed=77)
     dW, xd = xfp.upload(W), dev_x(xi.activations(np.random.default_rng(1), 1, 4096))
@@ -140,7 +154,9 @@ def test_strided_x_and_y():
 # ------------------------------------------------------------------ batched
 @pytest.mark.parametrize("mode,bits,N,K,M", [(V2, 4, 200, 8192, 16), (V2, 4, 77, 1024, 5),
                                              (V2, 3, 64, 4096, 16), (V2A, 3, 48, 2048, 8),
-                                             (V2, 4, 33, 4096, 2), (V2, 4, 40, 2048, 33)])
+                                             (V2, 4, 33, 4096, 2), (V2, 4, 40, 2048, 33),
+                                             (V2, 4, 90, 1408, 16), (V2, 4, 50, 5120, 7),
+                                             (V2, 4, 4500, 128, 16), (V2, 4, 35, 7296, 3)])
 def test_batched_matches_oracle_and_single_calls(mode, bits, N, K, M):
     W = xi.random_weights(mode, bits, N, K, density=0.003, seed=M + N)
     x = xi.activations(np.random.default_rng(M), M, K)
@@ -151,8 +167,28 @@ def test_batched_matches_oracle_and_single_calls(mode, bits, N, K, M):
         assert gated_rel_err(yb[m], y1[0]) <= TOL_F32
 
 
+def test_batched_with_more_outliers_than_a_tile_keeps_on_chip():
+    """5 % outliers: a 16-row tile of K = 4096 holds about 3300 entries, far past the on-chip product
+    buffer, and one row alone holds every entry of its tile."""
+    W = xi.random_weights(V2, 4, 80, 4096, density=0.05, seed=77)
+    check_gemv(W, xi.activations(np.random.default_rng(70), 16, 4096))
+    K = 2048
+    W = xi.random_weights(V2, 4, 40, K, density=0.0, seed=78)
+    rp = np.zeros(41, dtype=np.int32)
+    rp[18:] = K                                                   # row 17 holds all K entries
+    W.out_row_ptr, W.out_col = rp, np.arange(K, dtype=np.int32)
+    W.out_val = xi.activations(np.random.default_rng(71), 1, K).ravel()
+    check_gemv(W, xi.activations(np.random.default_rng(72), 9, K))
+
+
 def test_workload_5_reduced_rows():
     W = xi.config_weights(5, N=2048)
+    check_gemv(W, xi.config_x(5, 16, W.K))
+
+
+def test_workload_5_full_size():
+    W = xi.config_weights(5)
+    assert (W.N, W.K, W.bits) == (28672, 8192, 4)
     check_gemv(W, xi.config_x(5, 16, W.K))
 
 
@@ -187,3 +223,19 @@ def test_workload_4_reduced_bank():
     assert gated_rel_err(y, oracle.gemv_moe(gu, ids, x1, shared_x=True)) <= TOL_F16
     y = host(xfp.xfp_gemv_moe(xfp.upload(dn), ids_d, dev_x(x2)))
     assert gated_rel_err(y, oracle.gemv_moe(dn, ids, x2, shared_x=False)) <= TOL_F16
+
+
+def test_workload_4_full_bank():
+    """All 256 experts resident, the routings the benchmark cycles through (first two draws)."""
+    gu, dn = xi.config_weights(4)
+    assert (gu.E, gu.N, gu.K, dn.N, dn.K) == (256, 2048, 4096, 4096, 1024)
+    dgu, ddn = xfp.upload(gu), xfp.upload(dn)
+    x1 = xi.config_x(4, 1, gu.K)
+    x2 = xi.activations(np.random.default_rng(xi.BASE_SEED + 404), 8, dn.K)
+    for draw in (0, 1):
+        ids = xi.config_expert_ids(4, 8, gu.E, draw=draw)
+        ids_d = torch.from_numpy(ids).cuda()
+        y = host(xfp.xfp_gemv_moe(dgu, ids_d, dev_x(x1)[0]))
+        assert gated_rel_err(y, oracle.gemv_moe(gu, ids, x1, shared_x=True)) <= TOL_F16
+        y = host(xfp.xfp_gemv_moe(ddn, ids_d, dev_x(x2)))
+        assert gated_rel_err(y, oracle.gemv_moe(dn, ids, x2, shared_x=False)) <= TOL_F16
