@@ -21,7 +21,9 @@
 //     quad-permute DPP + select              lane bits 1, 0  <->  register bits 1, 0
 // after which lane (i, q) holds, in register b, piece q of chunk b of tile row
 // pi(i) = 4 (i % 4) + i / 4.  The row permutation costs nothing: the tables and
-// the epilogue simply use pi.  12 to 20 VALU operations per 32 weights, no LDS.
+// the epilogue simply use pi.  12 to 20 VALU operations per 32 weights, no LDS
+// (the same permutation through ds_bpermute_b32 measured no faster: the LDS
+// pipe, busy with the lookups, is the scarcer resource).
 // The registers of a group are reloaded for the workgroup's next tile as soon
 // as they are transposed, so one tile of index words is always in flight.
 //
@@ -234,37 +236,39 @@ __global__ __launch_bounds__(W * kWave) void decode_batch4_kernel(BatchArgs ta)
         }
         return r;
     };
-    // Outlier entry `tid` of a tile: col/val through bounds-checked buffer loads
+    // Outlier entry `tid` of a tile: col and val through bounds-checked buffer loads
     // (entries past the end of the tile read as zero).
-    auto load_colval = [&](const TileRp &r, uint32_t &col, uint32_t &val) {
-        const int32_t cnt = r.end - r.base;
-        __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc((void *)(a.col + r.base), 0, cnt * 4, 0x00020000);
-        __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc((void *)(a.val + r.base), 0, cnt * 2, 0x00020000);
+    auto load_col = [&](const TileRp &r, uint32_t &col) {
+        __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc((void *)(a.col + r.base), 0, (r.end - r.base) * 4, 0x00020000);
         col = __builtin_amdgcn_raw_buffer_load_b32(rc, tid * 4, 0, 0);
+    };
+    auto load_val = [&](const TileRp &r, uint32_t &val) {
+        __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc((void *)(a.val + r.base), 0, (r.end - r.base) * 2, 0x00020000);
         val = __builtin_amdgcn_raw_buffer_load_b16(rv, tid * 2, 0, 0);
     };
     // Table builder role of this thread: slot tid % 32 (operand row i = slot % 16,
-    // i.e. tile row pi(i)); with tb = tid / 32 it writes the entries tb + 2W j
-    // (first index tb % 16, second index tb / 16 + (W / 8) j).
-    const uint32_t tb_slot = tid & 31, tb = tid >> 5;
+    // i.e. tile row pi(i)) and role tid / 32 = 4 rb + ra.  It writes the 16 entries
+    // whose first index is 4 ra + u and second index 4 rb + v (u, v = 0..3), for
+    // which it needs 4 + 4 codebook values: two 8-byte loads.  Two register sets,
+    // one per tile parity, so that a tile's codebook can be requested a whole pass
+    // before its tables are built.
+    static_assert(W == 8, "32 slots x 16 builder roles = 512 threads");
+    constexpr int NB = 16;                                 // table entries a thread writes per tile
+    const uint32_t tb_slot = tid & 31, tb_ra = (tid >> 5) & 3, tb_rb = tid >> 7;
     const uint32_t tb_row = 4 * (tb_slot & 3) + ((tb_slot & 15) >> 2);
-    uint32_t cbr[8], cblo = 0;
-    auto load_codebook = [&](uint32_t tile) {
+    uint2 cbl[2], cbh[2];
+    auto load_codebook = [&](int set, uint32_t tile) {
         const uint16_t *p = a.cb + (size_t)min(tile * kTile + tb_row, N - 1) * 16;
-        const uint4 v0 = reinterpret_cast<const uint4 *>(p)[0], v1 = reinterpret_cast<const uint4 *>(p)[1];
-        cbr[0] = v0.x; cbr[1] = v0.y; cbr[2] = v0.z; cbr[3] = v0.w;
-        cbr[4] = v1.x; cbr[5] = v1.y; cbr[6] = v1.z; cbr[7] = v1.w;
-        cblo = p[tb & 15];
+        cbl[set] = *reinterpret_cast<const uint2 *>(p + 4 * tb_ra);
+        cbh[set] = *reinterpret_cast<const uint2 *>(p + 4 * tb_rb);
     };
-    auto build_table = [&](uint32_t buf) {
-        const uint32_t base = lds0 + tb * 256 + (buf * 32 + tb_slot) * 4;
-#pragma unroll
-        for (int j = 0; j < 128 / W; ++j) {
-            uint32_t hi;
-            if constexpr (W == 8) hi = (j & 1) ? (cbr[j >> 1] & 0xFFFF0000u) : (cbr[j >> 1] << 16);   // second index j
-            else hi = (tb & 16) ? (cbr[j] & 0xFFFF0000u) : (cbr[j] << 16);                           // second index tb / 16 + 2 j
-            *(lds_u32_t *)(uintptr_t)(base + j * 2 * W * 256) = cblo | hi;
-        }
+    auto build_step = [&](uint32_t buf, int set, int j) {  // j = 4 v + u
+        const int u = j & 3, v = j >> 2;
+        const uint32_t base = lds0 + (4 * tb_ra + 64 * tb_rb) * 256 + (buf * 32 + tb_slot) * 4;
+        const uint32_t lw = u < 2 ? cbl[set].x : cbl[set].y, hw = v < 2 ? cbh[set].x : cbh[set].y;
+        const uint32_t lo = (u & 1) ? lw >> 16 : lw & 0xFFFFu;
+        const uint32_t hi = (v & 1) ? hw & 0xFFFF0000u : hw << 16;
+        *(lds_u32_t *)(uintptr_t)(base + (u + 16 * v) * 256) = lo | hi;
     };
 
     uint32_t t = blockIdx.x;
@@ -288,7 +292,7 @@ __global__ __launch_bounds__(W * kWave) void decode_batch4_kernel(BatchArgs ta)
         const uint32_t kib = ((blockIdx.x >> 3) * W + wave) % (K * kTile * 2 / 1024);
         warm = ta.xb[(size_t)kib * 64 + lane];
     }
-    load_codebook(t);
+    load_codebook(0, t);
     // a1: B operands.  Step s = 4 c + b contracts, in k block q, piece q of chunk b
     // of group g0 + c.
     uint32_t xr[NS][4];
@@ -310,20 +314,100 @@ __global__ __launch_bounds__(W * kWave) void decode_batch4_kernel(BatchArgs ta)
     }
     asm volatile("" :: "v"(warm.x), "v"(warm.y), "v"(warm.z), "v"(warm.w));
     // a2: tables of the first tile.
-    build_table(0);
-    load_codebook(have1 ? t + tstep : t);
+#pragma unroll
+    for (int j = 0; j < NB; ++j) build_step(0, 0, j);
+    load_codebook(1, have1 ? t + tstep : t);
     uint32_t ocol = 0, oval = 0;
-    load_colval(rp_c, ocol, oval);
+    load_col(rp_c, ocol);
+    load_val(rp_c, oval);
     lds_barrier();
     const uint32_t bank4 = (((q & 1) << 4) | i) * 4;       // this lane's private bank
 
 
     // ---------------------------------------------------------------- one tile
     // P = parity of the tile within this workgroup's sequence: table buffer,
-    // reduction and product buffers.
+    // codebook registers, reduction and product buffers.  Only the MFMA loop and
+    // one barrier are on a wave's critical path; everything else a tile needs is
+    // spread over the steps of a loop, where its VALU and LDS instructions fill
+    // the slots the lookups leave open.  Vector loads return in the order they
+    // were issued, so every load is issued BEFORE the index words that will be
+    // consumed ahead of it, and its consumer never waits for younger index words:
+    //   before step 0 : gather x at this tile's outlier columns (col came a pass ago);
+    //   step 1        : request col of the next tile and the codebook of the tile after;
+    //   steps NS/4 .. : the table of the NEXT tile, a few entries per step (other buffer);
+    //   late          : outlier products of this tile -> LDS (the gather is older
+    //                   than every index word of this tile), request val of the
+    //                   next tile; then cross-wave sum, outlier fold and store of
+    //                   the PREVIOUS tile (its partial sums and products sit in
+    //                   the other parity's buffers, complete since the barrier
+    //                   that ended its pass).
+    constexpr int BPS = (NB + NS - 1) / NS;                // table entries written per step
+    constexpr int BUILD_STEPS = (NB + BPS - 1) / BPS;      // steps that write table entries
+    constexpr int BUILD_FROM = NS >= 2 * BUILD_STEPS ? NS / 4 : 0;
+    constexpr int AHEAD_STEP = NS >= 8 ? 1 : 0;
+    constexpr int PROD_STEP = NS >= 16 ? NS - 4 : NS - 1;
+    constexpr int EPI_STEP = NS >= 16 ? NS - 2 : NS - 1;
+
+    // ---- a8: cross-wave sum, outlier fold, store (fixed order) ----
+    // output (row, token m) is summed by the 4 lanes of a quad: lane j takes waves
+    // j, j+4, ... and entries lo+j, lo+j+4, ...; a wave finishes row w (and w + 8).
+    struct Epi { float part[RPW][W / 4], pv[RPW][kRd]; int32_t lo[RPW], hi[RPW], hf[RPW]; };
+    const uint32_t sub = lane & 3, em = lane >> 2;
+    auto epi_read = [&](auto Ptag, const TileRp &r, Epi &e) {
+        constexpr int P = decltype(Ptag)::value;
+        const int32_t ob = r.base;
+        const uint32_t pbase = lds0 + kProd + P * kProdOne;
+        const uint32_t rbase = lds0 + kRed + P * kRedOne;
+#pragma unroll
+        for (int h = 0; h < RPW; ++h) {
+            const uint32_t o = (wave + W * h) * 16 + em;
+#pragma unroll
+            for (int j = 0; j < W / 4; ++j)
+                e.part[h][j] = *(lds_f32_t *)(uintptr_t)(rbase + (sub + 4 * j) * 1024 + o * 4);
+            e.lo[h] = r.lo[h] - ob;
+            e.hf[h] = r.hi[h] - ob;
+            e.hi[h] = min(e.hf[h], (int32_t)kProdCap);
+            // reads past the row's entries stay inside the padded buffer and are masked
+            const uint32_t eb = pbase + (uint32_t)(min(e.lo[h], (int32_t)kProdCap) + (int32_t)sub) * 64 + em * 4;
+#pragma unroll
+            for (int j = 0; j < kRd; ++j) e.pv[h][j] = *(lds_f32_t *)(uintptr_t)(eb + j * 256);
+        }
+    };
+    auto epi_sum = [&](auto Ptag, const TileRp &r, uint32_t n0, const Epi &e) {
+        constexpr int P = decltype(Ptag)::value;
+        const int32_t ob = r.base;
+        const uint32_t pbase = lds0 + kProd + P * kProdOne;
+        const uint16_t *xrow = a.x + (size_t)min(em, (uint32_t)M - 1) * a.x_stride;
+#pragma unroll
+        for (int h = 0; h < RPW; ++h) {
+            const uint32_t n = n0 + wave + W * h;
+            float s = e.part[h][0];
+#pragma unroll
+            for (int j = 1; j < W / 4; ++j) s += e.part[h][j];
+            const int32_t nv = e.hi[h] - e.lo[h] - (int32_t)sub;       // entry 4 j of this lane is valid iff 4 j < nv
+#pragma unroll
+            for (int j = 0; j < kRd; ++j) s += 4 * j < nv ? e.pv[h][j] : 0.f;
+            for (int32_t en = e.lo[h] + (int32_t)sub + 4 * kRd; en < e.hi[h]; en += 4)                    // long rows: rare
+                s += *(lds_f32_t *)(uintptr_t)(pbase + en * 64 + em * 4);
+            for (int32_t en = max(e.lo[h], (int32_t)kProdCap) + (int32_t)sub; en < e.hf[h]; en += 4)      // > kProdCap per tile: rare
+                s = fmaf(half_bits_to_float(a.val[ob + en]), half_bits_to_float(xrow[a.col[ob + en]]), s);
+            s = dpp_add<0xB1>(s);                          // quad_perm [1,0,3,2]
+            s = dpp_add<0x4E>(s);                          // quad_perm [2,3,0,1]
+            if (sub == 0 && n < N && em < (uint32_t)M) {
+                const int64_t oo = (int64_t)em * a.y_stride + n;
+                if (ta.y_f32) static_cast<float *>(a.y)[oo] = s;
+                else static_cast<_Float16 *>(a.y)[oo] = (_Float16)s;
+            }
+        }
+    };
+
+    TileRp rp_p = rp_c;                                    // previous tile (none yet)
+    uint32_t n0_p = 0;
+    bool have_prev = false;
+
     auto tile_pass = [&](auto Ptag, uint32_t tile) {
         constexpr int P = decltype(Ptag)::value;
-        const uint32_t n0 = tile * kTile;
+        using Prev = std::integral_constant<int, P ^ 1>;
         const uint32_t t1 = tile + tstep, t2 = tile + 2 * tstep;
         const bool have_next = t1 < ntiles, have2 = t2 < ntiles;
         const TileRp rp_f = load_rp(have2 ? t2 : tile);    // two tiles ahead (scalar cache)
@@ -333,7 +417,7 @@ __global__ __launch_bounds__(W * kWave) void decode_batch4_kernel(BatchArgs ta)
         float4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
         const uint32_t sel = bank4 + P * 128;
         uint32_t pw[2][4];                                 // transposed pieces of the current and the next group
-        constexpr int LA = 2;             // steps the lookups run ahead of the MFMAs
+        constexpr int LA = 2;                              // steps the lookups run ahead of the MFMAs
         static_assert(LA >= 1 && LA <= 3, "a group is transposed while the previous one is still being looked up");
         uint32_t av[LA + 1][4];
         auto transpose_group = [&](int c) {
@@ -349,8 +433,24 @@ __global__ __launch_bounds__(W * kWave) void decode_batch4_kernel(BatchArgs ta)
             v[2] = *(lds_cu32_t *)(uintptr_t)__builtin_amdgcn_perm(w, sel, 0x0c0c0600u);
             v[3] = *(lds_cu32_t *)(uintptr_t)__builtin_amdgcn_perm(w, sel, 0x0c0c0700u);
         };
+        // a7: outlier products of the first kProdCap entries -> LDS
         uint4 ox0 = make_uint4(0u, 0u, 0u, 0u), ox1 = ox0;     // x at this thread's outlier column
-        constexpr int GATHER_STEP = NS >= 8 ? NS / 2 : 0;
+        auto products = [&]() {
+            if (W * kWave <= kProdCap || tid < (uint32_t)kProdCap) {
+                const float v = half_bits_to_float((uint16_t)oval);
+                const uint32_t xw[8] = {ox0.x, ox0.y, ox0.z, ox0.w, ox1.x, ox1.y, ox1.z, ox1.w};
+                float p[16];
+#pragma unroll
+                for (int m = 0; m < 16; ++m)
+                    p[m] = v * half_bits_to_float((uint16_t)(m & 1 ? xw[m / 2] >> 16 : xw[m / 2] & 0xFFFFu));
+                lds_f4_t *dst = (lds_f4_t *)(uintptr_t)(lds0 + kProd + P * kProdOne + tid * 64);
+#pragma unroll
+                for (int g = 0; g < 4; ++g) dst[g] = float4_t{p[4 * g], p[4 * g + 1], p[4 * g + 2], p[4 * g + 3]};
+            }
+            load_val(rp_n, oval);                          // next tile's values
+        };
+        ox0 = ta.xt[(size_t)ocol * 2];
+        ox1 = ta.xt[(size_t)ocol * 2 + 1];
         transpose_group(0);
 #pragma unroll
         for (int s = 0; s < LA && s < NS; ++s) lookup(s, av[s]);
@@ -367,29 +467,23 @@ __global__ __launch_bounds__(W * kWave) void decode_batch4_kernel(BatchArgs ta)
                 if (s & 1) acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(af, bf, acc1, 0, 0, 0);
                 else acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(af, bf, acc0, 0, 0, 0);
             }
-            if (s == GATHER_STEP) {                      // col of this tile arrived long ago
-                ox0 = ta.xt[(size_t)ocol * 2];
-                ox1 = ta.xt[(size_t)ocol * 2 + 1];
+            if (s == AHEAD_STEP) {
+                load_col(rp_n, ocol);                      // next tile's columns
+                load_codebook(P, have2 ? t2 : tile);       // two tiles ahead: this parity's registers are free
+            }
+            if (s >= BUILD_FROM && s < BUILD_FROM + BUILD_STEPS) {
+#pragma unroll
+                for (int j = (s - BUILD_FROM) * BPS; j < (s - BUILD_FROM + 1) * BPS && j < NB; ++j) build_step(P ^ 1, P ^ 1, j);
+            }
+            if (s == PROD_STEP) products();
+            if (s == EPI_STEP && have_prev) {
+                Epi ep;
+                epi_read(Prev{}, rp_p, ep);
+                epi_sum(Prev{}, rp_p, n0_p, ep);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
 
-        // ---- a7: outlier products of the first kProdCap entries -> LDS ----
-        if (W * kWave <= kProdCap || tid < (uint32_t)kProdCap) {
-            const float v = half_bits_to_float((uint16_t)oval);
-            const uint32_t xw[8] = {ox0.x, ox0.y, ox0.z, ox0.w, ox1.x, ox1.y, ox1.z, ox1.w};
-            float p[16];
-#pragma unroll
-            for (int m = 0; m < 16; ++m)
-                p[m] = v * half_bits_to_float((uint16_t)(m & 1 ? xw[m / 2] >> 16 : xw[m / 2] & 0xFFFFu));
-            lds_f4_t *dst = (lds_f4_t *)(uintptr_t)(lds0 + kProd + P * kProdOne + tid * 64);
-#pragma unroll
-            for (int g = 0; g < 4; ++g) dst[g] = float4_t{p[4 * g], p[4 * g + 1], p[4 * g + 2], p[4 * g + 3]};
-        }
-        // ---- tables of the next tile; loads that run one and two tiles ahead ----
-        if (have_next) build_table(P ^ 1);
-        load_codebook(have2 ? t2 : tile);
-        load_colval(rp_n, ocol, oval);                     // next tile's entries
         // ---- partial D of this wave -> LDS, indexed by tile row ----
         {
             const float4_t d = acc0 + acc1;                // lane (m, q'), register r: operand row 4q' + r = tile row 4r + q'
@@ -398,65 +492,25 @@ __global__ __launch_bounds__(W * kWave) void decode_batch4_kernel(BatchArgs ta)
             for (int r = 0; r < 4; ++r) *(lds_f32_t *)(uintptr_t)(rb + ((4 * r + q) * 16 + i) * 4) = d[r];
         }
         lds_barrier();
-
-        // ---- a8: cross-wave sum, outlier fold, store (fixed order) ----
-        // output (row, token m) is summed by the 4 lanes of a quad: lane j takes waves
-        // j, j+4, ... and entries lo+j, lo+j+4, ...; a wave finishes row w (and w + 8).
-        {
-            const int32_t ob = rp_c.base;
-            const uint32_t pbase = lds0 + kProd + P * kProdOne;
-            const uint32_t rbase = lds0 + kRed + P * kRedOne;
-            const uint32_t sub = lane & 3, m = lane >> 2;
-            const uint16_t *xrow = a.x + (size_t)min(m, (uint32_t)M - 1) * a.x_stride;
-            float part[RPW][W / 4], pv[RPW][kRd];
-            int32_t lo[RPW], hi[RPW], hf[RPW];
-#pragma unroll
-            for (int h = 0; h < RPW; ++h) {                // issue every LDS read first
-                const uint32_t o = (wave + W * h) * 16 + m;
-#pragma unroll
-                for (int j = 0; j < W / 4; ++j)
-                    part[h][j] = *(lds_f32_t *)(uintptr_t)(rbase + (sub + 4 * j) * 1024 + o * 4);
-                lo[h] = rp_c.lo[h] - ob;
-                hf[h] = rp_c.hi[h] - ob;
-                hi[h] = min(hf[h], (int32_t)kProdCap);
-                // reads past the row's entries stay inside the padded buffer and are masked
-                const uint32_t eb = pbase + (uint32_t)(min(lo[h], (int32_t)kProdCap) + (int32_t)sub) * 64 + m * 4;
-#pragma unroll
-                for (int j = 0; j < kRd; ++j) pv[h][j] = *(lds_f32_t *)(uintptr_t)(eb + j * 256);
-            }
-#pragma unroll
-            for (int h = 0; h < RPW; ++h) {
-                const uint32_t n = n0 + wave + W * h;
-                float s = part[h][0];
-#pragma unroll
-                for (int j = 1; j < W / 4; ++j) s += part[h][j];
-                const int32_t nv = hi[h] - lo[h] - (int32_t)sub;       // entry 4 j of this lane is valid iff 4 j < nv
-#pragma unroll
-                for (int j = 0; j < kRd; ++j) s += 4 * j < nv ? pv[h][j] : 0.f;
-                for (int32_t en = lo[h] + (int32_t)sub + 4 * kRd; en < hi[h]; en += 4)                    // long rows: rare
-                    s += *(lds_f32_t *)(uintptr_t)(pbase + en * 64 + m * 4);
-                for (int32_t en = max(lo[h], (int32_t)kProdCap) + (int32_t)sub; en < hf[h]; en += 4)      // > kProdCap per tile: rare
-                    s = fmaf(half_bits_to_float(a.val[ob + en]), half_bits_to_float(xrow[a.col[ob + en]]), s);
-                s = dpp_add<0xB1>(s);                      // quad_perm [1,0,3,2]
-                s = dpp_add<0x4E>(s);                      // quad_perm [2,3,0,1]
-                if (sub == 0 && n < N && m < (uint32_t)M) {
-                    const int64_t oo = (int64_t)m * a.y_stride + n;
-                    if (ta.y_f32) static_cast<float *>(a.y)[oo] = s;
-                    else static_cast<_Float16 *>(a.y)[oo] = (_Float16)s;
-                }
-            }
-        }
+        rp_p = rp_c;
+        n0_p = tile * kTile;
+        have_prev = true;
         rp_c = rp_n;
         rp_n = rp_f;
+    };
+    auto last_epilogue = [&](auto Ptag) {
+        Epi ep;
+        epi_read(Ptag, rp_p, ep);
+        epi_sum(Ptag, rp_p, n0_p, ep);
     };
 
     for (;;) {
         tile_pass(std::integral_constant<int, 0>{}, t);
         t += tstep;
-        if (t >= ntiles) break;
+        if (t >= ntiles) { last_epilogue(std::integral_constant<int, 0>{}); break; }
         tile_pass(std::integral_constant<int, 1>{}, t);
         t += tstep;
-        if (t >= ntiles) break;
+        if (t >= ntiles) { last_epilogue(std::integral_constant<int, 1>{}); break; }
     }
 }
 
