@@ -103,6 +103,8 @@ int decode(const xfp_weights *W, const int32_t *eids, int slots, const void *x, 
     }
     if (xfp::stream_supports((int)W->bits, (int)W->mode, W->K, W->L))
         return finish(xfp::launch_decode_stream((int)W->bits, (int)W->mode, y_dtype == XFP_F32, a, slots, s));
+    if (const int S = xfp::splitk_slices((int)W->bits, (int)W->mode, W->N, W->K, W->L, slots))
+        return finish(xfp::launch_decode_splitk((int)W->bits, (int)W->mode, y_dtype == XFP_F32, a, slots, S, s));
     a.rows_per_block = rows_per_block(W->N, slots);
     return finish(xfp::launch_decode_rows((int)W->bits, (int)W->mode, y_dtype == XFP_F32, a, slots, s));
 }

@@ -32,6 +32,7 @@
 //    in flight and folded into the owning row's sum before the reduction.
 #include "xfp_device.h"
 
+#include <atomic>
 #include <type_traits>
 
 namespace xfp {
@@ -243,13 +244,17 @@ void decode_stream_kernel(DecodeArgs a, int y_f32)
     const uint32_t slot = blockIdx.y;
     const uint32_t e = a.eids ? (uint32_t)a.eids[slot] : 0u;
     const uint32_t N = a.N, K = a.K;
-    const uint32_t wpr = K / 32 * BITS;
-    const uint32_t G = K / kGroup;
-    const uint32_t *idx = a.idx + (size_t)e * N * wpr;
+    // split-K: this workgroup decodes columns [z K, (z + 1) K) of every row; only
+    // slice 0 folds the outliers (their columns index the whole activation row)
+    const uint32_t z = blockIdx.z;
+    const uint32_t wpr = a.row_words ? a.row_words : K / 32 * BITS;    // dwords of a full row
+    const uint32_t G = a.gid_row ? a.gid_row : K / kGroup;             // library ids of a full row
+    const uint32_t *idx = a.idx + (size_t)e * N * wpr + (size_t)z * (K / 32 * BITS);
     const uint32_t *cbw = reinterpret_cast<const uint32_t *>(a.cb) + (size_t)e * (MODE == 0 ? N : a.L) * (ENT / 2);
-    const uint8_t *gid = MODE == 1 ? a.gid + (size_t)e * N * G : nullptr;
+    const uint8_t *gid = MODE == 1 ? a.gid + (size_t)e * N * G + (size_t)z * (K / kGroup) : nullptr;
     const int32_t *rp = a.rp + (size_t)e * N;
-    const uint16_t *x = a.x + (int64_t)slot * a.x_stride;
+    const uint16_t *x = a.x + (int64_t)slot * a.x_stride + (size_t)z * K;
+    const bool with_outliers = z == 0;
 
     const bool live_last = !TAIL || ((NCH - 1) * kWave + lis) * kLaneWeights < K;
     const uint32_t unit_last = live_last ? (NCH - 1) * kWave + lis : 0u;
@@ -284,7 +289,7 @@ void decode_stream_kernel(DecodeArgs a, int y_f32)
     // which their consumers can start: row pointers (they gate the outlier
     // loads), codebooks (they gate the first lookup), activations, index words.
     // Lanes 0..B hold rp[rb + lane]: the CSR boundaries of the batch.
-    int32_t rpv = rp[min(row_begin + lane, N)];
+    int32_t rpv = with_outliers ? rp[min(row_begin + lane, N)] : 0;
     uint32_t cbv[CBW];
     if constexpr (MODE == 0) {
 #pragma unroll
@@ -408,7 +413,7 @@ void decode_stream_kernel(DecodeArgs a, int y_f32)
         }
         // next batch's row pointers and codebooks: issued now, consumed next pass
         if (rb + B < row_end) {
-            rpv = rp[min(rb + B + lane, N)];
+            rpv = with_outliers ? rp[min(rb + B + lane, N)] : 0;
             if constexpr (MODE == 0) {
 #pragma unroll
                 for (int i = 0; i < CBW; ++i)
@@ -500,7 +505,7 @@ void decode_stream_kernel(DecodeArgs a, int y_f32)
             const uint32_t row = rb + u * RPC + seg;
             float t = segment_sum<LPR>(sum[u]);
             if (lis == 0 && row < row_end) {
-                const int64_t o = (int64_t)slot * a.y_stride + row;
+                const int64_t o = (int64_t)z * a.z_stride + (int64_t)slot * a.y_stride + row;
                 if (y_f32) static_cast<float *>(a.y)[o] = t;
                 else static_cast<_Float16 *>(a.y)[o] = (_Float16)t;
             }
@@ -523,7 +528,8 @@ static hipError_t launch_stream_u(DecodeArgs a, int slots, bool y_f32, hipStream
     } else {
         constexpr int B = Cfg::kBatchRows;
         constexpr int kStreamWaves = stream_waves(MODE), kStreamThreads = kStreamWaves * kWave;
-        const uint64_t total_rows = (uint64_t)a.N * slots;
+        const uint32_t S = a.k_slices ? a.k_slices : 1u;
+        const uint64_t total_rows = (uint64_t)a.N * slots * S;
         uint32_t rpw = B;
         while ((total_rows + rpw - 1) / rpw > stream_max_waves(MODE) && rpw < 64 * B) rpw += B;
         a.rows_per_block = rpw;
@@ -535,7 +541,7 @@ static hipError_t launch_stream_u(DecodeArgs a, int slots, bool y_f32, hipStream
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
             if (err != hipSuccess) return err;
         }
-        dim3 grid((waves + kStreamWaves - 1) / kStreamWaves, slots);
+        dim3 grid((waves + kStreamWaves - 1) / kStreamWaves, slots, S);
         hipLaunchKernelGGL(kern, grid, dim3(kStreamThreads), smem, s, a, (int)y_f32);
         return hipGetLastError();
     }
@@ -547,7 +553,7 @@ static hipError_t launch_stream_u(DecodeArgs a, int slots, bool y_f32, hipStream
 template <int BITS, int NCH, int RPC, bool TAIL, int MODE>
 static hipError_t launch_stream_t(const DecodeArgs &a, int slots, bool y_f32, hipStream_t s)
 {
-    const uint64_t groups = ((uint64_t)a.N * slots + RPC - 1) / RPC;
+    const uint64_t groups = ((uint64_t)a.N * slots * (a.k_slices ? a.k_slices : 1u) + RPC - 1) / RPC;
     constexpr uint32_t W = stream_max_waves(MODE);
     constexpr bool f2 = StreamCfg<BITS, NCH, RPC, 2>::kFits, f4 = StreamCfg<BITS, NCH, RPC, 4>::kFits;
     if (groups <= W || !f2) return launch_stream_u<BITS, NCH, RPC, TAIL, MODE, 1>(a, slots, y_f32, s);
@@ -602,6 +608,69 @@ hipError_t launch_decode_stream(int bits, int mode, bool y_f32, const DecodeArgs
     case 3: return launch_stream_b<3>(a, mode, slots, y_f32, s);
     default: return launch_stream_b<4>(a, mode, slots, y_f32, s);
     }
+}
+
+// ---------------------------------------------------------------- split-K
+// Rows longer than the streaming kernel holds in registers (K > 16384) are cut
+// into S equal slices (S divides K / 128, a slice is at most 8192 columns so
+// that four waves fit a SIMD); grid z = slice.  Slice z writes fp32 partial sums
+// to its own plane of a file-scope buffer and a second kernel adds the planes in
+// slice order: deterministic, no atomics.  A ring of kSplitSlots buffers lets
+// that many split-K calls overlap on one GPU before a slot is reused.
+constexpr uint32_t kSplitFloats = 1u << 20;            // S * slots * N per call (4 MB per ring slot)
+constexpr int kSplitSlots = 4;
+__device__ __align__(256) float g_partial[kSplitSlots][kSplitFloats];
+
+__global__ __launch_bounds__(256) void splitk_sum_kernel(const float *part, uint32_t S, uint32_t N, uint32_t slots,
+                                                         void *y, int64_t y_stride, int y_f32)
+{
+    const uint32_t n = blockIdx.x * 256 + threadIdx.x, slot = blockIdx.y;
+    if (n >= N) return;
+    const size_t plane = (size_t)slots * N;
+    float s = part[(size_t)slot * N + n];
+    for (uint32_t z = 1; z < S; ++z) s += part[z * plane + (size_t)slot * N + n];
+    const int64_t o = (int64_t)slot * y_stride + n;
+    if (y_f32) static_cast<float *>(y)[o] = s;
+    else static_cast<_Float16 *>(y)[o] = (_Float16)s;
+}
+
+int splitk_slices(int bits, int mode, uint32_t N, uint32_t K, uint32_t L, int slots)
+{
+    const uint32_t G = K / kGroup;
+    for (uint32_t S = (K + 8191) / 8192; S <= 16; ++S) {
+        if (G % S != 0) continue;
+        if (!stream_supports(bits, mode, K / S, L)) return 0;
+        if ((uint64_t)S * (uint64_t)slots * N > kSplitFloats) return 0;
+        return (int)S;
+    }
+    return 0;
+}
+
+hipError_t launch_decode_splitk(int bits, int mode, bool y_f32, const DecodeArgs &a, int slots, int slices,
+                                hipStream_t s)
+{
+    static std::atomic<void *> ring{nullptr};          // device address of g_partial (one GPU per process)
+    void *p = ring.load(std::memory_order_relaxed);
+    if (!p) {
+        hipError_t err = hipGetSymbolAddress(&p, HIP_SYMBOL(g_partial));
+        if (err != hipSuccess) return err;
+        ring.store(p, std::memory_order_relaxed);
+    }
+    static std::atomic<unsigned> next_slot{0};
+    float *part = static_cast<float *>(p) + (size_t)(next_slot.fetch_add(1, std::memory_order_relaxed) % kSplitSlots) * kSplitFloats;
+    DecodeArgs c = a;
+    c.k_slices = (uint32_t)slices;
+    c.row_words = a.K / 32 * (uint32_t)bits;
+    c.gid_row = a.K / kGroup;
+    c.K = a.K / (uint32_t)slices;
+    c.y = part;
+    c.y_stride = a.N;
+    c.z_stride = (int64_t)slots * a.N;
+    hipError_t err = launch_decode_stream(bits, mode, true, c, slots, s);
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL(splitk_sum_kernel, dim3((a.N + 255) / 256, slots), dim3(256), 0, s, part, (uint32_t)slices, a.N,
+                       (uint32_t)slots, a.y, a.y_stride, (int)y_f32);
+    return hipGetLastError();
 }
 
 }  // namespace xfp

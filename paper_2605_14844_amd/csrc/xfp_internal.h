@@ -25,6 +25,12 @@ struct DecodeArgs {
     int64_t y_stride;
     uint32_t N, K, L;
     uint32_t rows_per_block;
+    // Split-K launches of the streaming kernel (zero otherwise): K above is then the
+    // length of one slice, workgroup z decodes columns [z K, (z + 1) K) of every row.
+    uint32_t k_slices;     // slices (grid z)
+    uint32_t row_words;    // dwords of a full index row
+    uint32_t gid_row;      // library ids of a full row
+    int64_t z_stride;      // slice z writes y + z * z_stride (fp32 partial sums)
 };
 
 // Launchers, one per kernel family (defined in the .hip files).
@@ -34,6 +40,13 @@ hipError_t launch_decode_rows(int bits, int mode, bool y_f32, const DecodeArgs &
 // registers, pair tables in LDS.
 bool stream_supports(int bits, int mode, uint32_t K, uint32_t L);
 hipError_t launch_decode_stream(int bits, int mode, bool y_f32, const DecodeArgs &a, int slots, hipStream_t s);
+// Split-K form of the streaming kernel for rows longer than it holds in registers:
+// S equal slices of K, fp32 partial sums in a file-scope device buffer, summed in
+// slice order by a second kernel.  splitk_slices returns S, or 0 if the shape does
+// not fit (then the general kernel runs).
+int splitk_slices(int bits, int mode, uint32_t N, uint32_t K, uint32_t L, int slots);
+hipError_t launch_decode_splitk(int bits, int mode, bool y_f32, const DecodeArgs &a, int slots, int slices,
+                                hipStream_t s);
 // Matrix-core kernel for 2..16 tokens per launch (V2, 4-bit, K <= 8192).
 bool batch_supports(int bits, int mode, uint32_t K, int M);
 hipError_t launch_decode_batch(const DecodeArgs &a, int M, bool y_f32, hipStream_t s);

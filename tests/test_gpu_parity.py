@@ -72,6 +72,30 @@ def test_gemv_m1_matches_oracle(mode, bits, N, K):
     check_gemv(W, x)
 
 
+# rows longer than the streaming kernel holds in registers: split-K (equal slices, partial sums
+# added in slice order), or the general kernel when K / 128 has no suitable divisor
+@pytest.mark.parametrize("mode,bits,N,K,M", [
+    (V2, 4, 200, 28672, 1), (V2, 4, 70, 20480, 1), (V2, 4, 33, 16512, 1), (V2, 4, 21, 16768, 1),
+    (V2, 3, 90, 24576, 1), (V2A, 3, 75, 32768, 1), (V2, 2, 40, 65536, 1), (V2A, 4, 50, 18432, 3),
+    (V2, 4, 64, 28672, 16)])
+def test_long_rows_split_k(mode, bits, N, K, M):
+    W = xi.random_weights(mode, bits, N, K, density=0.003, seed=N + bits)
+    check_gemv(W, xi.activations(np.random.default_rng(K), M, K))
+
+
+def test_long_rows_split_k_expert_indexed():
+    W = xi.random_weights(V2, 3, 48, 20480, E=5, density=0.002, seed=31)
+    ids = np.array([4, 0, 2, 4], dtype=np.int32)
+    ids_d = torch.from_numpy(ids).cuda()
+    xb = xi.activations(np.random.default_rng(32), len(ids), W.K)
+    dW = xfp.upload(W)
+    for shared in (True, False):
+        ref = oracle.gemv_moe(W, ids, xb[:1] if shared else xb, shared_x=shared)
+        xd = dev_x(xb)
+        y = host(xfp.xfp_gemv_moe(dW, ids_d, xd[0] if shared else xd, y_dtype=torch.float32))
+        assert gated_rel_err(y, ref) <= TOL_F32
+
+
 def test_workload_1_full():
     W = xi.config_weights(1)
     check_gemv(W, xi.config_x(1, 1, W.K))
