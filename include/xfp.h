@@ -120,6 +120,28 @@ int xfp_gemv_moe(const xfp_weights *bank, const int32_t *expert_ids, int T,
                  void *y, int y_dtype, int64_t ldy, void *hip_stream);
 
 /*
+ * Gate/up projection of a gated-MLP expert with its activation folded into the
+ * store: the bank's matrices stack the gate rows [0, N/2) on the up rows
+ * [N/2, N), and for each slot t
+ *     h[t][j] = SiLU(g) * u,   g = y[t][j],  u = y[t][N/2 + j],  SiLU(g) = g / (1 + exp(-g)),
+ * with y as xfp_gemv_moe defines it, kept in fp32 until the one rounding to
+ * h_dtype.  The paper's models are gated-MLP mixtures of experts (section 6.1)
+ * and it names kernel-launch overhead as what dominates a routed-expert layer
+ * (section 6); it does not describe this epilogue, which is this library's
+ * addition: one launch and no round trip of y through memory.
+ *
+ * bank->N must be even.  expert_ids may be NULL when bank->E == 1 (a dense
+ * gated MLP: slot t is token t).  h is [T][ldh], ldh >= N/2; everything else
+ * as for xfp_gemv_moe.  Shapes the streaming kernel does not take (K / 128
+ * without a split, oversized V2a libraries) run the plain decode into a static
+ * fp32 scratch plane plus a small kernel; XFP_ERR_UNSUPPORTED if T * N exceeds
+ * that plane (2^20 floats).
+ */
+int xfp_gemv_moe_silu_mul(const xfp_weights *bank, const int32_t *expert_ids, int T,
+                          const void *x, int64_t x_slot_stride,
+                          void *h, int h_dtype, int64_t ldh, void *hip_stream);
+
+/*
  * Parity hooks: the first two fused steps on their own (paper section 5,
  * steps 1 and 2), so that they can be compared bit for bit.
  * xfp_unpack_indices writes every index as one byte, idx_out [E*N][K].

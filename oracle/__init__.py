@@ -135,3 +135,15 @@ def gemv_moe(W, expert_ids, x, shared_x: bool, threads=None):
     if rc:
         raise ValueError(f"oracle gemv_moe rejected arguments ({rc})")
     return y
+
+
+def silu_mul(y: np.ndarray) -> np.ndarray:
+    """h[..., j] = SiLU(y[..., j]) * y[..., N/2 + j] in double, SiLU(g) = g / (1 + exp(-g)): the activation of a
+    gated-MLP expert (the paper's models, section 6.1, are mixtures of such experts; the paper does not print
+    the formula, this is the standard one) applied to a gate/up projection whose gate rows come first."""
+    y = np.asarray(y, dtype=np.float64)
+    half = y.shape[-1] // 2
+    assert y.shape[-1] == 2 * half
+    g, u = y[..., :half], y[..., half:]
+    with np.errstate(over="ignore"):
+        return g / (1.0 + np.exp(-g)) * u

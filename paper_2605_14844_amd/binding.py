@@ -57,13 +57,14 @@ def load_library():
     wp = ctypes.POINTER(xfp_weights)
     lib.xfp_gemv.argtypes = [wp, vp, i32, i64, vp, i32, i64, vp]
     lib.xfp_gemv_moe.argtypes = [wp, vp, i32, vp, i64, vp, i32, i64, vp]
+    lib.xfp_gemv_moe_silu_mul.argtypes = [wp, vp, i32, vp, i64, vp, i32, i64, vp]
     lib.xfp_unpack_indices.argtypes = [wp, vp, vp]
     lib.xfp_dequant_bulk.argtypes = [wp, vp, vp]
     lib.xfp_probe_read.argtypes = [vp, u64, vp, vp]
     lib.xfp_probe_copy.argtypes = [vp, vp, u64, vp]
     lib.xfp_strerror.argtypes = [i32]
     lib.xfp_strerror.restype = ctypes.c_char_p
-    for name in ("xfp_gemv", "xfp_gemv_moe", "xfp_unpack_indices", "xfp_dequant_bulk",
+    for name in ("xfp_gemv", "xfp_gemv_moe", "xfp_gemv_moe_silu_mul", "xfp_unpack_indices", "xfp_dequant_bulk",
                  "xfp_probe_read", "xfp_probe_copy", "xfp_version"):
         getattr(lib, name).restype = i32
     _lib = lib
@@ -182,6 +183,22 @@ def xfp_gemv_moe(bank: DeviceWeights, expert_ids: torch.Tensor, x: torch.Tensor,
                                        x_slot_stride, _ptr(y) if T else y.data_ptr(),
                                        _y_code(y.dtype), ldy, _stream(stream)))
     return y
+
+
+def xfp_gemv_moe_silu_mul(bank: DeviceWeights, expert_ids: Optional[torch.Tensor], x: torch.Tensor,
+                          h: Optional[torch.Tensor] = None, h_dtype=torch.float16, stream=None) -> torch.Tensor:
+    """h[t, j] = SiLU(y[t, j]) * y[t, N/2 + j] with y as xfp_gemv_moe gives it (gate rows first, then up rows).
+    expert_ids None: one matrix (bank.E == 1), slot t is row t of x."""
+    T = int(expert_ids.numel()) if expert_ids is not None else (1 if x.dim() == 1 else int(x.shape[0]))
+    shared = x.dim() == 1 or x.shape[0] == 1 and T != 1
+    x_slot_stride = 0 if shared else x.stride(0)
+    if h is None:
+        h = torch.empty((T, bank.N // 2), dtype=h_dtype, device=x.device)
+    ldh = h.stride(0) if h.dim() == 2 and T > 1 else bank.N // 2
+    _check(load_library().xfp_gemv_moe_silu_mul(
+        ctypes.byref(bank.desc), _ptr(expert_ids) if expert_ids is not None else None, T, _ptr(x), x_slot_stride,
+        _ptr(h) if T else h.data_ptr(), _y_code(h.dtype), ldh, _stream(stream)))
+    return h
 
 
 def xfp_unpack_indices(W: DeviceWeights, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:

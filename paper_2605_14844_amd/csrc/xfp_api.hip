@@ -109,6 +109,31 @@ int decode(const xfp_weights *W, const int32_t *eids, int slots, const void *x, 
     return finish(xfp::launch_decode_rows((int)W->bits, (int)W->mode, y_dtype == XFP_F32, a, slots, s));
 }
 
+// h[t][j] = SiLU(y[t][j]) * y[t][N/2 + j]: in the streaming kernel's store when it
+// takes the shape, else the plain decode into a scratch plane plus a small kernel.
+int decode_silu_mul(const xfp_weights *W, const int32_t *eids, int slots, const void *x, int64_t x_stride,
+                    void *h, int h_dtype, int64_t ldh, hipStream_t s)
+{
+    if (xfp::stream_supports((int)W->bits, (int)W->mode, W->K, W->L)) {
+        xfp::DecodeArgs a = base_args(W);
+        a.x = static_cast<const uint16_t *>(x);
+        a.y = h;
+        a.eids = eids;
+        a.x_stride = x_stride;
+        a.y_stride = ldh;
+        a.fuse_half = W->N / 2;
+        hipError_t err = xfp::launch_decode_stream((int)W->bits, (int)W->mode, h_dtype == XFP_F32, a, slots, s);
+        if (err != hipErrorInvalidValue) return finish(err);     // InvalidValue: no even batch fits, nothing launched
+    }
+    if ((uint64_t)slots * W->N > xfp::scratch_plane_floats()) return XFP_ERR_UNSUPPORTED;
+    hipError_t perr = hipSuccess;
+    float *plane = xfp::scratch_plane(&perr);
+    if (!plane) return finish(perr);
+    int rc = decode(W, eids, slots, x, x_stride, plane, XFP_F32, (int64_t)W->N, s);
+    if (rc) return rc;
+    return finish(xfp::launch_silu_mul(plane, W->N / 2, slots, h, ldh, h_dtype == XFP_F32, s));
+}
+
 }  // namespace
 
 extern "C" {
@@ -141,6 +166,25 @@ int xfp_gemv_moe(const xfp_weights *bank, const int32_t *expert_ids, int T, cons
     if (x_slot_stride % 8 != 0 || misaligned(expert_ids, 4)) return XFP_ERR_ALIGN;
     return decode(bank, expert_ids, T, x, x_slot_stride, y, y_dtype, ldy,
                   static_cast<hipStream_t>(hip_stream));
+}
+
+int xfp_gemv_moe_silu_mul(const xfp_weights *bank, const int32_t *expert_ids, int T, const void *x,
+                          int64_t x_slot_stride, void *h, int h_dtype, int64_t ldh, void *hip_stream)
+{
+    int rc = check_weights(bank);
+    if (rc) return rc;
+    if (bank->N % 2 != 0) return XFP_ERR_SHAPE;
+    if (T < 0 || T > 65535) return XFP_ERR_SHAPE;
+    if (T == 0) return XFP_OK;
+    if (!expert_ids && bank->E != 1) return XFP_ERR_NULL;
+    if (!x || !h) return XFP_ERR_NULL;
+    if (h_dtype != XFP_F16 && h_dtype != XFP_F32) return XFP_ERR_UNSUPPORTED;
+    if (ldh < (int64_t)(bank->N / 2)) return XFP_ERR_SHAPE;
+    if (x_slot_stride != 0 && x_slot_stride < (int64_t)bank->K) return XFP_ERR_SHAPE;
+    if (misaligned(x, 16) || misaligned(h, 16) || x_slot_stride % 8 != 0 || misaligned(expert_ids, 4))
+        return XFP_ERR_ALIGN;
+    return decode_silu_mul(bank, expert_ids, T, x, x_slot_stride, h, h_dtype, ldh,
+                           static_cast<hipStream_t>(hip_stream));
 }
 
 int xfp_unpack_indices(const xfp_weights *W, uint8_t *idx_out, void *hip_stream)

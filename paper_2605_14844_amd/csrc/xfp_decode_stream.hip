@@ -1,597 +1,16 @@
-// Streaming fused decode kernel, M = 1 per slot, V2 (one codebook per output
-// channel) and V2a (a library of codebooks plus one id per 128-weight group).
-// This is the fast path for the shapes decode actually sees.
-//
-// Work unit: one wave owns a run of output rows.  V2: a workgroup is a single
-// wave, so nothing ever waits at a barrier and every LDS address is a
-// compile-time constant that folds into the lookups' offset field.  V2a: a
-// workgroup is four waves that share the library's tables (one barrier after
-// they are built, none afterwards).  Design points, all for gfx950:
-//  - The activation row lives in VGPRs, not LDS: lane l always decodes the
-//    same k range of every row (32 consecutive k per 2048-wide chunk), so its
-//    32 activations per chunk are loaded once per wave and reused for every
-//    row.  This is the paper's activation-row caching (section 5) moved one
-//    level closer to the ALUs; it leaves the LDS pipe to the codebook lookups.
-//  - Index words are streamed with one 16-byte (4-bit), 12-byte (3-bit) or
-//    8-byte (2-bit) load per lane per chunk; a wave issues the loads of a
-//    whole batch of rows before it touches any of them, and no load is
-//    conditional (out-of-range rows and lanes read a clamped address).
-//  - Codebook lookups go to LDS.  4-bit: the row's 16 fp16 entries as they
-//    are (8 dwords = 8 banks, equal addresses broadcast, so no conflicts);
-//    the byte address of an entry is produced by one SDWA shift per index.
-//    A pair table (two indices -> two fp16 in one dword) is built per row
-//    (V2) or per library codebook (V2a, once per workgroup), so one lookup and
-//    one v_dot2_f32_f16 serve two weights.  V2a: the group's library id picks
-//    the table per lane; it is OR-ed into the lookup address.
-//  - Lookups are software-pipelined in groups of eight: the addresses and LDS
-//    reads of group t+1 are issued before the multiply-accumulates of group t.
-//  - fp32 accumulation in a fixed order, DPP reduction, no atomics: results
-//    are run-to-run deterministic.
-//  - The CSR outliers of a batch of rows are contiguous; they are fetched with
-//    one bounds-checked buffer load per lane while the index stream is still
-//    in flight and folded into the owning row's sum before the reduction.
-#include "xfp_device.h"
+// Streaming fused decode, plain variant, plus what the variants share on the
+// host side: shape support, split-K launch and its sum kernel, the fp32 scratch
+// ring, the unfused SiLU(gate) * up kernel.  The kernel itself is in
+// xfp_decode_stream.inc.h.
+#include "xfp_decode_stream.inc.h"
 
 #include <atomic>
-#include <type_traits>
 
 namespace xfp {
 
-typedef __attribute__((address_space(3))) const uint16_t lds_u16_t;
-typedef __attribute__((address_space(3))) const uint32_t lds_u32_t;
-typedef __attribute__((address_space(3))) uint32_t lds_u32_w_t;
-
-#define XFP_SDWA_BYTE(op, dst, amount, src, J)                                                   \
-    asm(op " %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_" #J     \
-        : "=v"(dst) : "v"(amount), "v"(src))
-
-// (byte j of m) << amount and (byte j of m) >> amount in one VALU op each.
-// j must be a compile-time constant after unrolling.
-__device__ __forceinline__ uint32_t byte_shl(uint32_t m, int j, uint32_t amount)
-{
-    uint32_t r;
-    switch (j) {
-    case 0: XFP_SDWA_BYTE("v_lshlrev_b32_sdwa", r, amount, m, 0); break;
-    case 1: XFP_SDWA_BYTE("v_lshlrev_b32_sdwa", r, amount, m, 1); break;
-    case 2: XFP_SDWA_BYTE("v_lshlrev_b32_sdwa", r, amount, m, 2); break;
-    default: XFP_SDWA_BYTE("v_lshlrev_b32_sdwa", r, amount, m, 3); break;
-    }
-    return r;
-}
-__device__ __forceinline__ uint32_t byte_shr(uint32_t m, int j, uint32_t amount)
-{
-    uint32_t r;
-    switch (j) {
-    case 0: XFP_SDWA_BYTE("v_lshrrev_b32_sdwa", r, amount, m, 0); break;
-    case 1: XFP_SDWA_BYTE("v_lshrrev_b32_sdwa", r, amount, m, 1); break;
-    case 2: XFP_SDWA_BYTE("v_lshrrev_b32_sdwa", r, amount, m, 2); break;
-    default: XFP_SDWA_BYTE("v_lshrrev_b32_sdwa", r, amount, m, 3); break;
-    }
-    return r;
-}
-
-__device__ __forceinline__ float fma_h(_Float16 c, _Float16 x, float acc)
-{
-    return __builtin_fmaf((float)c, (float)x, acc);     // v_fma_mix_f32
-}
-
-#ifndef XFP_B4_PAIR
-#define XFP_B4_PAIR 1
-#endif
-
-// Geometry of the per-row LDS table for each bit width.  A pair table maps two
-// adjacent indices (4, 6 or 8 stream bits) to two fp16 values in one dword.
-template <int BITS>
-struct TableFmt {
-    static constexpr int kEntries = 1 << BITS;
-    static constexpr bool kPair = BITS != 4 || XFP_B4_PAIR;
-    static constexpr int kRowBytes = kPair ? (4 << (2 * BITS)) : 2 * kEntries;   // 64, 256, 1024 (32 unpaired)
-    static constexpr int kRawBytes = 2 * kEntries;                              // 8, 16, 32
-    static constexpr int kGroupsPerLaneLoad = kPair ? 2 : 4;                    // groups of 8 lookups
-};
-
-// Eight lookups of one lane-load: compute LDS addresses and issue the reads.
-//   tb    LDS byte address of the table (wave-uniform, folds into the offset field)
-//   bias  per-lane table selector added on top of tb when BIASED: the number of
-//         tables to skip (row of a multi-row chunk, or the all-zero table for
-//         lanes past the end of a short row).  It is OR-ed into the index bytes
-//         (4-/2-bit) or the address (3-bit), which costs no extra instruction.
-//         WIDE: the selector may exceed 15 (a V2a library id); for 2-bit indices
-//         it is then OR-ed into the address instead of the index bytes.
-template <int BITS, bool BIASED, bool WIDE = false>
-__device__ __forceinline__ void issue_group(const LaneWords<BITS> &lw, int g, uint32_t tb, uint32_t bias,
-                                            uint32_t (&v)[8], uint32_t k1, uint32_t k2, uint32_t k3)
-{
-    if constexpr (BITS == 4 && TableFmt<4>::kPair) {
-        // an index byte (two indices) selects one dword of the row's 256-entry pair table
-        const uint32_t ab = BIASED ? bias * TableFmt<4>::kRowBytes : 0u;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const uint32_t a = byte_shl(lw.w[2 * g + (i >> 2)], i & 3, k2);   // byte * 4
-            v[i] = *(lds_u32_t *)(uintptr_t)(tb + (BIASED ? (a | ab) : a));
-        }
-    } else if constexpr (BITS == 4) {
-        const uint32_t w = lw.w[g];
-        uint32_t m0, m1;
-        if constexpr (BIASED) {
-            const uint32_t bb = bias * 0x10101010u;
-            m0 = (w & 0x0F0F0F0Fu) | bb;
-            m1 = ((w >> 4) & 0x0F0F0F0Fu) | bb;
-        } else {
-            m0 = w & 0x0F0F0F0Fu;
-            m1 = w & 0xF0F0F0F0u;
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const uint32_t a0 = byte_shl(m0, j, k1);                       // index * 2
-            const uint32_t a1 = BIASED ? byte_shl(m1, j, k1) : byte_shr(m1, j, k3);
-            v[2 * j] = *(lds_u16_t *)(uintptr_t)(tb + a0);
-            v[2 * j + 1] = *(lds_u16_t *)(uintptr_t)(tb + a1);
-        }
-    } else if constexpr (BITS == 3) {
-        const uint32_t ab = BIASED ? bias * TableFmt<3>::kRowBytes : 0u;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int bit = 6 * (g * 8 + i), word = bit / 32, sh = bit % 32;   // pair = 6 stream bits
-            uint32_t t;
-            if (sh + 6 <= 32) t = sh >= 2 ? lw.w[word] >> (sh - 2) : lw.w[word] << (2 - sh);
-            else t = __builtin_amdgcn_alignbit(lw.w[(word + 1) % 3], lw.w[word], sh - 2);
-            const uint32_t a = BIASED ? ((t & 0xFCu) | ab) : (t & 0xFCu);      // pair index * 4
-            v[i] = *(lds_u32_t *)(uintptr_t)(tb + a);
-        }
-    } else {
-        const uint32_t w = lw.w[g];
-        uint32_t m0, m1;
-        const uint32_t ab = (BIASED && WIDE) ? bias * TableFmt<2>::kRowBytes : 0u;
-        if constexpr (BIASED) {
-            const uint32_t bb = WIDE ? 0u : bias * 0x10101010u;
-            m0 = (w & 0x0F0F0F0Fu) | bb;
-            m1 = ((w >> 4) & 0x0F0F0F0Fu) | bb;
-        } else {
-            m0 = w & 0x0F0F0F0Fu;
-            m1 = w & 0xF0F0F0F0u;
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            uint32_t a0 = byte_shl(m0, j, k2);                             // nibble (= pair) * 4
-            uint32_t a1 = BIASED ? byte_shl(m1, j, k2) : byte_shr(m1, j, k2);
-            if constexpr (BIASED && WIDE) { a0 |= ab; a1 |= ab; }
-            v[2 * j] = *(lds_u32_t *)(uintptr_t)(tb + a0);
-            v[2 * j + 1] = *(lds_u32_t *)(uintptr_t)(tb + a1);
-        }
-    }
-}
-
-// Multiply-accumulate the eight looked-up values of group g against the
-// matching activations xw[0..15] of the lane-load.
-template <int BITS>
-__device__ __forceinline__ void consume_group(int g, const uint32_t (&v)[8], const uint32_t *xw, float (&acc)[4])
-{
-    if constexpr (BITS == 4 && !TableFmt<4>::kPair) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const half2_t xp = as_half2(xw[g * 4 + j]);
-            acc[(2 * j) & 3] = fma_h(as_half2(v[2 * j]).x, xp.x, acc[(2 * j) & 3]);
-            acc[(2 * j + 1) & 3] = fma_h(as_half2(v[2 * j + 1]).x, xp.y, acc[(2 * j + 1) & 3]);
-        }
-    } else {
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-            acc[i & 3] = dot2(as_half2(v[i]), as_half2(xw[g * 8 + i]), acc[i & 3]);
-    }
-}
-
-// NCH : 2048-wide chunks per row (RPC == 1), K <= NCH * 2048
-// RPC : rows per chunk (K == 2048 / RPC exactly) for short rows; then NCH == 1
-// TAIL: K is not a multiple of 2048 (RPC == 1): lanes past the row's end in the
-//       last chunk read a clamped address, zero activations and the zero table
-constexpr int stream_waves(int mode) { return mode == 0 ? 1 : 4; }   // waves per workgroup
-// waves a launch aims for at most (measured: V2 is fastest with about 16 single-wave
-// workgroups per CU, V2a with about 2 four-wave workgroups)
-constexpr uint32_t stream_max_waves(int mode) { return mode == 0 ? 6144 : 3072; }
-
-// U: row groups a wave decodes at once (all their loads are issued before the
-// first is touched).  The launcher picks the smallest U that lets every wave
-// finish its rows in ONE batch, so that nothing is loaded late.
-template <int BITS, int NCH, int RPC, int U_>
-struct StreamCfg {
-    static constexpr int kUnroll = U_;
-    static constexpr int kBatchRows = kUnroll * RPC;           // rows a wave decodes at once
-    static constexpr int kLanesPerRow = kWave / RPC;
-    static constexpr int kTableBytes = (kBatchRows + 1) * TableFmt<BITS>::kRowBytes;   // + zero table
-    static constexpr int kRawBytes = TableFmt<BITS>::kPair ? kBatchRows * TableFmt<BITS>::kRawBytes : 0;
-    // registers: 16 per chunk for x, BITS per lane-load in flight, ~60 working
-    static constexpr int kRegs = 16 * NCH + BITS * NCH * kUnroll + 60;
-    static constexpr int kWavesPerSimd = kRegs <= 128 ? 4 : (kRegs <= 168 ? 3 : 2);
-    // largest U the registers allow (x: 16 per chunk; index words: BITS per chunk and row group)
-    static constexpr bool kFits = BITS * NCH * kUnroll <= 64 && kRegs <= 250;
-};
-
-// LDS byte address of a static array of BYTES bytes (one per instantiation).
-template <int BYTES>
-__device__ __forceinline__ uint32_t static_lds()
-{
-    __shared__ __align__(16) unsigned char buf[BYTES];
-    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)buf;
-}
-
-template <int BITS, int NCH, int RPC, bool TAIL, int MODE, int UNROLL>
-__global__ __launch_bounds__(stream_waves(MODE) * kWave, (StreamCfg<BITS, NCH, RPC, UNROLL>::kWavesPerSimd))
-void decode_stream_kernel(DecodeArgs a, int y_f32)
-{
-    constexpr int kStreamWaves = stream_waves(MODE), kStreamThreads = kStreamWaves * kWave;
-    using Cfg = StreamCfg<BITS, NCH, RPC, UNROLL>;
-    using Fmt = TableFmt<BITS>;
-    static_assert(Fmt::kPair, "pair tables only");
-    constexpr int U = Cfg::kUnroll, B = Cfg::kBatchRows, LPR = Cfg::kLanesPerRow;
-    constexpr int ENT = Fmt::kEntries, GPL = Fmt::kGroupsPerLaneLoad;
-    // V2: the wave's tables, a static array.  V2a: the library's tables fill the
-    // dynamic segment, which starts at LDS address 0 because this instantiation
-    // has no static LDS; a constant base keeps the lookups free of address adds.
-    uint32_t lds_base = 0u;
-    if constexpr (MODE == 0) {
-        lds_base = static_lds<Cfg::kTableBytes + Cfg::kRawBytes + 16>();
-    } else {
-        extern __shared__ __align__(16) unsigned char lds_dyn[];
-        if ((uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds_dyn != 0u) return;
-    }
-    const uint32_t lds0 = lds_base;
-
-    const uint32_t lane = threadIdx.x & (kWave - 1);
-    const uint32_t wv = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    const uint32_t seg = RPC > 1 ? lane / LPR : 0u;            // which row of a chunk this lane is in
-    const uint32_t lis = RPC > 1 ? lane % LPR : lane;          // lane within its row
-    const uint32_t slot = blockIdx.y;
-    const uint32_t e = a.eids ? (uint32_t)a.eids[slot] : 0u;
-    const uint32_t N = a.N, K = a.K;
-    // split-K: this workgroup decodes columns [z K, (z + 1) K) of every row; only
-    // slice 0 folds the outliers (their columns index the whole activation row)
-    const uint32_t z = blockIdx.z;
-    const uint32_t wpr = a.row_words ? a.row_words : K / 32 * BITS;    // dwords of a full row
-    const uint32_t G = a.gid_row ? a.gid_row : K / kGroup;             // library ids of a full row
-    const uint32_t *idx = a.idx + (size_t)e * N * wpr + (size_t)z * (K / 32 * BITS);
-    const uint32_t *cbw = reinterpret_cast<const uint32_t *>(a.cb) + (size_t)e * (MODE == 0 ? N : a.L) * (ENT / 2);
-    const uint8_t *gid = MODE == 1 ? a.gid + (size_t)e * N * G + (size_t)z * (K / kGroup) : nullptr;
-    const int32_t *rp = a.rp + (size_t)e * N;
-    const uint16_t *x = a.x + (int64_t)slot * a.x_stride + (size_t)z * K;
-    const bool with_outliers = z == 0;
-
-    const bool live_last = !TAIL || ((NCH - 1) * kWave + lis) * kLaneWeights < K;
-    const uint32_t unit_last = live_last ? (NCH - 1) * kWave + lis : 0u;
-
-    // Rows of this wave.  A wave past the end of the matrix still runs the
-    // prologue (every address below is clamped into the matrix) and leaves
-    // before the row loop.
-    const uint32_t row_begin = (blockIdx.x * kStreamWaves + wv) * a.rows_per_block;
-    const uint32_t row_end = min(N, row_begin + a.rows_per_block);
-    const uint32_t cb_last = min(N, max(row_end, 1u)) * (ENT / 2) - 1;   // last valid codebook dword
-    const uint32_t k1 = 1, k2 = 2, k3 = 3;
-    constexpr int CBW = (B * (ENT / 2) + kWave - 1) / kWave;   // codebook dwords per lane per batch
-
-    // a3: the index words (and V2a library ids) of one batch of rows; rows past
-    // the end are clamped to the last row and never stored.
-    LaneWords<BITS> lw[U][NCH];
-    uint32_t lib[MODE == 1 ? U : 1][MODE == 1 ? NCH : 1];
-    auto load_batch = [&](uint32_t rb) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint32_t row = min(rb + u * RPC + seg, N - 1);
-#pragma unroll
-            for (int c = 0; c < NCH; ++c) {
-                const uint32_t unit = c == NCH - 1 ? unit_last : c * kWave + lis;
-                lw[u][c] = load_lane_words<BITS>(idx + (size_t)row * wpr + (size_t)unit * BITS);
-                if constexpr (MODE == 1) lib[u][c] = gid[(size_t)row * G + unit / (kGroup / kLaneWeights)];
-            }
-        }
-    };
-
-    // Vector loads complete in issue order, so the order below is the order in
-    // which their consumers can start: row pointers (they gate the outlier
-    // loads), codebooks (they gate the first lookup), activations, index words.
-    // Lanes 0..B hold rp[rb + lane]: the CSR boundaries of the batch.
-    int32_t rpv = with_outliers ? rp[min(row_begin + lane, N)] : 0;
-    uint32_t cbv[CBW];
-    if constexpr (MODE == 0) {
-#pragma unroll
-        for (int i = 0; i < CBW; ++i) cbv[i] = cbw[min(row_begin * (ENT / 2) + i * kWave + lane, cb_last)];
-    }
-    __builtin_amdgcn_sched_barrier(0);
-
-    // a1: this lane's activations, once per wave.
-    uint32_t xr[NCH][16];
-#pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-        const uint32_t unit = c == NCH - 1 ? unit_last : c * kWave + lis;   // 32-weight unit in the row
-        const uint4 *xp = reinterpret_cast<const uint4 *>(x + (size_t)unit * kLaneWeights);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            uint4 v = xp[i];
-            xr[c][4 * i] = v.x; xr[c][4 * i + 1] = v.y; xr[c][4 * i + 2] = v.z; xr[c][4 * i + 3] = v.w;
-        }
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    load_batch(row_begin);
-    __builtin_amdgcn_sched_barrier(0);
-
-    if constexpr (MODE == 1) {
-        // a2 (V2a): the library's pair tables, once per workgroup, while the first
-        // loads are in flight.  Table l sits at l * kRowBytes; table L is all zero
-        // (lanes past the end of a short row).
-        const uint32_t L = a.L;
-        const uint32_t raw_base = lds0 + (L + 1) * Fmt::kRowBytes;
-        for (uint32_t i = threadIdx.x; i < L * (ENT / 2); i += kStreamThreads)
-            *(lds_u32_w_t *)(uintptr_t)(raw_base + i * 4) = cbw[i];
-        __syncthreads();
-        constexpr uint32_t PE = 1u << (2 * BITS);              // pair entries per table
-        for (uint32_t i = threadIdx.x; i < (L + 1) * PE; i += kStreamThreads) {
-            const uint32_t l = i / PE, pe = i % PE;
-            uint32_t v = 0u;
-            if (l < L) {
-                const uint32_t lo = *(lds_u16_t *)(uintptr_t)(raw_base + (l * ENT + (pe & (ENT - 1))) * 2);
-                const uint32_t hi = *(lds_u16_t *)(uintptr_t)(raw_base + (l * ENT + (pe >> BITS)) * 2);
-                v = lo | (hi << 16);
-            }
-            *(lds_u32_w_t *)(uintptr_t)(lds0 + i * 4) = v;
-        }
-        __syncthreads();
-    } else if constexpr (TAIL) {
-        // the all-zero table that lanes past the end of the row look up
-#pragma unroll
-        for (int i = lane; i < Fmt::kRowBytes / 4; i += kWave)
-            *(lds_u32_w_t *)(uintptr_t)(lds_base + B * Fmt::kRowBytes + i * 4) = 0u;
-    }
-    if (row_begin >= N) return;
-
-    // One batch of rows.  FIRST: its index words were loaded in the prologue.
-    auto pass = [&](auto first, uint32_t rb) {
-        if constexpr (!decltype(first)::value) {
-            load_batch(rb);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        // a7 (issue): the CSR entries of the batch are contiguous.  Each lane
-        // takes one entry per row group through a bounds-checked buffer load
-        // (offsets past the end read as zero): no loop, no branch.
-        const int32_t ob0 = __builtin_amdgcn_readlane(rpv, 0);       // entry range of the batch
-        const int32_t ob1 = __builtin_amdgcn_readlane(rpv, B);
-        __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc(
-            (void *)(a.col + ob0), 0, (ob1 - ob0) * 4, 0x00020000);
-        __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(
-            (void *)(a.val + ob0), 0, (ob1 - ob0) * 2, 0x00020000);
-        constexpr int OV = RPC > 1 ? U : 1;
-        int32_t orp[RPC > 1 ? 1 : U + 1];    // RPC == 1: row boundaries (uniform)
-        int32_t oj[OV], oj1[OV];             // this lane's entry; RPC > 1: its row's end
-        uint32_t ocol[OV], oval[OV];
-        if constexpr (RPC == 1) {
-#pragma unroll
-            for (int u = 0; u <= U; ++u) orp[u] = __builtin_amdgcn_readlane(rpv, u);
-            oj[0] = ob0 + (int32_t)lane;
-            oj1[0] = ob1;
-            ocol[0] = __builtin_amdgcn_raw_buffer_load_b32(rc, lane * 4, 0, 0);
-            oval[0] = __builtin_amdgcn_raw_buffer_load_b16(rv, lane * 2, 0, 0);
-        } else {
-            orp[0] = 0;
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int32_t r0 = __shfl(rpv, u * RPC + seg);
-                oj1[u] = __shfl(rpv, u * RPC + seg + 1);
-                oj[u] = r0 + (int32_t)lis;
-                ocol[u] = __builtin_amdgcn_raw_buffer_load_b32(rc, (oj[u] - ob0) * 4, 0, 0);
-                oval[u] = __builtin_amdgcn_raw_buffer_load_b16(rv, (oj[u] - ob0) * 2, 0, 0);
-            }
-        }
-        __builtin_amdgcn_sched_barrier(0);
-
-        // a2 (V2): codebooks of the batch -> LDS tables.
-        if constexpr (MODE == 0) {
-            __builtin_amdgcn_wave_barrier();
-            const uint32_t raw_base = lds_base + Cfg::kTableBytes;
-#pragma unroll
-            for (int i = 0; i < CBW; ++i)
-                if (CBW * kWave == B * (ENT / 2) || i * kWave + lane < B * (ENT / 2))
-                    *(lds_u32_w_t *)(uintptr_t)(raw_base + (i * kWave + lane) * 4) = cbv[i];
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            // entry e = (first index) | (second index) << BITS; this lane builds e = lane, lane+64, ...
-            constexpr int PE = 1 << (2 * BITS);                // pair entries per row (16, 64 or 256)
-            constexpr int PR = PE >= kWave ? PE / kWave : 1;
-            if (PE >= kWave || lane < PE) {
-#pragma unroll
-                for (int r = 0; r < B; ++r) {
-                    // 64 is a multiple of the codebook size, so the first index of every
-                    // entry this lane builds is the same
-                    const uint32_t lo = *(lds_u16_t *)(uintptr_t)(raw_base + r * Fmt::kRawBytes + (lane & (ENT - 1)) * 2);
-#pragma unroll
-                    for (int p = 0; p < PR; ++p) {
-                        const uint32_t e = lane + p * kWave;
-                        const uint32_t hi = *(lds_u16_t *)(uintptr_t)(raw_base + r * Fmt::kRawBytes + (e >> BITS) * 2);
-                        *(lds_u32_w_t *)(uintptr_t)(lds_base + r * Fmt::kRowBytes + e * 4) = lo | (hi << 16);
-                    }
-                }
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-        }
-        // next batch's row pointers and codebooks: issued now, consumed next pass
-        if (rb + B < row_end) {
-            rpv = with_outliers ? rp[min(rb + B + lane, N)] : 0;
-            if constexpr (MODE == 0) {
-#pragma unroll
-                for (int i = 0; i < CBW; ++i)
-                    cbv[i] = cbw[min((rb + B) * (ENT / 2) + i * kWave + lane, cb_last)];
-            }
-        }
-        __builtin_amdgcn_sched_barrier(0);
-
-        // Keep the activations as packed fp16 pairs: without this the compiler
-        // hoists their fp32 conversions out of the loop and doubles the registers.
-#pragma unroll
-        for (int c = 0; c < NCH; ++c)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                if (TAIL && c == NCH - 1) xr[c][i] = live_last ? xr[c][i] : 0u;
-                asm volatile("" : "+v"(xr[c][i]));
-            }
-
-        // a4-a6: depack, gather, multiply-accumulate, software-pipelined over
-        // groups of eight lookups: task t = (row u, chunk c, group g).
-        float sum[U];
-        uint16_t oxv[OV];
-        {
-            constexpr int TPR = NCH * GPL;                     // tasks per row
-            constexpr int NT = U * TPR;
-            uint32_t val[2][8];
-            float acc[4] = {0.f, 0.f, 0.f, 0.f};
-            auto issue = [&](int t, uint32_t (&v)[8]) {
-                const int u = t / TPR, c = (t % TPR) / GPL, g = t % GPL;
-                const uint32_t tb = lds_base + u * RPC * Fmt::kRowBytes;
-                if constexpr (MODE == 1) {
-                    const uint32_t dead = TAIL && c == NCH - 1 && !live_last;
-                    issue_group<BITS, true, true>(lw[u][c], g, lds_base, dead ? a.L : lib[u][c], v, k1, k2, k3);
-                } else if (RPC > 1)
-                    issue_group<BITS, true>(lw[u][c], g, tb, seg, v, k1, k2, k3);
-                else if (TAIL && c == NCH - 1)
-                    issue_group<BITS, true>(lw[u][c], g, tb, live_last ? 0u : (uint32_t)(B - u), v, k1, k2, k3);
-                else
-                    issue_group<BITS, false>(lw[u][c], g, tb, 0u, v, k1, k2, k3);
-            };
-            issue(0, val[0]);
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const int u = t / TPR, c = (t % TPR) / GPL, g = t % GPL;
-                if (t + 1 < NT) issue(t + 1, val[(t + 1) & 1]);
-                if (t == NT / 2) {
-                    // a7 (gather): x at the outlier columns; col arrived with the index
-                    // words, the values are needed after the last multiply-accumulate
-#pragma unroll
-                    for (int v = 0; v < OV; ++v) oxv[v] = x[ocol[v]];
-                }
-                __builtin_amdgcn_sched_barrier(0);
-                consume_group<BITS>(g, val[t & 1], xr[c], acc);
-                if (t % TPR == TPR - 1) {                      // row finished
-                    sum[u] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
-                    acc[0] = acc[1] = acc[2] = acc[3] = 0.f;
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-
-        // a7 (fold): add each outlier product to the row that owns the entry.
-        {
-            if constexpr (RPC == 1) {
-                const float p = half_bits_to_float((uint16_t)oval[0]) * half_bits_to_float(oxv[0]);
-#pragma unroll
-                for (int u = 0; u < U; ++u) sum[u] += (oj[0] >= orp[u] && oj[0] < orp[u + 1]) ? p : 0.f;
-                for (int32_t jw = ob0 + kWave; jw < ob1; jw += kWave) {     // > 64 entries: rare
-                    const int32_t jj = jw + (int32_t)lane;
-                    if (jj < ob1) {
-                        const float q = half_bits_to_float(a.val[jj]) * half_bits_to_float(x[a.col[jj]]);
-#pragma unroll
-                        for (int u = 0; u < U; ++u) sum[u] += (jj >= orp[u] && jj < orp[u + 1]) ? q : 0.f;
-                    }
-                }
-            } else {
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const float p = half_bits_to_float((uint16_t)oval[u]) * half_bits_to_float(oxv[u]);
-                    sum[u] += oj[u] < oj1[u] ? p : 0.f;
-                    for (int32_t jj = oj[u] + LPR; jj < oj1[u]; jj += LPR)         // > LPR entries: rare
-                        sum[u] = fmaf(half_bits_to_float(a.val[jj]), half_bits_to_float(x[a.col[jj]]), sum[u]);
-                }
-            }
-        }
-        // a8: reduce and store.
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint32_t row = rb + u * RPC + seg;
-            float t = segment_sum<LPR>(sum[u]);
-            if (lis == 0 && row < row_end) {
-                const int64_t o = (int64_t)z * a.z_stride + (int64_t)slot * a.y_stride + row;
-                if (y_f32) static_cast<float *>(a.y)[o] = t;
-                else static_cast<_Float16 *>(a.y)[o] = (_Float16)t;
-            }
-        }
-    };
-
-    pass(std::true_type{}, row_begin);
-    for (uint32_t rb = row_begin + B; rb < row_end; rb += B) pass(std::false_type{}, rb);
-}
-
-// rows per wave: a multiple of the batch, sized so that the grid is a few
-// thousand waves (about 16 per CU) when the problem is large enough.
-template <int BITS, int NCH, int RPC, bool TAIL, int MODE, int UNROLL>
-static hipError_t launch_stream_u(DecodeArgs a, int slots, bool y_f32, hipStream_t s)
-{
-    using Cfg = StreamCfg<BITS, NCH, RPC, UNROLL>;
-    using Fmt = TableFmt<BITS>;
-    if constexpr (!Cfg::kFits) {
-        return hipErrorInvalidValue;
-    } else {
-        constexpr int B = Cfg::kBatchRows;
-        constexpr int kStreamWaves = stream_waves(MODE), kStreamThreads = kStreamWaves * kWave;
-        const uint32_t S = a.k_slices ? a.k_slices : 1u;
-        const uint64_t total_rows = (uint64_t)a.N * slots * S;
-        uint32_t rpw = B;
-        while ((total_rows + rpw - 1) / rpw > stream_max_waves(MODE) && rpw < 64 * B) rpw += B;
-        a.rows_per_block = rpw;
-        const uint32_t waves = (a.N + rpw - 1) / rpw;
-        const size_t smem = MODE == 0 ? 0 : (size_t)(a.L + 1) * Fmt::kRowBytes + (size_t)a.L * Fmt::kRawBytes;
-        auto kern = decode_stream_kernel<BITS, NCH, RPC, TAIL, MODE, UNROLL>;
-        if (smem > 48 * 1024) {
-            hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-            if (err != hipSuccess) return err;
-        }
-        dim3 grid((waves + kStreamWaves - 1) / kStreamWaves, slots, S);
-        hipLaunchKernelGGL(kern, grid, dim3(kStreamThreads), smem, s, a, (int)y_f32);
-        return hipGetLastError();
-    }
-}
-
-// Smallest batch (1, 2 or 4 row groups) with which every wave has ONE batch,
-// i.e. all of a wave's loads are issued up front; the largest the registers
-// allow when even that leaves more than the target number of waves.
-template <int BITS, int NCH, int RPC, bool TAIL, int MODE>
-static hipError_t launch_stream_t(const DecodeArgs &a, int slots, bool y_f32, hipStream_t s)
-{
-    const uint64_t groups = ((uint64_t)a.N * slots * (a.k_slices ? a.k_slices : 1u) + RPC - 1) / RPC;
-    constexpr uint32_t W = stream_max_waves(MODE);
-    constexpr bool f2 = StreamCfg<BITS, NCH, RPC, 2>::kFits, f4 = StreamCfg<BITS, NCH, RPC, 4>::kFits;
-    if (groups <= W || !f2) return launch_stream_u<BITS, NCH, RPC, TAIL, MODE, 1>(a, slots, y_f32, s);
-    if (groups <= 2 * W || !f4) return launch_stream_u<BITS, NCH, RPC, TAIL, MODE, 2>(a, slots, y_f32, s);
-    return launch_stream_u<BITS, NCH, RPC, TAIL, MODE, 4>(a, slots, y_f32, s);
-}
-
-template <int BITS, int NCH, int RPC, bool TAIL>
-static hipError_t launch_stream_m(const DecodeArgs &a, int mode, int slots, bool y_f32, hipStream_t s)
-{
-    if (mode == 0) return launch_stream_t<BITS, NCH, RPC, TAIL, 0>(a, slots, y_f32, s);
-    return launch_stream_t<BITS, NCH, RPC, TAIL, 1>(a, slots, y_f32, s);
-}
-
-template <int BITS, int NCH>
-static hipError_t launch_stream_n(const DecodeArgs &a, int mode, int slots, bool y_f32, hipStream_t s)
-{
-    if (a.K % 2048 == 0) return launch_stream_m<BITS, NCH, 1, false>(a, mode, slots, y_f32, s);
-    return launch_stream_m<BITS, NCH, 1, true>(a, mode, slots, y_f32, s);
-}
-
-template <int BITS>
-static hipError_t launch_stream_b(const DecodeArgs &a, int mode, int slots, bool y_f32, hipStream_t s)
-{
-    const uint32_t K = a.K;
-    if (K == 1024) return launch_stream_m<BITS, 1, 2, false>(a, mode, slots, y_f32, s);
-    if (K == 512) return launch_stream_m<BITS, 1, 4, false>(a, mode, slots, y_f32, s);
-    switch ((K + 2047) / 2048) {
-    case 1: return launch_stream_n<BITS, 1>(a, mode, slots, y_f32, s);
-    case 2: return launch_stream_n<BITS, 2>(a, mode, slots, y_f32, s);
-    case 3: return launch_stream_n<BITS, 3>(a, mode, slots, y_f32, s);
-    case 4: return launch_stream_n<BITS, 4>(a, mode, slots, y_f32, s);
-    case 5: return launch_stream_n<BITS, 5>(a, mode, slots, y_f32, s);
-    case 6: return launch_stream_n<BITS, 6>(a, mode, slots, y_f32, s);
-    case 7: return launch_stream_n<BITS, 7>(a, mode, slots, y_f32, s);
-    default: return launch_stream_n<BITS, 8>(a, mode, slots, y_f32, s);
-    }
-}
+// defined in xfp_decode_stream_split.hip / xfp_decode_stream_fused.hip
+hipError_t launch_stream_split(int bits, int mode, bool y_f32, const DecodeArgs &a, int slots, hipStream_t s);
+hipError_t launch_stream_fused(int bits, int mode, bool y_f32, const DecodeArgs &a, int slots, hipStream_t s);
 
 // V2a needs the library's pair tables in LDS: (L + 1) tables of 64 B / 256 B / 1 KB.
 bool stream_supports(int bits, int mode, uint32_t K, uint32_t L)
@@ -603,11 +22,9 @@ bool stream_supports(int bits, int mode, uint32_t K, uint32_t L)
 
 hipError_t launch_decode_stream(int bits, int mode, bool y_f32, const DecodeArgs &a, int slots, hipStream_t s)
 {
-    switch (bits) {
-    case 2: return launch_stream_b<2>(a, mode, slots, y_f32, s);
-    case 3: return launch_stream_b<3>(a, mode, slots, y_f32, s);
-    default: return launch_stream_b<4>(a, mode, slots, y_f32, s);
-    }
+    if (a.fuse_half) return launch_stream_fused(bits, mode, y_f32, a, slots, s);
+    if (a.k_slices) return launch_stream_split(bits, mode, y_f32, a, slots, s);
+    return launch_stream_variant<0>(bits, mode, y_f32, a, slots, s);
 }
 
 // ---------------------------------------------------------------- split-K
@@ -646,18 +63,29 @@ int splitk_slices(int bits, int mode, uint32_t N, uint32_t K, uint32_t L, int sl
     return 0;
 }
 
-hipError_t launch_decode_splitk(int bits, int mode, bool y_f32, const DecodeArgs &a, int slots, int slices,
-                                hipStream_t s)
+// One slot of the ring of fp32 scratch planes (kSplitFloats floats each), or
+// nullptr with *err set.
+float *scratch_plane(hipError_t *err)
 {
     static std::atomic<void *> ring{nullptr};          // device address of g_partial (one GPU per process)
     void *p = ring.load(std::memory_order_relaxed);
     if (!p) {
-        hipError_t err = hipGetSymbolAddress(&p, HIP_SYMBOL(g_partial));
-        if (err != hipSuccess) return err;
+        *err = hipGetSymbolAddress(&p, HIP_SYMBOL(g_partial));
+        if (*err != hipSuccess) return nullptr;
         ring.store(p, std::memory_order_relaxed);
     }
     static std::atomic<unsigned> next_slot{0};
-    float *part = static_cast<float *>(p) + (size_t)(next_slot.fetch_add(1, std::memory_order_relaxed) % kSplitSlots) * kSplitFloats;
+    return static_cast<float *>(p) + (size_t)(next_slot.fetch_add(1, std::memory_order_relaxed) % kSplitSlots) * kSplitFloats;
+}
+
+uint32_t scratch_plane_floats() { return kSplitFloats; }
+
+hipError_t launch_decode_splitk(int bits, int mode, bool y_f32, const DecodeArgs &a, int slots, int slices,
+                                hipStream_t s)
+{
+    hipError_t perr = hipSuccess;
+    float *part = scratch_plane(&perr);
+    if (!part) return perr;
     DecodeArgs c = a;
     c.k_slices = (uint32_t)slices;
     c.row_words = a.K / 32 * (uint32_t)bits;
@@ -670,6 +98,28 @@ hipError_t launch_decode_splitk(int bits, int mode, bool y_f32, const DecodeArgs
     if (err != hipSuccess) return err;
     hipLaunchKernelGGL(splitk_sum_kernel, dim3((a.N + 255) / 256, slots), dim3(256), 0, s, part, (uint32_t)slices, a.N,
                        (uint32_t)slots, a.y, a.y_stride, (int)y_f32);
+    return hipGetLastError();
+}
+
+// h[t][j] = SiLU(y[t][j]) * y[t][half + j] from fp32 sums (the unfused form of
+// the streaming kernel's gate/up epilogue, for shapes that kernel does not take).
+__global__ __launch_bounds__(256) void silu_mul_kernel(const float *y, uint32_t half, uint32_t slots, void *h,
+                                                       int64_t h_stride, int h_f32)
+{
+    const uint32_t j = blockIdx.x * 256 + threadIdx.x, slot = blockIdx.y;
+    if (j >= half) return;
+    const float g = y[(size_t)slot * 2 * half + j], up = y[(size_t)slot * 2 * half + half + j];
+    const float v = g / (1.0f + __expf(-g)) * up;
+    const int64_t o = (int64_t)slot * h_stride + j;
+    if (h_f32) static_cast<float *>(h)[o] = v;
+    else static_cast<_Float16 *>(h)[o] = (_Float16)v;
+}
+
+hipError_t launch_silu_mul(const float *y, uint32_t half, int slots, void *h, int64_t h_stride, bool h_f32,
+                           hipStream_t s)
+{
+    hipLaunchKernelGGL(silu_mul_kernel, dim3((half + 255) / 256, slots), dim3(256), 0, s, y, half, (uint32_t)slots, h,
+                       h_stride, (int)h_f32);
     return hipGetLastError();
 }
 

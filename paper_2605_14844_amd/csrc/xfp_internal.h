@@ -31,6 +31,9 @@ struct DecodeArgs {
     uint32_t row_words;    // dwords of a full index row
     uint32_t gid_row;      // library ids of a full row
     int64_t z_stride;      // slice z writes y + z * z_stride (fp32 partial sums)
+    // Fused SiLU(gate) * up (zero otherwise): rows [0, fuse_half) are gate rows, rows
+    // [fuse_half, 2 fuse_half) up rows; y gets fuse_half values per slot.
+    uint32_t fuse_half;
 };
 
 // Launchers, one per kernel family (defined in the .hip files).
@@ -50,6 +53,11 @@ hipError_t launch_decode_splitk(int bits, int mode, bool y_f32, const DecodeArgs
 // Matrix-core kernel for 2..16 tokens per launch (V2, 4-bit, K <= 8192).
 bool batch_supports(int bits, int mode, uint32_t K, int M);
 hipError_t launch_decode_batch(const DecodeArgs &a, int M, bool y_f32, hipStream_t s);
+// fp32 scratch plane from a small static ring (split-K partial sums, unfused epilogues)
+float *scratch_plane(hipError_t *err);
+uint32_t scratch_plane_floats();
+hipError_t launch_silu_mul(const float *y, uint32_t half, int slots, void *h, int64_t h_stride, bool h_f32,
+                           hipStream_t s);
 hipError_t launch_unpack(int bits, const uint32_t *idx, uint64_t rows, uint32_t K, uint8_t *out,
                          hipStream_t s);
 hipError_t launch_dequant(int bits, int mode, const DecodeArgs &a, uint32_t E, uint16_t *out,

@@ -263,3 +263,54 @@ def test_workload_4_full_bank():
         assert gated_rel_err(y, oracle.gemv_moe(gu, ids, x1, shared_x=True)) <= TOL_F16
         y = host(xfp.xfp_gemv_moe(ddn, ids_d, dev_x(x2)))
         assert gated_rel_err(y, oracle.gemv_moe(dn, ids, x2, shared_x=False)) <= TOL_F16
+
+
+# ------------------------------------------------------------------ gate/up projection with SiLU(gate) * up in the store
+def check_silu_mul(W, ids, xb, shared):
+    """fp32 output: 1e-4 like y (the epilogue adds two roundings and a hardware exp/rcp, about 1e-6);
+    fp16 output: 1e-3.  The gate is taken on h itself (its own rms floor)."""
+    ref = oracle.silu_mul(oracle.gemv_moe(W, ids, xb, shared_x=shared))
+    dW = xfp.upload(W)
+    ids_d = torch.from_numpy(ids).cuda()
+    xd = dev_x(xb)
+    xin = xd[0] if shared else xd
+    h32 = host(xfp.xfp_gemv_moe_silu_mul(dW, ids_d, xin, h_dtype=torch.float32))
+    h16 = host(xfp.xfp_gemv_moe_silu_mul(dW, ids_d, xin, h_dtype=torch.float16))
+    e32, e16 = gated_rel_err(h32, ref), gated_rel_err(h16, ref)
+    print(f"  silu_mul N={W.N} K={W.K} b={W.bits} mode={W.mode} T={len(ids)}: err f32 {e32:.2e} f16 {e16:.2e}", flush=True)
+    assert h32.shape == (len(ids), W.N // 2)
+    assert e32 <= TOL_F32 and e16 <= TOL_F16
+
+
+@pytest.mark.parametrize("mode,bits,N,K,E", [
+    (V2, 3, 2048, 4096, 4), (V2, 3, 130, 1024, 3), (V2, 4, 66, 512, 2), (V2, 4, 300, 8192, 2), (V2, 2, 36, 2048, 2),
+    (V2A, 3, 200, 4096, 2), (V2A, 4, 34, 640, 3), (V2, 4, 10, 5120, 2), (V2, 3, 2, 384, 1),
+    (V2, 4, 40, 20480, 2), (V2, 4, 22, 16768, 1)])                       # the last two: unfused fallback
+def test_gate_up_silu_mul_matches_oracle(mode, bits, N, K, E):
+    W = xi.random_weights(mode, bits, N, K, E=E, density=0.004, seed=N + E)
+    ids = np.array([E - 1, 0, E - 1], dtype=np.int32)
+    xs = xi.activations(np.random.default_rng(3), 1, K)
+    xt = xi.activations(np.random.default_rng(4), len(ids), K)
+    check_silu_mul(W, ids, xs, True)
+    check_silu_mul(W, ids, xt, False)
+
+
+def test_gate_up_silu_mul_dense_rows_of_outliers_and_single_matrix():
+    K = 2048
+    W = xi.random_weights(V2, 4, 24, K, density=0.0, seed=41)
+    rp = np.zeros(25, dtype=np.int32)
+    rp[4:] = 100                 # gate row 3 holds 100 entries
+    rp[16:] += K                 # up row 15 (pairs with gate row 3) holds a whole row of them
+    W.out_row_ptr = rp
+    W.out_col = np.concatenate([np.arange(100, dtype=np.int32) * 7, np.arange(K, dtype=np.int32)])
+    W.out_val = xi.activations(np.random.default_rng(42), 1, 100 + K).ravel()
+    xb = xi.activations(np.random.default_rng(43), 2, K)
+    ref = oracle.silu_mul(oracle.gemv_weights(W, xb))
+    got = host(xfp.xfp_gemv_moe_silu_mul(xfp.upload(W), None, dev_x(xb), h_dtype=torch.float32))
+    assert gated_rel_err(got, ref) <= TOL_F32
+
+
+def test_workload_4_gate_up_fused_full_bank():
+    gu, _ = xi.config_weights(4)
+    ids = xi.config_expert_ids(4, 8, gu.E, draw=0)
+    check_silu_mul(gu, ids, xi.config_x(4, 1, gu.K), True)

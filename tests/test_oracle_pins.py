@@ -280,3 +280,23 @@ def test_a_dropped_term_would_exceed_the_gate():
     y_bad = y.copy()
     y_bad[0, n] -= float(W.out_val[j:j + 1].view(np.float16)[0]) * xd[0, W.out_col[j]]
     assert gated_rel_err(y_bad, y) > 1e-3
+
+
+def test_silu_mul_against_library_logistic_closed_forms_and_layout():
+    # SiLU(g) = g * logistic(g): scipy's expit is an independent routine for the logistic function
+    from scipy.special import expit
+    rng = np.random.default_rng(5)
+    y = rng.normal(0.0, 3.0, size=(4, 10))
+    h = oracle.silu_mul(y)
+    assert h.shape == (4, 5)
+    assert np.allclose(h, y[:, :5] * expit(y[:, :5]) * y[:, 5:], rtol=1e-14, atol=0.0)
+    # closed forms: SiLU(0) = 0; SiLU(g) - SiLU(-g) = g; SiLU(g) -> g for large g, -> 0 for very negative g
+    z = oracle.silu_mul(np.array([0.0, 7.0, -7.0, 50.0, -800.0, 1.0, 1.0, 1.0, 1.0, 1.0]))
+    assert z[0] == 0.0 and abs((z[1] - z[2]) - 7.0) < 1e-14
+    assert abs(z[3] - 50.0) < 1e-12 and z[4] == 0.0
+    # SiLU(1) = 1 / (1 + 1/e)
+    assert abs(oracle.silu_mul(np.array([1.0, 2.0]))[0] - 2.0 / (1.0 + np.exp(-1.0))) < 1e-15
+    # layout: gate rows first, up rows second; swapping them changes the result (silu is not symmetric)
+    w = np.array([[2.0, -1.0, 0.5, 3.0]])
+    assert np.allclose(oracle.silu_mul(w), [[2.0 * expit(2.0) * 0.5, -expit(-1.0) * 3.0]])
+    assert not np.allclose(oracle.silu_mul(w), oracle.silu_mul(w[:, [2, 3, 0, 1]]))
