@@ -504,9 +504,11 @@ void decode_stream_kernel(DecodeArgs a, int y_f32)
             for (int t = 0; t < NT; ++t) {
                 const int u = t / TPR, c = (t % TPR) / GPL, g = t % GPL;
                 if (t + 1 < NT) issue(t + 1, val[(t + 1) & 1]);
-                if (t == NT / 2) {
-                    // a7 (gather): x at the outlier columns; col arrived with the index
-                    // words, the values are needed after the last multiply-accumulate
+                if (t == 3 * NT / 4) {
+                    // a7 (gather): x at the outlier columns.  col was requested after the index
+                    // words and loads return in order, so this waits for the whole batch: late
+                    // enough that little is left to wait for, early enough that the last quarter
+                    // of the multiply-accumulates covers part of the gather's latency
 #pragma unroll
                     for (int v = 0; v < OV; ++v) oxv[v] = x[ocol[v]];
                 }
