@@ -17,7 +17,7 @@ bool stream_supports(int bits, int mode, uint32_t K, uint32_t L)
 {
     if (bits < 2 || bits > 4 || K > 8 * 2048) return false;
     if (mode == 0) return true;
-    return mode == 1 && (size_t)(L + 1) * (4u << (2 * bits)) + (size_t)L * (2u << bits) <= 64 * 1024;
+    return mode == 1 && (size_t)(L + 1) * (4u << (2 * bits)) <= 64 * 1024;
 }
 
 hipError_t launch_decode_stream(int bits, int mode, bool y_f32, const DecodeArgs &a, int slots, hipStream_t s)

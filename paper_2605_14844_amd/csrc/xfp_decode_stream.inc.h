@@ -318,6 +318,19 @@ void decode_stream_kernel(DecodeArgs a, int y_f32)
 #pragma unroll
         for (int i = 0; i < CBW; ++i) cbv[i] = cbw[cb_word(row_begin, i * kWave + lane)];
     }
+    // V2a: this thread's share of the library, requested ahead of everything that
+    // streams (loads return in issue order, and the tables gate the first lookup).
+    // Item j = (codebook l = j / ENT, second index hi = j % ENT) builds the ENT
+    // pair entries (lo, hi), lo = 0 .. ENT-1, which are contiguous in table l; it
+    // needs codebook l (ENT / 2 dwords) and its entry hi.
+    constexpr int CW = ENT / 2;
+    uint32_t libw[MODE == 1 ? CW : 1], libhi = 0u;
+    if constexpr (MODE == 1) {
+        const uint32_t l = min(threadIdx.x / ENT, a.L - 1), hi = threadIdx.x % ENT;
+#pragma unroll
+        for (int d = 0; d < CW; ++d) libw[d] = cbw[l * CW + d];
+        libhi = reinterpret_cast<const uint16_t *>(cbw)[l * ENT + hi];
+    }
     __builtin_amdgcn_sched_barrier(0);
 
     // a1: this lane's activations, once per wave.
@@ -339,22 +352,34 @@ void decode_stream_kernel(DecodeArgs a, int y_f32)
     if constexpr (MODE == 1) {
         // a2 (V2a): the library's pair tables, once per workgroup, while the first
         // loads are in flight.  Table l sits at l * kRowBytes; table L is all zero
-        // (lanes past the end of a short row).
-        const uint32_t L = a.L;
-        const uint32_t raw_base = lds0 + (L + 1) * Fmt::kRowBytes;
-        for (uint32_t i = threadIdx.x; i < L * (ENT / 2); i += kStreamThreads)
-            *(lds_u32_w_t *)(uintptr_t)(raw_base + i * 4) = cbw[i];
-        __syncthreads();
-        constexpr uint32_t PE = 1u << (2 * BITS);              // pair entries per table
-        for (uint32_t i = threadIdx.x; i < (L + 1) * PE; i += kStreamThreads) {
-            const uint32_t l = i / PE, pe = i % PE;
-            uint32_t v = 0u;
-            if (l < L) {
-                const uint32_t lo = *(lds_u16_t *)(uintptr_t)(raw_base + (l * ENT + (pe & (ENT - 1))) * 2);
-                const uint32_t hi = *(lds_u16_t *)(uintptr_t)(raw_base + (l * ENT + (pe >> BITS)) * 2);
-                v = lo | (hi << 16);
+        // (lanes past the end of a short row).  One barrier: nothing is staged.
+        const uint32_t L = a.L, items = (L + 1) * ENT;
+        for (uint32_t j = threadIdx.x; j < items; j += kStreamThreads) {
+            const uint32_t l = j / ENT, hi = j % ENT;
+            uint32_t w[CW], hv;
+            if (j == threadIdx.x) {
+#pragma unroll
+                for (int d = 0; d < CW; ++d) w[d] = libw[d];
+                hv = libhi;
+            } else {                                           // libraries of more than 256 / ENT codebooks
+                const uint32_t lc = min(l, L - 1);
+#pragma unroll
+                for (int d = 0; d < CW; ++d) w[d] = cbw[lc * CW + d];
+                hv = reinterpret_cast<const uint16_t *>(cbw)[lc * ENT + hi];
             }
-            *(lds_u32_w_t *)(uintptr_t)(lds0 + i * 4) = v;
+            const uint32_t keep = l < L ? 0xFFFFFFFFu : 0u, hs = hv << 16;
+            const uint32_t dst = lds0 + l * Fmt::kRowBytes + hi * ENT * 4;
+#pragma unroll
+            for (int c4 = 0; c4 < ENT / 4; ++c4) {
+                uint32_t v[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int lo = 4 * c4 + k;
+                    v[k] = (((lo & 1) ? w[lo / 2] >> 16 : w[lo / 2] & 0xFFFFu) | hs) & keep;
+                }
+                typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+                *(__attribute__((address_space(3))) u4 *)(uintptr_t)(dst + c4 * 16) = u4{v[0], v[1], v[2], v[3]};
+            }
         }
         __syncthreads();
     } else if constexpr (TAIL) {
@@ -596,7 +621,7 @@ static hipError_t launch_stream_u(DecodeArgs a, int slots, bool y_f32, hipStream
         while ((total_rows + rpw - 1) / rpw > stream_max_waves(MODE) && rpw < 64 * B) rpw += B;
         a.rows_per_block = rpw;
         const uint32_t waves = (a.N + rpw - 1) / rpw;
-        const size_t smem = MODE == 0 ? 0 : (size_t)(a.L + 1) * Fmt::kRowBytes + (size_t)a.L * Fmt::kRawBytes;
+        const size_t smem = MODE == 0 ? 0 : (size_t)(a.L + 1) * Fmt::kRowBytes;
         auto kern = decode_stream_kernel<BITS, NCH, RPC, TAIL, MODE, UNROLL, VAR>;
         if (smem > 48 * 1024) {
             hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
