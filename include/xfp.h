@@ -27,6 +27,7 @@
  *    alignment).  Contents of device buffers (expert ids in range, group ids
  *    below L, CSR row pointers ascending and columns in [0, K)) are the
  *    caller's contract; violating it is undefined behaviour.
+ *    xfp_check_contents checks that contract on the device.
  *  - No global mutable state; calls from several host threads are safe.
  *
  * Data layout (all little-endian)
@@ -150,6 +151,30 @@ int xfp_gemv_moe_silu_mul(const xfp_weights *bank, const int32_t *expert_ids, in
  */
 int xfp_unpack_indices(const xfp_weights *W, uint8_t *idx_out, void *hip_stream);
 int xfp_dequant_bulk(const xfp_weights *W, uint16_t *w_out, void *hip_stream);
+
+/*
+ * Debugging aid (no paper counterpart): checks on the device the contents the
+ * decode entry points take on trust, and writes a report instead of trapping.
+ * Asynchronous like everything else; read the report after synchronising.
+ *
+ * nnz_capacity  entries allocated in out_col / out_val (row pointers beyond it
+ *               are reported and never followed).
+ * expert_ids    device int32 [T] or NULL (then T is ignored).
+ * report        device uint32 [4], 8-byte aligned:
+ *               [0] number of violations, [1] OR of (1 << kind) over them,
+ *               [2], [3] low / high word of the smallest position among them
+ *               (all ones when there is none).  Positions: group id index,
+ *               row pointer index, outlier entry index, slot.
+ */
+typedef enum {
+    XFP_CHECK_GROUP_ID = 1,   /* a V2a group id >= L                               */
+    XFP_CHECK_ROW_PTR = 2,    /* row_ptr[0] != 0, decreasing, or beyond nnz_capacity */
+    XFP_CHECK_COL_RANGE = 3,  /* an outlier column outside [0, K)                  */
+    XFP_CHECK_COL_ORDER = 4,  /* columns of a row not strictly ascending           */
+    XFP_CHECK_EXPERT_ID = 5   /* an expert id outside [0, E)                       */
+} xfp_check_kind;
+int xfp_check_contents(const xfp_weights *W, int64_t nnz_capacity, const int32_t *expert_ids, int T,
+                       uint32_t *report, void *hip_stream);
 
 /*
  * Measurement helpers (no paper counterpart): stream `bytes` (a multiple of

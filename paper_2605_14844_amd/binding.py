@@ -16,6 +16,7 @@ import torch
 
 XFP_MODE_V2, XFP_MODE_V2A = 0, 1
 XFP_F16, XFP_F32 = 0, 1
+XFP_CHECK_GROUP_ID, XFP_CHECK_ROW_PTR, XFP_CHECK_COL_RANGE, XFP_CHECK_COL_ORDER, XFP_CHECK_EXPERT_ID = 1, 2, 3, 4, 5
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libxfp.so")
@@ -59,12 +60,13 @@ def load_library():
     lib.xfp_gemv_moe.argtypes = [wp, vp, i32, vp, i64, vp, i32, i64, vp]
     lib.xfp_gemv_moe_silu_mul.argtypes = [wp, vp, i32, vp, i64, vp, i32, i64, vp]
     lib.xfp_unpack_indices.argtypes = [wp, vp, vp]
+    lib.xfp_check_contents.argtypes = [wp, i64, vp, i32, vp, vp]
     lib.xfp_dequant_bulk.argtypes = [wp, vp, vp]
     lib.xfp_probe_read.argtypes = [vp, u64, vp, vp]
     lib.xfp_probe_copy.argtypes = [vp, vp, u64, vp]
     lib.xfp_strerror.argtypes = [i32]
     lib.xfp_strerror.restype = ctypes.c_char_p
-    for name in ("xfp_gemv", "xfp_gemv_moe", "xfp_gemv_moe_silu_mul", "xfp_unpack_indices", "xfp_dequant_bulk",
+    for name in ("xfp_gemv", "xfp_gemv_moe", "xfp_gemv_moe_silu_mul", "xfp_check_contents", "xfp_unpack_indices", "xfp_dequant_bulk",
                  "xfp_probe_read", "xfp_probe_copy", "xfp_version"):
         getattr(lib, name).restype = i32
     _lib = lib
@@ -199,6 +201,20 @@ def xfp_gemv_moe_silu_mul(bank: DeviceWeights, expert_ids: Optional[torch.Tensor
         ctypes.byref(bank.desc), _ptr(expert_ids) if expert_ids is not None else None, T, _ptr(x), x_slot_stride,
         _ptr(h) if T else h.data_ptr(), _y_code(h.dtype), ldh, _stream(stream)))
     return h
+
+
+def xfp_check_contents(W: DeviceWeights, expert_ids: Optional[torch.Tensor] = None, stream=None) -> dict:
+    """Device-side check of group ids, CSR arrays and expert ids; synchronises and returns the report."""
+    report = torch.zeros(4, dtype=torch.int32, device="cuda")
+    col = W.tensors.get("out_col")
+    cap = 0 if col is None else int(col.numel())
+    T = 0 if expert_ids is None else int(expert_ids.numel())
+    _check(load_library().xfp_check_contents(ctypes.byref(W.desc), cap, _ptr(expert_ids), T, _ptr(report),
+                                             _stream(stream)))
+    torch.cuda.synchronize()
+    r = [int(v) & 0xFFFFFFFF for v in report.cpu().tolist()]
+    kinds = [k for k in range(1, 6) if r[1] >> k & 1]
+    return {"violations": r[0], "kinds": kinds, "first_position": None if r[0] == 0 else r[2] | r[3] << 32}
 
 
 def xfp_unpack_indices(W: DeviceWeights, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:

@@ -208,6 +208,20 @@ int xfp_dequant_bulk(const xfp_weights *W, uint16_t *w_out, void *hip_stream)
                                       static_cast<hipStream_t>(hip_stream)));
 }
 
+int xfp_check_contents(const xfp_weights *W, int64_t nnz_capacity, const int32_t *expert_ids, int T,
+                       uint32_t *report, void *hip_stream)
+{
+    int rc = check_weights(W);
+    if (rc) return rc;
+    if (!report) return XFP_ERR_NULL;
+    if (nnz_capacity < 0 || T < 0) return XFP_ERR_SHAPE;
+    if (nnz_capacity > 0 && !W->out_col) return XFP_ERR_NULL;
+    if (misaligned(report, 8) || misaligned(expert_ids, 4)) return XFP_ERR_ALIGN;
+    xfp::DecodeArgs a = base_args(W);
+    return finish(xfp::launch_check_contents(a, W->E, (uint64_t)nnz_capacity, expert_ids, expert_ids ? T : 0, report,
+                                             static_cast<hipStream_t>(hip_stream)));
+}
+
 int xfp_probe_read(const void *src, uint64_t bytes, uint32_t *sink, void *hip_stream)
 {
     if (!src || !sink) return XFP_ERR_NULL;

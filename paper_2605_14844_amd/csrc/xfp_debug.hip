@@ -1,6 +1,7 @@
 // Parity hooks (depack and codebook gather on their own) and the streaming
 // probes used to calibrate bandwidth figures and profiler byte counters.
 #include "xfp_device.h"
+#include "../../include/xfp.h"
 
 namespace xfp {
 
@@ -147,6 +148,87 @@ hipError_t launch_probe_copy(const void *src, void *dst, uint64_t bytes, hipStre
     unsigned blocks = (unsigned)((n16 + 255) / 256 < kProbeBlocks ? (n16 + 255) / 256 : kProbeBlocks);
     hipLaunchKernelGGL(probe_copy_kernel, dim3(blocks), dim3(256), 0, s,
                        static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), n16);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- content check
+// What the decode entry points take on trust, checked on the device.
+// report[0] violations found; report[1] OR of (1 << kind) over them;
+// report[2], report[3] low and high word of the smallest position among them
+// (kind 1: group id index; 2: row pointer index; 3, 4: outlier entry index;
+// 5: slot).  All three are order-independent, so the report is deterministic.
+struct CheckArgs {
+    const uint8_t *gid;
+    const int32_t *rp, *col, *eids;
+    uint64_t n_gid, n_rows, cap;       // group ids, stacked rows, entries allocated in col
+    uint32_t K, L, E;
+    int T;
+    uint32_t *report;
+};
+
+__device__ __forceinline__ void check_fail(uint32_t *report, int kind, uint64_t pos)
+{
+    atomicAdd(&report[0], 1u);
+    atomicOr(&report[1], 1u << kind);
+    atomicMin(reinterpret_cast<unsigned long long *>(report + 2), (unsigned long long)pos);
+}
+
+__global__ void check_init_kernel(uint32_t *report)
+{
+    report[0] = 0u;
+    report[1] = 0u;
+    report[2] = 0xFFFFFFFFu;
+    report[3] = 0xFFFFFFFFu;
+}
+
+__global__ __launch_bounds__(256) void check_contents_kernel(CheckArgs c)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * 256;
+    const uint64_t t0 = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (c.gid)
+        for (uint64_t i = t0; i < c.n_gid; i += stride)
+            if (c.gid[i] >= c.L) check_fail(c.report, XFP_CHECK_GROUP_ID, i);
+    if (t0 == 0 && c.rp[0] != 0) check_fail(c.report, XFP_CHECK_ROW_PTR, 0);
+    for (uint64_t r = t0; r < c.n_rows; r += stride) {
+        const int64_t a = c.rp[r], b = c.rp[r + 1];
+        if (b < a || b < 0 || (uint64_t)b > c.cap) {
+            check_fail(c.report, XFP_CHECK_ROW_PTR, r + 1);
+            continue;
+        }
+        if (a < 0) continue;                               // reported at the previous row
+        int64_t prev = -1;
+        for (int64_t j = a; j < b; ++j) {
+            const int64_t k = c.col[j];
+            if (k < 0 || k >= (int64_t)c.K) check_fail(c.report, XFP_CHECK_COL_RANGE, (uint64_t)j);
+            else if (k <= prev) check_fail(c.report, XFP_CHECK_COL_ORDER, (uint64_t)j);
+            prev = k;
+        }
+    }
+    if (c.eids)
+        for (uint64_t t = t0; t < (uint64_t)c.T; t += stride)
+            if (c.eids[t] < 0 || (uint32_t)c.eids[t] >= c.E) check_fail(c.report, XFP_CHECK_EXPERT_ID, t);
+}
+
+hipError_t launch_check_contents(const DecodeArgs &a, uint32_t E, uint64_t nnz_capacity, const int32_t *eids, int T,
+                                 uint32_t *report, hipStream_t s)
+{
+    CheckArgs c;
+    c.gid = a.gid;
+    c.rp = a.rp;
+    c.col = a.col;
+    c.eids = eids;
+    c.n_rows = (uint64_t)E * a.N;
+    c.n_gid = a.gid ? c.n_rows * (a.K / kGroup) : 0;
+    c.cap = nnz_capacity;
+    c.K = a.K;
+    c.L = a.L;
+    c.E = E;
+    c.T = T;
+    c.report = report;
+    hipLaunchKernelGGL(check_init_kernel, dim3(1), dim3(1), 0, s, report);
+    const uint64_t work = c.n_gid > c.n_rows ? c.n_gid : c.n_rows;
+    const unsigned blocks = (unsigned)((work + 255) / 256 < 4096 ? (work + 255) / 256 : 4096);
+    hipLaunchKernelGGL(check_contents_kernel, dim3(blocks ? blocks : 1), dim3(256), 0, s, c);
     return hipGetLastError();
 }
 

@@ -62,6 +62,8 @@ hipError_t launch_unpack(int bits, const uint32_t *idx, uint64_t rows, uint32_t 
                          hipStream_t s);
 hipError_t launch_dequant(int bits, int mode, const DecodeArgs &a, uint32_t E, uint16_t *out,
                           hipStream_t s);
+hipError_t launch_check_contents(const DecodeArgs &a, uint32_t E, uint64_t nnz_capacity, const int32_t *eids, int T,
+                                 uint32_t *report, hipStream_t s);
 hipError_t launch_probe_read(const void *src, uint64_t bytes, uint32_t *sink, hipStream_t s);
 hipError_t launch_probe_copy(const void *src, void *dst, uint64_t bytes, hipStream_t s);
 

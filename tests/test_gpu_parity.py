@@ -314,3 +314,32 @@ def test_workload_4_gate_up_fused_full_bank():
     gu, _ = xi.config_weights(4)
     ids = xi.config_expert_ids(4, 8, gu.E, draw=0)
     check_silu_mul(gu, ids, xi.config_x(4, 1, gu.K), True)
+
+
+# ------------------------------------------------------------------ device-side content check
+def test_check_contents_reports_each_kind_of_violation():
+    W = xi.random_weights(V2A, 3, 40, 512, E=3, density=0.01, seed=90)
+    ids = torch.tensor([0, 2, 1], dtype=torch.int32, device="cuda")
+    ok = xfp.xfp_check_contents(xfp.upload(W), ids)
+    assert ok == {"violations": 0, "kinds": [], "first_position": None}
+
+    def broken(edit, ids=ids):
+        import copy
+        W2 = copy.deepcopy(W)
+        edit(W2)
+        return xfp.xfp_check_contents(xfp.upload(W2), ids)
+
+    r = broken(lambda w: w.group_ids.reshape(-1).__setitem__(77, w.L))
+    assert r["kinds"] == [xfp.binding.XFP_CHECK_GROUP_ID] and r["violations"] == 1 and r["first_position"] == 77
+    r = broken(lambda w: w.out_row_ptr.__setitem__(5, w.out_row_ptr[6] + 1))          # row 4 runs past row 5's start
+    assert xfp.binding.XFP_CHECK_ROW_PTR in r["kinds"] and r["first_position"] == 6
+    first = int(np.argmax(np.diff(W.out_row_ptr) >= 2))                               # a row with two entries
+    j = int(W.out_row_ptr[first])
+    r = broken(lambda w: w.out_col.__setitem__(j, w.K))
+    assert xfp.binding.XFP_CHECK_COL_RANGE in r["kinds"] and r["first_position"] == j
+    r = broken(lambda w: w.out_col.__setitem__(j + 1, w.out_col[j]))                  # duplicate column
+    assert r["kinds"] == [xfp.binding.XFP_CHECK_COL_ORDER] and r["first_position"] == j + 1
+    r = xfp.xfp_check_contents(xfp.upload(W), torch.tensor([0, 3, -1], dtype=torch.int32, device="cuda"))
+    assert r["kinds"] == [xfp.binding.XFP_CHECK_EXPERT_ID] and r["violations"] == 2 and r["first_position"] == 1
+    r = broken(lambda w: w.out_row_ptr.__setitem__(len(w.out_row_ptr) - 1, w.out_row_ptr[-1] + 1000))
+    assert xfp.binding.XFP_CHECK_ROW_PTR in r["kinds"]                                # beyond the allocated entries
