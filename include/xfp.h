@@ -43,7 +43,8 @@
  *    absolute offsets (row_ptr[0] == 0), int32 col [nnz] ascending within a
  *    row with no duplicates, fp16 val [nnz].  The outlier value is ADDED to
  *    the codebook value at that position (eq. 1 is a sum).
- *  - x is fp16; y is fp16 or fp32; accumulation is fp32.
+ *  - x is fp16 (or bf16, converted: XFP_X_BF16); y is fp16, bf16 or fp32, rounded
+ *    once, to nearest even, from the fp32 sum; accumulation is fp32.
  */
 #ifndef XFP_H
 #define XFP_H
@@ -64,7 +65,13 @@ typedef enum {
 } xfp_status;
 
 typedef enum { XFP_MODE_V2 = 0, XFP_MODE_V2A = 1 } xfp_mode;
-typedef enum { XFP_F16 = 0, XFP_F32 = 1 } xfp_dtype;
+typedef enum { XFP_F16 = 0, XFP_F32 = 1, XFP_BF16 = 2 } xfp_dtype;   /* type of an output (y, h) */
+/* OR into a y_dtype / h_dtype argument: the activations x are bf16 instead of
+ * fp16 (the paper's kernel takes and returns bf16, section 5).  They are first
+ * converted to fp16 into a static scratch plane by one small extra launch
+ * (see xfp_convert_bf16_to_f16 for the rounding; rows * K <= 2^21), so a
+ * caller that feeds several projections from one x converts once itself. */
+#define XFP_X_BF16 0x100
 
 #define XFP_GROUP 128
 #define XFP_MAX_LIBRARY 256          /* V2a ids are one byte each */
@@ -141,6 +148,16 @@ int xfp_gemv_moe(const xfp_weights *bank, const int32_t *expert_ids, int T,
 int xfp_gemv_moe_silu_mul(const xfp_weights *bank, const int32_t *expert_ids, int T,
                           const void *x, int64_t x_slot_stride,
                           void *h, int h_dtype, int64_t ldh, void *hip_stream);
+
+/*
+ * bf16 -> fp16 for activations, dst[r][c] = src[r * ld_src + c], dst dense
+ * [rows][cols].  Every bf16 value is exact in fp32; the one rounding to fp16
+ * (to nearest even) is exact for magnitudes in [2^-14, 65504], rounds to a
+ * multiple of 2^-24 below and SATURATES at +-65504 above (an infinity in x
+ * would turn every output into NaN or infinity); NaN stays NaN.
+ * cols % 8 == 0, ld_src >= cols and % 8 == 0, rows <= 65535, 16-byte aligned.
+ */
+int xfp_convert_bf16_to_f16(const void *src, int64_t ld_src, void *dst, int rows, int cols, void *hip_stream);
 
 /*
  * Parity hooks: the first two fused steps on their own (paper section 5,

@@ -15,7 +15,8 @@ import numpy as np
 import torch
 
 XFP_MODE_V2, XFP_MODE_V2A = 0, 1
-XFP_F16, XFP_F32 = 0, 1
+XFP_F16, XFP_F32, XFP_BF16 = 0, 1, 2
+XFP_X_BF16 = 0x100
 XFP_CHECK_GROUP_ID, XFP_CHECK_ROW_PTR, XFP_CHECK_COL_RANGE, XFP_CHECK_COL_ORDER, XFP_CHECK_EXPERT_ID = 1, 2, 3, 4, 5
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -60,13 +61,14 @@ def load_library():
     lib.xfp_gemv_moe.argtypes = [wp, vp, i32, vp, i64, vp, i32, i64, vp]
     lib.xfp_gemv_moe_silu_mul.argtypes = [wp, vp, i32, vp, i64, vp, i32, i64, vp]
     lib.xfp_unpack_indices.argtypes = [wp, vp, vp]
+    lib.xfp_convert_bf16_to_f16.argtypes = [vp, i64, vp, i32, i32, vp]
     lib.xfp_check_contents.argtypes = [wp, i64, vp, i32, vp, vp]
     lib.xfp_dequant_bulk.argtypes = [wp, vp, vp]
     lib.xfp_probe_read.argtypes = [vp, u64, vp, vp]
     lib.xfp_probe_copy.argtypes = [vp, vp, u64, vp]
     lib.xfp_strerror.argtypes = [i32]
     lib.xfp_strerror.restype = ctypes.c_char_p
-    for name in ("xfp_gemv", "xfp_gemv_moe", "xfp_gemv_moe_silu_mul", "xfp_check_contents", "xfp_unpack_indices", "xfp_dequant_bulk",
+    for name in ("xfp_gemv", "xfp_gemv_moe", "xfp_gemv_moe_silu_mul", "xfp_check_contents", "xfp_convert_bf16_to_f16", "xfp_unpack_indices", "xfp_dequant_bulk",
                  "xfp_probe_read", "xfp_probe_copy", "xfp_version"):
         getattr(lib, name).restype = i32
     _lib = lib
@@ -149,12 +151,21 @@ def upload(W, device="cuda") -> DeviceWeights:
         _to_dev(W.out_col, device), _to_dev(W.out_val, device, np.int16), group=W.group)
 
 
-def _y_code(dtype) -> int:
+def _y_code(dtype, x: Optional[torch.Tensor] = None) -> int:
+    """dtype argument of the C ABI: the output type, plus the flag for bf16 activations."""
+    flag = 0
+    if x is not None:
+        if x.dtype == torch.bfloat16:
+            flag = XFP_X_BF16
+        elif x.dtype != torch.float16:
+            raise XfpError(-3, "x dtype must be torch.float16 or torch.bfloat16")
     if dtype == torch.float16:
-        return XFP_F16
+        return XFP_F16 | flag
     if dtype == torch.float32:
-        return XFP_F32
-    raise XfpError(-3, "y dtype must be torch.float16 or torch.float32")
+        return XFP_F32 | flag
+    if dtype == torch.bfloat16:
+        return XFP_BF16 | flag
+    raise XfpError(-3, "y dtype must be torch.float16, torch.bfloat16 or torch.float32")
 
 
 def xfp_gemv(W: DeviceWeights, x: torch.Tensor, y: Optional[torch.Tensor] = None,
@@ -168,7 +179,7 @@ def xfp_gemv(W: DeviceWeights, x: torch.Tensor, y: Optional[torch.Tensor] = None
     ldx = x2.stride(0) if M > 1 else max(x2.shape[1], 1)
     ldy = y2.stride(0) if M > 1 else max(y2.shape[1], 1)
     _check(load_library().xfp_gemv(ctypes.byref(W.desc), _ptr(x2), M, ldx, _ptr(y2),
-                                   _y_code(y2.dtype), ldy, _stream(stream)))
+                                   _y_code(y2.dtype, x2), ldy, _stream(stream)))
     return y
 
 
@@ -183,7 +194,7 @@ def xfp_gemv_moe(bank: DeviceWeights, expert_ids: torch.Tensor, x: torch.Tensor,
     ldy = y.stride(0) if y.dim() == 2 and T > 1 else bank.N
     _check(load_library().xfp_gemv_moe(ctypes.byref(bank.desc), _ptr(expert_ids), T, _ptr(x),
                                        x_slot_stride, _ptr(y) if T else y.data_ptr(),
-                                       _y_code(y.dtype), ldy, _stream(stream)))
+                                       _y_code(y.dtype, x), ldy, _stream(stream)))
     return y
 
 
@@ -199,7 +210,7 @@ def xfp_gemv_moe_silu_mul(bank: DeviceWeights, expert_ids: Optional[torch.Tensor
     ldh = h.stride(0) if h.dim() == 2 and T > 1 else bank.N // 2
     _check(load_library().xfp_gemv_moe_silu_mul(
         ctypes.byref(bank.desc), _ptr(expert_ids) if expert_ids is not None else None, T, _ptr(x), x_slot_stride,
-        _ptr(h) if T else h.data_ptr(), _y_code(h.dtype), ldh, _stream(stream)))
+        _ptr(h) if T else h.data_ptr(), _y_code(h.dtype, x), ldh, _stream(stream)))
     return h
 
 
@@ -215,6 +226,16 @@ def xfp_check_contents(W: DeviceWeights, expert_ids: Optional[torch.Tensor] = No
     r = [int(v) & 0xFFFFFFFF for v in report.cpu().tolist()]
     kinds = [k for k in range(1, 6) if r[1] >> k & 1]
     return {"violations": r[0], "kinds": kinds, "first_position": None if r[0] == 0 else r[2] | r[3] << 32}
+
+
+def xfp_convert_bf16_to_f16(src: torch.Tensor, stream=None) -> torch.Tensor:
+    """fp16 copy of a bf16 tensor [rows, cols] (or [cols]); exact inside fp16's normal range, saturating beyond."""
+    s2 = src if src.dim() == 2 else src.unsqueeze(0)
+    rows, cols = int(s2.shape[0]), int(s2.shape[1])
+    dst = torch.empty((rows, cols), dtype=torch.float16, device=src.device)
+    _check(load_library().xfp_convert_bf16_to_f16(_ptr(s2), s2.stride(0) if rows > 1 else cols, _ptr(dst), rows, cols,
+                                                  _stream(stream)))
+    return dst if src.dim() == 2 else dst[0]
 
 
 def xfp_unpack_indices(W: DeviceWeights, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:

@@ -59,10 +59,30 @@ int finish(hipError_t err)
     return XFP_ERR_HIP;
 }
 
+// y_dtype argument: an xfp_dtype, optionally OR-ed with XFP_X_BF16
+bool dtype_ok(int y_dtype)
+{
+    return (y_dtype & ~(0xFF | XFP_X_BF16)) == 0 && (y_dtype & 0xFF) <= XFP_BF16;
+}
+
+// x given as bf16: an fp16 copy [rows][K] in a scratch plane takes its place
+int convert_x(const xfp_weights *W, int rows, const void *&x, int64_t &x_stride, hipStream_t s)
+{
+    if ((uint64_t)rows * W->K > 2ull * xfp::scratch_plane_floats()) return XFP_ERR_UNSUPPORTED;
+    hipError_t perr = hipSuccess;
+    float *plane = xfp::scratch_plane(&perr);
+    if (!plane) return finish(perr);
+    hipError_t err = xfp::launch_bf16_to_f16(x, rows > 1 ? x_stride : (int64_t)W->K, plane, (uint32_t)rows, W->K, s);
+    if (err != hipSuccess) return finish(err);
+    x = plane;
+    x_stride = x_stride == 0 ? 0 : (int64_t)W->K;
+    return XFP_OK;
+}
+
 int check_io(const xfp_weights *W, const void *x, const void *y, int y_dtype, int64_t ldy)
 {
     if (!x || !y) return XFP_ERR_NULL;
-    if (y_dtype != XFP_F16 && y_dtype != XFP_F32) return XFP_ERR_UNSUPPORTED;
+    if (!dtype_ok(y_dtype)) return XFP_ERR_UNSUPPORTED;
     if (ldy < (int64_t)W->N) return XFP_ERR_SHAPE;
     if (misaligned(x, 16) || misaligned(y, 16)) return XFP_ERR_ALIGN;
     return XFP_OK;
@@ -81,12 +101,18 @@ uint32_t rows_per_block(uint32_t N, int slots)
 int decode(const xfp_weights *W, const int32_t *eids, int slots, const void *x, int64_t x_stride,
            void *y, int y_dtype, int64_t ldy, hipStream_t s)
 {
+    if (y_dtype & XFP_X_BF16) {
+        const int rc = convert_x(W, x_stride == 0 ? 1 : slots, x, x_stride, s);
+        if (rc) return rc;
+    }
+    y_dtype &= 0xFF;
     xfp::DecodeArgs a = base_args(W);
     a.x = static_cast<const uint16_t *>(x);
     a.y = y;
     a.eids = eids;
     a.x_stride = x_stride;
     a.y_stride = ldy;
+    a.y_bf16 = y_dtype == XFP_BF16;
     if (!eids && xfp::batch_supports((int)W->bits, (int)W->mode, W->K, slots)) {
         // batched tokens: the weights are read once per 16 tokens
         const size_t ysz = y_dtype == XFP_F32 ? 4 : 2;
@@ -114,8 +140,14 @@ int decode(const xfp_weights *W, const int32_t *eids, int slots, const void *x, 
 int decode_silu_mul(const xfp_weights *W, const int32_t *eids, int slots, const void *x, int64_t x_stride,
                     void *h, int h_dtype, int64_t ldh, hipStream_t s)
 {
+    if (h_dtype & XFP_X_BF16) {
+        const int rc = convert_x(W, x_stride == 0 ? 1 : slots, x, x_stride, s);
+        if (rc) return rc;
+    }
+    h_dtype &= 0xFF;
     if (xfp::stream_supports((int)W->bits, (int)W->mode, W->K, W->L)) {
         xfp::DecodeArgs a = base_args(W);
+        a.y_bf16 = h_dtype == XFP_BF16;
         a.x = static_cast<const uint16_t *>(x);
         a.y = h;
         a.eids = eids;
@@ -131,7 +163,7 @@ int decode_silu_mul(const xfp_weights *W, const int32_t *eids, int slots, const 
     if (!plane) return finish(perr);
     int rc = decode(W, eids, slots, x, x_stride, plane, XFP_F32, (int64_t)W->N, s);
     if (rc) return rc;
-    return finish(xfp::launch_silu_mul(plane, W->N / 2, slots, h, ldh, h_dtype == XFP_F32, s));
+    return finish(xfp::launch_silu_mul(plane, W->N / 2, slots, h, ldh, h_dtype == XFP_F32, h_dtype == XFP_BF16, s));
 }
 
 }  // namespace
@@ -178,13 +210,23 @@ int xfp_gemv_moe_silu_mul(const xfp_weights *bank, const int32_t *expert_ids, in
     if (T == 0) return XFP_OK;
     if (!expert_ids && bank->E != 1) return XFP_ERR_NULL;
     if (!x || !h) return XFP_ERR_NULL;
-    if (h_dtype != XFP_F16 && h_dtype != XFP_F32) return XFP_ERR_UNSUPPORTED;
+    if (!dtype_ok(h_dtype)) return XFP_ERR_UNSUPPORTED;
     if (ldh < (int64_t)(bank->N / 2)) return XFP_ERR_SHAPE;
     if (x_slot_stride != 0 && x_slot_stride < (int64_t)bank->K) return XFP_ERR_SHAPE;
     if (misaligned(x, 16) || misaligned(h, 16) || x_slot_stride % 8 != 0 || misaligned(expert_ids, 4))
         return XFP_ERR_ALIGN;
     return decode_silu_mul(bank, expert_ids, T, x, x_slot_stride, h, h_dtype, ldh,
                            static_cast<hipStream_t>(hip_stream));
+}
+
+int xfp_convert_bf16_to_f16(const void *src, int64_t ld_src, void *dst, int rows, int cols, void *hip_stream)
+{
+    if (!src || !dst) return XFP_ERR_NULL;
+    if (rows < 0 || cols < 0 || cols % 8 != 0 || rows > 65535 || ld_src < cols) return XFP_ERR_SHAPE;
+    if (misaligned(src, 16) || misaligned(dst, 16) || ld_src % 8 != 0) return XFP_ERR_ALIGN;
+    if (rows == 0 || cols == 0) return XFP_OK;
+    return finish(xfp::launch_bf16_to_f16(src, ld_src, dst, (uint32_t)rows, (uint32_t)cols,
+                                          static_cast<hipStream_t>(hip_stream)));
 }
 
 int xfp_unpack_indices(const xfp_weights *W, uint8_t *idx_out, void *hip_stream)

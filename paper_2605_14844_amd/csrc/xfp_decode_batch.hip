@@ -395,8 +395,7 @@ __global__ __launch_bounds__(W * kWave) void decode_batch4_kernel(BatchArgs ta)
             s = dpp_add<0x4E>(s);                          // quad_perm [2,3,0,1]
             if (sub == 0 && n < N && em < (uint32_t)M) {
                 const int64_t oo = (int64_t)em * a.y_stride + n;
-                if (ta.y_f32) static_cast<float *>(a.y)[oo] = s;
-                else static_cast<_Float16 *>(a.y)[oo] = (_Float16)s;
+                store_out(a.y, oo, s, ta.y_f32 != 0, a.y_bf16 != 0);
             }
         }
     };

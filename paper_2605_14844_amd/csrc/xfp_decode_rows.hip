@@ -93,7 +93,7 @@ __global__ __launch_bounds__(kRowsThreads) void decode_rows_kernel(DecodeArgs a)
         }
         // a8: reduce and store.
         acc = wave_sum(acc);
-        if (lane == 0) store_y<YF32>(a.y, (int64_t)slot * a.y_stride + row, acc);
+        if (lane == 0) store_y<YF32>(a.y, (int64_t)slot * a.y_stride + row, acc, a.y_bf16 != 0);
     }
 }
 

@@ -39,7 +39,7 @@ constexpr int kSplitSlots = 4;
 __device__ __align__(256) float g_partial[kSplitSlots][kSplitFloats];
 
 __global__ __launch_bounds__(256) void splitk_sum_kernel(const float *part, uint32_t S, uint32_t N, uint32_t slots,
-                                                         void *y, int64_t y_stride, int y_f32)
+                                                         void *y, int64_t y_stride, int y_f32, int y_bf16)
 {
     const uint32_t n = blockIdx.x * 256 + threadIdx.x, slot = blockIdx.y;
     if (n >= N) return;
@@ -47,8 +47,7 @@ __global__ __launch_bounds__(256) void splitk_sum_kernel(const float *part, uint
     float s = part[(size_t)slot * N + n];
     for (uint32_t z = 1; z < S; ++z) s += part[z * plane + (size_t)slot * N + n];
     const int64_t o = (int64_t)slot * y_stride + n;
-    if (y_f32) static_cast<float *>(y)[o] = s;
-    else static_cast<_Float16 *>(y)[o] = (_Float16)s;
+    store_out(y, o, s, y_f32 != 0, y_bf16 != 0);
 }
 
 int splitk_slices(int bits, int mode, uint32_t N, uint32_t K, uint32_t L, int slots)
@@ -97,29 +96,58 @@ hipError_t launch_decode_splitk(int bits, int mode, bool y_f32, const DecodeArgs
     hipError_t err = launch_decode_stream(bits, mode, true, c, slots, s);
     if (err != hipSuccess) return err;
     hipLaunchKernelGGL(splitk_sum_kernel, dim3((a.N + 255) / 256, slots), dim3(256), 0, s, part, (uint32_t)slices, a.N,
-                       (uint32_t)slots, a.y, a.y_stride, (int)y_f32);
+                       (uint32_t)slots, a.y, a.y_stride, (int)y_f32, (int)a.y_bf16);
     return hipGetLastError();
 }
 
 // h[t][j] = SiLU(y[t][j]) * y[t][half + j] from fp32 sums (the unfused form of
 // the streaming kernel's gate/up epilogue, for shapes that kernel does not take).
 __global__ __launch_bounds__(256) void silu_mul_kernel(const float *y, uint32_t half, uint32_t slots, void *h,
-                                                       int64_t h_stride, int h_f32)
+                                                       int64_t h_stride, int h_f32, int h_bf16)
 {
     const uint32_t j = blockIdx.x * 256 + threadIdx.x, slot = blockIdx.y;
     if (j >= half) return;
     const float g = y[(size_t)slot * 2 * half + j], up = y[(size_t)slot * 2 * half + half + j];
     const float v = g / (1.0f + __expf(-g)) * up;
     const int64_t o = (int64_t)slot * h_stride + j;
-    if (h_f32) static_cast<float *>(h)[o] = v;
-    else static_cast<_Float16 *>(h)[o] = (_Float16)v;
+    store_out(h, o, v, h_f32 != 0, h_bf16 != 0);
 }
 
 hipError_t launch_silu_mul(const float *y, uint32_t half, int slots, void *h, int64_t h_stride, bool h_f32,
-                           hipStream_t s)
+                           bool h_bf16, hipStream_t s)
 {
     hipLaunchKernelGGL(silu_mul_kernel, dim3((half + 255) / 256, slots), dim3(256), 0, s, y, half, (uint32_t)slots, h,
-                       h_stride, (int)h_f32);
+                       h_stride, (int)h_f32, (int)h_bf16);
+    return hipGetLastError();
+}
+
+// bf16 -> fp16, eight values per thread.  A bf16 value is exact in fp32; the
+// rounding to fp16 is exact inside fp16's normal range, rounds to a multiple of
+// 2^-24 below 2^-14 and saturates at +-65504 (an activation that large would
+// otherwise become an infinity and poison every output).
+__global__ __launch_bounds__(256) void bf16_to_f16_kernel(const uint16_t *src, int64_t ld, uint16_t *dst, uint32_t rows,
+                                                          uint32_t K)
+{
+    const uint32_t c8 = blockIdx.x * 256 + threadIdx.x, row = blockIdx.y;
+    if (c8 * 8 >= K) return;
+    const uint4 v = *reinterpret_cast<const uint4 *>(src + (size_t)row * ld + (size_t)c8 * 8);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    uint32_t o[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float lo = __builtin_bit_cast(float, w[i] << 16), hi = __builtin_bit_cast(float, w[i] & 0xFFFF0000u);
+        lo = lo != lo ? lo : fminf(fmaxf(lo, -65504.f), 65504.f);      // NaN stays NaN
+        hi = hi != hi ? hi : fminf(fmaxf(hi, -65504.f), 65504.f);
+        const _Float16 l16 = (_Float16)lo, h16 = (_Float16)hi;
+        o[i] = (uint32_t)__builtin_bit_cast(uint16_t, l16) | ((uint32_t)__builtin_bit_cast(uint16_t, h16) << 16);
+    }
+    *reinterpret_cast<uint4 *>(dst + (size_t)row * K + (size_t)c8 * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+hipError_t launch_bf16_to_f16(const void *src, int64_t ld, void *dst, uint32_t rows, uint32_t K, hipStream_t s)
+{
+    hipLaunchKernelGGL(bf16_to_f16_kernel, dim3((K / 8 + 255) / 256, rows), dim3(256), 0, s,
+                       static_cast<const uint16_t *>(src), ld, static_cast<uint16_t *>(dst), rows, K);
     return hipGetLastError();
 }
 

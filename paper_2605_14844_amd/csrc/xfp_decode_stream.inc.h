@@ -580,8 +580,7 @@ void decode_stream_kernel(DecodeArgs a, int y_f32)
                     const float h = g / (1.0f + __expf(-g)) * up;
                     if (lis == 0 && j < row_end / 2) {
                         const int64_t o = (int64_t)slot * a.y_stride + j;
-                        if (y_f32) static_cast<float *>(a.y)[o] = h;
-                        else static_cast<_Float16 *>(a.y)[o] = (_Float16)h;
+                        store_out(a.y, o, h, y_f32 != 0, a.y_bf16 != 0);
                     }
                 }
             }
@@ -593,8 +592,7 @@ void decode_stream_kernel(DecodeArgs a, int y_f32)
             float t = segment_sum<LPR>(sum[u]);
             if (lis == 0 && row < row_end) {
                 const int64_t o = (int64_t)z * a.z_stride + (int64_t)slot * a.y_stride + row;
-                if (y_f32) static_cast<float *>(a.y)[o] = t;
-                else static_cast<_Float16 *>(a.y)[o] = (_Float16)t;
+                store_out(a.y, o, t, y_f32 != 0, a.y_bf16 != 0);
             }
         }
     };

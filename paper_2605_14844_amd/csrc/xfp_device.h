@@ -105,14 +105,27 @@ __device__ __forceinline__ float segment_sum(float v)
     return v;
 }
 
-template <bool YF32>
-__device__ __forceinline__ void store_y(void *y, int64_t i, float v)
+// fp32 -> bf16 bit pattern, round to nearest even, NaN stays NaN
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float v)
 {
-    if constexpr (YF32) {
-        static_cast<float *>(y)[i] = v;
-    } else {
-        static_cast<_Float16 *>(y)[i] = (_Float16)v;   // round to nearest even
-    }
+    uint32_t u = __builtin_bit_cast(uint32_t, v);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// One output element: fp32 as it is, else one rounding (to nearest even) to fp16 or bf16.
+__device__ __forceinline__ void store_out(void *y, int64_t i, float v, bool f32, bool bf16)
+{
+    if (f32) static_cast<float *>(y)[i] = v;
+    else if (bf16) static_cast<uint16_t *>(y)[i] = float_to_bf16_bits(v);
+    else static_cast<_Float16 *>(y)[i] = (_Float16)v;
+}
+
+template <bool YF32>
+__device__ __forceinline__ void store_y(void *y, int64_t i, float v, bool bf16)
+{
+    store_out(y, i, v, YF32, bf16);
 }
 
 }  // namespace xfp

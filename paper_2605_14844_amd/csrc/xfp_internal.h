@@ -34,6 +34,7 @@ struct DecodeArgs {
     // Fused SiLU(gate) * up (zero otherwise): rows [0, fuse_half) are gate rows, rows
     // [fuse_half, 2 fuse_half) up rows; y gets fuse_half values per slot.
     uint32_t fuse_half;
+    uint32_t y_bf16;       // the 16-bit output type is bf16 instead of fp16
 };
 
 // Launchers, one per kernel family (defined in the .hip files).
@@ -57,7 +58,9 @@ hipError_t launch_decode_batch(const DecodeArgs &a, int M, bool y_f32, hipStream
 float *scratch_plane(hipError_t *err);
 uint32_t scratch_plane_floats();
 hipError_t launch_silu_mul(const float *y, uint32_t half, int slots, void *h, int64_t h_stride, bool h_f32,
-                           hipStream_t s);
+                           bool h_bf16, hipStream_t s);
+// bf16 [rows][ld] -> fp16 [rows][K] (exact inside fp16's normal range, saturating beyond it)
+hipError_t launch_bf16_to_f16(const void *src, int64_t ld, void *dst, uint32_t rows, uint32_t K, hipStream_t s);
 hipError_t launch_unpack(int bits, const uint32_t *idx, uint64_t rows, uint32_t K, uint8_t *out,
                          hipStream_t s);
 hipError_t launch_dequant(int bits, int mode, const DecodeArgs &a, uint32_t E, uint16_t *out,

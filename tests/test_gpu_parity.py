@@ -343,3 +343,56 @@ def test_check_contents_reports_each_kind_of_violation():
     assert r["kinds"] == [xfp.binding.XFP_CHECK_EXPERT_ID] and r["violations"] == 2 and r["first_position"] == 1
     r = broken(lambda w: w.out_row_ptr.__setitem__(len(w.out_row_ptr) - 1, w.out_row_ptr[-1] + 1000))
     assert xfp.binding.XFP_CHECK_ROW_PTR in r["kinds"]                                # beyond the allocated entries
+
+
+# ------------------------------------------------------------------ bf16 in and out
+# bf16 output (7 stored mantissa bits): one rounding to nearest even of the fp32 sum, half an ulp = 2^-8 = 3.9e-3
+# relative at worst
+TOL_BF16 = 4.0e-3
+
+
+def test_convert_bf16_to_f16_every_bit_pattern():
+    bits = np.arange(65536, dtype=np.uint16)
+    src = torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16).reshape(8, 8192)
+    got = xfp.xfp_convert_bf16_to_f16(src).cpu().numpy().view(np.uint16).ravel()
+    f32 = (bits.astype(np.uint32) << 16).view(np.float32)
+    with np.errstate(invalid="ignore"):
+        ref = np.clip(f32, -65504.0, 65504.0).astype(np.float16)       # numpy rounds to nearest even; clip keeps NaN
+    nan = np.isnan(f32)
+    assert np.array_equal(np.isnan(got.view(np.float16)), nan)
+    assert np.array_equal(got[~nan], ref.view(np.uint16)[~nan])
+    assert got[bits == 0x7F80][0] == 0x7BFF and got[bits == 0xFF80][0] == 0xFBFF   # infinities saturate
+
+
+@pytest.mark.parametrize("mode,bits,N,K,M", [(V2, 4, 300, 4096, 1), (V2A, 3, 64, 2048, 3), (V2, 4, 48, 8192, 16),
+                                             (V2, 3, 40, 20480, 2)])
+def test_bf16_activations_and_outputs(mode, bits, N, K, M):
+    W = xi.random_weights(mode, bits, N, K, density=0.003, seed=N + M)
+    x16 = xi.activations(np.random.default_rng(M + K), M, K) & np.uint16(0xFFF8)   # 7 mantissa bits: exact in both types
+    xbf = ((x16.view(np.float16).astype(np.float32).view(np.uint32)) >> 16).astype(np.uint16)
+    ref = oracle.gemv_weights(W, x16)
+    dW = xfp.upload(W)
+    xd = torch.from_numpy(xbf.view(np.int16)).cuda().view(torch.bfloat16)
+    y32 = host(xfp.xfp_gemv(dW, xd, y_dtype=torch.float32))
+    ybf = host(xfp.xfp_gemv(dW, xd, y_dtype=torch.bfloat16))
+    y16 = host(xfp.xfp_gemv(dW, dev_x(x16), y_dtype=torch.bfloat16))
+    assert gated_rel_err(y32, ref) <= TOL_F32
+    assert gated_rel_err(ybf, ref) <= TOL_BF16 and gated_rel_err(y16, ref) <= TOL_BF16
+    assert np.array_equal(ybf, y16)                                     # same fp16 activations either way
+
+
+def test_bf16_moe_and_gate_up():
+    W = xi.random_weights(V2, 3, 128, 1024, E=3, density=0.002, seed=77)
+    ids = np.array([2, 0, 2, 1], dtype=np.int32)
+    ids_d = torch.from_numpy(ids).cuda()
+    x16 = xi.activations(np.random.default_rng(78), len(ids), W.K) & np.uint16(0xFFF8)
+    xbf = ((x16.view(np.float16).astype(np.float32).view(np.uint32)) >> 16).astype(np.uint16)
+    xd = torch.from_numpy(xbf.view(np.int16)).cuda().view(torch.bfloat16)
+    dW = xfp.upload(W)
+    for shared in (True, False):
+        xin, xo = (xd[0], x16[:1]) if shared else (xd, x16)
+        y = oracle.gemv_moe(W, ids, xo, shared_x=shared)
+        assert gated_rel_err(host(xfp.xfp_gemv_moe(dW, ids_d, xin, y_dtype=torch.bfloat16)), y) <= TOL_BF16
+        assert gated_rel_err(host(xfp.xfp_gemv_moe(dW, ids_d, xin, y_dtype=torch.float32)), y) <= TOL_F32
+        h = host(xfp.xfp_gemv_moe_silu_mul(dW, ids_d, xin, h_dtype=torch.bfloat16))
+        assert gated_rel_err(h, oracle.silu_mul(y)) <= TOL_BF16

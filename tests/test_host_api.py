@@ -16,7 +16,7 @@ FAKE = 0x10000          # a non-NULL, 16-byte aligned "device pointer" that is n
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "xfp.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(xfp_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(xfp_[a-z0-9_]+)\s*\(", text)))
 
 
 def desc(**kw):
@@ -40,7 +40,7 @@ def moe(d, ids=FAKE, T=2, x=FAKE, xs=0, y=FAKE, dt=0, ldy=64):
 def test_library_exports_every_declared_symbol():
     lib = xfp.load_library()
     names = declared_functions()
-    assert {"xfp_gemv", "xfp_gemv_moe", "xfp_gemv_moe_silu_mul", "xfp_check_contents", "xfp_unpack_indices", "xfp_dequant_bulk", "xfp_strerror",
+    assert {"xfp_gemv", "xfp_gemv_moe", "xfp_gemv_moe_silu_mul", "xfp_check_contents", "xfp_convert_bf16_to_f16", "xfp_unpack_indices", "xfp_dequant_bulk", "xfp_strerror",
             "xfp_version", "xfp_probe_read", "xfp_probe_copy"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
