@@ -150,6 +150,23 @@ int xfp_gemv_moe_silu_mul(const xfp_weights *bank, const int32_t *expert_ids, in
                           void *h, int h_dtype, int64_t ldh, void *hip_stream);
 
 /*
+ * Down projection of a routed-expert layer with the router's combine folded in:
+ *     y[n] = sum over slots t of slot_weights[t] * (matrix expert_ids[t] applied to input row t)[n],
+ * the slots added in ascending order in fp32, one rounding to y_dtype.  Like
+ * the gate/up epilogue this is the library's addition to what the paper
+ * describes (sections 1 and 6.1 apply the decode to routed experts and name
+ * launch overhead as what dominates them).  Today the per-slot results meet in
+ * a static fp32 scratch plane (T * N <= 2^20, else XFP_ERR_UNSUPPORTED) and a
+ * second small kernel adds them: one call and no fp16 round trip, two launches.
+ *
+ * slot_weights   device fp32 [T].   y  [N] of y_dtype.   T >= 1.
+ * Everything else as for xfp_gemv_moe.
+ */
+int xfp_gemv_moe_combine(const xfp_weights *bank, const int32_t *expert_ids, int T,
+                         const void *x, int64_t x_slot_stride, const float *slot_weights,
+                         void *y, int y_dtype, void *hip_stream);
+
+/*
  * bf16 -> fp16 for activations, dst[r][c] = src[r * ld_src + c], dst dense
  * [rows][cols].  Every bf16 value is exact in fp32; the one rounding to fp16
  * (to nearest even) is exact for magnitudes in [2^-14, 65504], rounds to a

@@ -147,3 +147,16 @@ def silu_mul(y: np.ndarray) -> np.ndarray:
     g, u = y[..., :half], y[..., half:]
     with np.errstate(over="ignore"):
         return g / (1.0 + np.exp(-g)) * u
+
+
+def moe_combine(y: np.ndarray, slot_weights: np.ndarray) -> np.ndarray:
+    """out[n] = sum_t slot_weights[t] * y[t, n] in double: the router's weighted sum over the active experts'
+    outputs (the paper's models are top-k routed mixtures of experts, section 6.1; the paper does not print the
+    formula, this is the standard one).  slot_weights are taken as given (fp32 values, widened exactly)."""
+    y = np.asarray(y, dtype=np.float64)
+    w = np.asarray(slot_weights, dtype=np.float32).astype(np.float64)
+    assert y.ndim == 2 and w.shape == (y.shape[0],)
+    out = np.zeros(y.shape[1], dtype=np.float64)
+    for t in range(y.shape[0]):
+        out += w[t] * y[t]
+    return out

@@ -61,6 +61,7 @@ def load_library():
     lib.xfp_gemv_moe.argtypes = [wp, vp, i32, vp, i64, vp, i32, i64, vp]
     lib.xfp_gemv_moe_silu_mul.argtypes = [wp, vp, i32, vp, i64, vp, i32, i64, vp]
     lib.xfp_unpack_indices.argtypes = [wp, vp, vp]
+    lib.xfp_gemv_moe_combine.argtypes = [wp, vp, i32, vp, i64, vp, vp, i32, vp]
     lib.xfp_convert_bf16_to_f16.argtypes = [vp, i64, vp, i32, i32, vp]
     lib.xfp_check_contents.argtypes = [wp, i64, vp, i32, vp, vp]
     lib.xfp_dequant_bulk.argtypes = [wp, vp, vp]
@@ -68,7 +69,7 @@ def load_library():
     lib.xfp_probe_copy.argtypes = [vp, vp, u64, vp]
     lib.xfp_strerror.argtypes = [i32]
     lib.xfp_strerror.restype = ctypes.c_char_p
-    for name in ("xfp_gemv", "xfp_gemv_moe", "xfp_gemv_moe_silu_mul", "xfp_check_contents", "xfp_convert_bf16_to_f16", "xfp_unpack_indices", "xfp_dequant_bulk",
+    for name in ("xfp_gemv", "xfp_gemv_moe", "xfp_gemv_moe_silu_mul", "xfp_gemv_moe_combine", "xfp_check_contents", "xfp_convert_bf16_to_f16", "xfp_unpack_indices", "xfp_dequant_bulk",
                  "xfp_probe_read", "xfp_probe_copy", "xfp_version"):
         getattr(lib, name).restype = i32
     _lib = lib
@@ -212,6 +213,20 @@ def xfp_gemv_moe_silu_mul(bank: DeviceWeights, expert_ids: Optional[torch.Tensor
         ctypes.byref(bank.desc), _ptr(expert_ids) if expert_ids is not None else None, T, _ptr(x), x_slot_stride,
         _ptr(h) if T else h.data_ptr(), _y_code(h.dtype, x), ldh, _stream(stream)))
     return h
+
+
+def xfp_gemv_moe_combine(bank: DeviceWeights, expert_ids: torch.Tensor, x: torch.Tensor, slot_weights: torch.Tensor,
+                         y: Optional[torch.Tensor] = None, y_dtype=torch.float16, stream=None) -> torch.Tensor:
+    """y[n] = sum_t slot_weights[t] * (matrix expert_ids[t] applied to x[t])[n]; slot_weights fp32 [T]."""
+    T = int(expert_ids.numel())
+    assert slot_weights.dtype == torch.float32 and slot_weights.numel() == T
+    shared = x.dim() == 1 or x.shape[0] == 1 and T != 1
+    x_slot_stride = 0 if shared else x.stride(0)
+    if y is None:
+        y = torch.empty((bank.N,), dtype=y_dtype, device=x.device)
+    _check(load_library().xfp_gemv_moe_combine(ctypes.byref(bank.desc), _ptr(expert_ids), T, _ptr(x), x_slot_stride,
+                                               _ptr(slot_weights), _ptr(y), _y_code(y.dtype, x), _stream(stream)))
+    return y
 
 
 def xfp_check_contents(W: DeviceWeights, expert_ids: Optional[torch.Tensor] = None, stream=None) -> dict:

@@ -219,6 +219,28 @@ int xfp_gemv_moe_silu_mul(const xfp_weights *bank, const int32_t *expert_ids, in
                            static_cast<hipStream_t>(hip_stream));
 }
 
+int xfp_gemv_moe_combine(const xfp_weights *bank, const int32_t *expert_ids, int T, const void *x,
+                         int64_t x_slot_stride, const float *slot_weights, void *y, int y_dtype, void *hip_stream)
+{
+    int rc = check_weights(bank);
+    if (rc) return rc;
+    if (T <= 0 || T > 65535) return XFP_ERR_SHAPE;
+    if (!expert_ids || !slot_weights) return XFP_ERR_NULL;
+    rc = check_io(bank, x, y, y_dtype, (int64_t)bank->N);
+    if (rc) return rc;
+    if (x_slot_stride != 0 && x_slot_stride < (int64_t)bank->K) return XFP_ERR_SHAPE;
+    if (x_slot_stride % 8 != 0 || misaligned(expert_ids, 4) || misaligned(slot_weights, 4)) return XFP_ERR_ALIGN;
+    if ((uint64_t)T * bank->N > xfp::scratch_plane_floats()) return XFP_ERR_UNSUPPORTED;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    hipError_t perr = hipSuccess;
+    float *plane = xfp::scratch_plane(&perr);
+    if (!plane) return finish(perr);
+    rc = decode(bank, expert_ids, T, x, x_slot_stride, plane, XFP_F32 | (y_dtype & XFP_X_BF16), (int64_t)bank->N, s);
+    if (rc) return rc;
+    return finish(xfp::launch_moe_combine(plane, slot_weights, bank->N, T, y, (y_dtype & 0xFF) == XFP_F32,
+                                          (y_dtype & 0xFF) == XFP_BF16, s));
+}
+
 int xfp_convert_bf16_to_f16(const void *src, int64_t ld_src, void *dst, int rows, int cols, void *hip_stream)
 {
     if (!src || !dst) return XFP_ERR_NULL;

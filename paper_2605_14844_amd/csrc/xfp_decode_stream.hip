@@ -151,4 +151,24 @@ hipError_t launch_bf16_to_f16(const void *src, int64_t ld, void *dst, uint32_t r
     return hipGetLastError();
 }
 
+// y[n] = sum over slots t, in slot order, of w[t] * part[t][n] (fp32): the combine
+// step of a routed-expert layer, for the shapes no fused kernel takes.
+__global__ __launch_bounds__(256) void moe_combine_kernel(const float *part, const float *w, uint32_t N, uint32_t slots,
+                                                          void *y, int y_f32, int y_bf16)
+{
+    const uint32_t n = blockIdx.x * 256 + threadIdx.x;
+    if (n >= N) return;
+    float s = 0.f;
+    for (uint32_t t = 0; t < slots; ++t) s = fmaf(w[t], part[(size_t)t * N + n], s);
+    store_out(y, n, s, y_f32 != 0, y_bf16 != 0);
+}
+
+hipError_t launch_moe_combine(const float *part, const float *w, uint32_t N, int slots, void *y, bool y_f32,
+                              bool y_bf16, hipStream_t s)
+{
+    hipLaunchKernelGGL(moe_combine_kernel, dim3((N + 255) / 256), dim3(256), 0, s, part, w, N, (uint32_t)slots, y,
+                       (int)y_f32, (int)y_bf16);
+    return hipGetLastError();
+}
+
 }  // namespace xfp

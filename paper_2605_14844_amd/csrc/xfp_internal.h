@@ -59,6 +59,8 @@ float *scratch_plane(hipError_t *err);
 uint32_t scratch_plane_floats();
 hipError_t launch_silu_mul(const float *y, uint32_t half, int slots, void *h, int64_t h_stride, bool h_f32,
                            bool h_bf16, hipStream_t s);
+hipError_t launch_moe_combine(const float *part, const float *w, uint32_t N, int slots, void *y, bool y_f32,
+                              bool y_bf16, hipStream_t s);
 // bf16 [rows][ld] -> fp16 [rows][K] (exact inside fp16's normal range, saturating beyond it)
 hipError_t launch_bf16_to_f16(const void *src, int64_t ld, void *dst, uint32_t rows, uint32_t K, hipStream_t s);
 hipError_t launch_unpack(int bits, const uint32_t *idx, uint64_t rows, uint32_t K, uint8_t *out,

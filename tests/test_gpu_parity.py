@@ -435,3 +435,32 @@ def test_every_decode_call_replays_from_a_hip_graph():
             ref = oracle.gemv_weights(W, xb)
             assert gated_rel_err(host(y), ref) <= TOL_F32, (name, rep)
             assert gated_rel_err(host(h), oracle.silu_mul(ref)) <= TOL_F32, (name, rep)
+
+
+# ------------------------------------------------------------------ down projection with the router's combine
+@pytest.mark.parametrize("mode,bits,N,K,E,T", [(V2, 3, 256, 1024, 6, 8), (V2, 4, 100, 2048, 3, 2), (V2A, 3, 64, 512, 4, 5),
+                                               (V2, 3, 40, 20480, 2, 3), (V2, 2, 33, 768, 9, 8)])
+def test_down_projection_with_combine(mode, bits, N, K, E, T):
+    W = xi.random_weights(mode, bits, N, K, E=E, density=0.003, seed=N + T)
+    rng = np.random.default_rng(T)
+    ids = rng.integers(0, E, size=T).astype(np.int32)
+    w = rng.random(T).astype(np.float32)
+    w /= w.sum()
+    xb = xi.activations(rng, T, K)
+    ref = oracle.moe_combine(oracle.gemv_moe(W, ids, xb, shared_x=False), w)
+    dW = xfp.upload(W)
+    args = (dW, torch.from_numpy(ids).cuda(), dev_x(xb), torch.from_numpy(w).cuda())
+    y32 = host(xfp.xfp_gemv_moe_combine(*args, y_dtype=torch.float32))
+    y16 = host(xfp.xfp_gemv_moe_combine(*args, y_dtype=torch.float16))
+    assert y32.shape == (N,)
+    assert gated_rel_err(y32, ref) <= TOL_F32 and gated_rel_err(y16, ref) <= TOL_F16
+
+
+def test_workload_4_down_with_combine_full_bank():
+    _, dn = xi.config_weights(4)
+    ids = xi.config_expert_ids(4, 8, dn.E, draw=0)
+    w = np.random.default_rng(5).random(8).astype(np.float32)
+    x2 = xi.activations(np.random.default_rng(xi.BASE_SEED + 404), 8, dn.K)
+    ref = oracle.moe_combine(oracle.gemv_moe(dn, ids, x2, shared_x=False), w)
+    got = host(xfp.xfp_gemv_moe_combine(xfp.upload(dn), torch.from_numpy(ids).cuda(), dev_x(x2), torch.from_numpy(w).cuda()))
+    assert gated_rel_err(got, ref) <= TOL_F16

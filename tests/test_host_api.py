@@ -40,7 +40,7 @@ def moe(d, ids=FAKE, T=2, x=FAKE, xs=0, y=FAKE, dt=0, ldy=64):
 def test_library_exports_every_declared_symbol():
     lib = xfp.load_library()
     names = declared_functions()
-    assert {"xfp_gemv", "xfp_gemv_moe", "xfp_gemv_moe_silu_mul", "xfp_check_contents", "xfp_convert_bf16_to_f16", "xfp_unpack_indices", "xfp_dequant_bulk", "xfp_strerror",
+    assert {"xfp_gemv", "xfp_gemv_moe", "xfp_gemv_moe_silu_mul", "xfp_gemv_moe_combine", "xfp_check_contents", "xfp_convert_bf16_to_f16", "xfp_unpack_indices", "xfp_dequant_bulk", "xfp_strerror",
             "xfp_version", "xfp_probe_read", "xfp_probe_copy"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
@@ -92,7 +92,8 @@ def test_unsupported_format():
     assert gemv(desc(mode=1, L=0, group_ids=FAKE)) == -3
     assert gemv(desc(mode=1, L=300, group_ids=FAKE)) == -3
     assert gemv(desc(L=32)) == -3                              # L given for V2
-    assert gemv(desc(), dt=2) == -3                            # bad y dtype
+    assert gemv(desc(), dt=3) == -3                            # bad y dtype (0 fp16, 1 fp32, 2 bf16)
+    assert gemv(desc(), dt=0x200) == -3                        # unknown flag (0x100: x is bf16)
 
 
 def test_alignment_errors():
@@ -112,4 +113,8 @@ def test_moe_zero_slots_is_a_no_op():
 def test_binding_rejects_bad_y_dtype_without_touching_the_gpu():
     import torch
     with pytest.raises(xfp.XfpError):
-        xfp.binding._y_code(torch.bfloat16)
+        xfp.binding._y_code(torch.float64)
+    with pytest.raises(xfp.XfpError):
+        xfp.binding._y_code(torch.float16, torch.zeros(4, dtype=torch.float32))     # x must be fp16 or bf16
+    assert xfp.binding._y_code(torch.bfloat16) == xfp.XFP_BF16
+    assert xfp.binding._y_code(torch.float32, torch.zeros(4, dtype=torch.bfloat16)) == xfp.XFP_F32 | xfp.XFP_X_BF16

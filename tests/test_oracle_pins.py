@@ -300,3 +300,21 @@ def test_silu_mul_against_library_logistic_closed_forms_and_layout():
     w = np.array([[2.0, -1.0, 0.5, 3.0]])
     assert np.allclose(oracle.silu_mul(w), [[2.0 * expit(2.0) * 0.5, -expit(-1.0) * 3.0]])
     assert not np.allclose(oracle.silu_mul(w), oracle.silu_mul(w[:, [2, 3, 0, 1]]))
+
+
+def test_moe_combine_special_cases_and_matmul():
+    rng = np.random.default_rng(9)
+    y = rng.normal(size=(5, 12))
+    w = rng.random(5).astype(np.float32)
+    assert np.allclose(oracle.moe_combine(y, w), w.astype(np.float64) @ y, rtol=1e-14)        # library matmul
+    e = np.zeros(5, np.float32)
+    e[3] = 1.0
+    assert np.array_equal(oracle.moe_combine(y, e), y[3])                                      # one-hot picks a slot
+    assert np.array_equal(oracle.moe_combine(y, np.zeros(5, np.float32)), np.zeros(12))
+    assert np.allclose(oracle.moe_combine(y, np.full(5, 0.5, np.float32)), 0.5 * y.sum(axis=0), rtol=1e-14)
+    # linear in the weights and in y
+    w2 = rng.random(5).astype(np.float32)
+    assert np.allclose(oracle.moe_combine(y, w) + oracle.moe_combine(y, w2),
+                       (w.astype(np.float64) + w2.astype(np.float64)) @ y, rtol=1e-13)
+    assert np.allclose(oracle.moe_combine(y + 2.0 * y[::-1], w), oracle.moe_combine(y, w) + 2.0 * oracle.moe_combine(y[::-1], w),
+                       rtol=1e-13)
