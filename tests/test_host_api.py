@@ -118,3 +118,30 @@ def test_binding_rejects_bad_y_dtype_without_touching_the_gpu():
         xfp.binding._y_code(torch.float16, torch.zeros(4, dtype=torch.float32))     # x must be fp16 or bf16
     assert xfp.binding._y_code(torch.bfloat16) == xfp.XFP_BF16
     assert xfp.binding._y_code(torch.float32, torch.zeros(4, dtype=torch.bfloat16)) == xfp.XFP_F32 | xfp.XFP_X_BF16
+
+
+def test_new_entry_points_reject_bad_arguments():
+    """Every call below fails validation, so nothing is launched (the pointers are fakes)."""
+    lib = xfp.load_library()
+    d = desc(E=4)
+    silu = lambda dd=d, ids=FAKE, T=2, x=FAKE, xs=0, h=FAKE, dt=0, ldh=32: lib.xfp_gemv_moe_silu_mul(
+        ctypes.byref(dd), ids, T, x, xs, h, dt, ldh, None)
+    assert silu(dd=desc(E=4, N=63)) == -2                      # N must be even
+    assert silu(ldh=31) == -2                                  # ldh < N / 2
+    assert silu(ids=None) == -1                                # ids required for a bank of several matrices
+    assert silu(h=None) == -1 and silu(x=None) == -1
+    assert silu(dt=7) == -3
+    assert silu(T=0, ids=None, x=None, h=None) == 0
+    comb = lambda ids=FAKE, T=2, x=FAKE, xs=256, w=FAKE, y=FAKE, dt=0: lib.xfp_gemv_moe_combine(
+        ctypes.byref(d), ids, T, x, xs, w, y, dt, None)
+    assert comb(T=0) == -2 and comb(xs=64) == -2
+    assert comb(w=None) == -1 and comb(ids=None) == -1 and comb(y=None) == -1
+    assert comb(w=FAKE + 2) == -4 and comb(dt=9) == -3
+    cvt = lambda src=FAKE, ld=256, dst=FAKE, rows=2, cols=256: lib.xfp_convert_bf16_to_f16(src, ld, dst, rows, cols, None)
+    assert cvt(src=None) == -1 and cvt(dst=None) == -1
+    assert cvt(cols=100) == -2 and cvt(ld=128) == -2 and cvt(rows=-1) == -2
+    assert cvt(src=FAKE + 2) == -4 and cvt(ld=260) == -4
+    assert cvt(rows=0) == 0
+    chk = lambda dd=d, cap=10, ids=None, T=0, rep=FAKE: lib.xfp_check_contents(ctypes.byref(dd), cap, ids, T, rep, None)
+    assert chk(rep=None) == -1 and chk(cap=-1) == -2 and chk(rep=FAKE + 4) == -4
+    assert chk(dd=desc(out_col=None)) == -1                   # entries claimed but no column array
