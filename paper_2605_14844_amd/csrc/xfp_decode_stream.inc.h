@@ -16,13 +16,15 @@
 //    8-byte (2-bit) load per lane per chunk; a wave issues the loads of a
 //    whole batch of rows before it touches any of them, and no load is
 //    conditional (out-of-range rows and lanes read a clamped address).
-//  - Codebook lookups go to LDS.  4-bit: the row's 16 fp16 entries as they
-//    are (8 dwords = 8 banks, equal addresses broadcast, so no conflicts);
-//    the byte address of an entry is produced by one SDWA shift per index.
-//    A pair table (two indices -> two fp16 in one dword) is built per row
-//    (V2) or per library codebook (V2a, once per workgroup), so one lookup and
-//    one v_dot2_f32_f16 serve two weights.  V2a: the group's library id picks
-//    the table per lane; it is OR-ed into the lookup address.
+//  - Codebook lookups go to LDS, through a pair table (two indices -> two
+//    fp16 in one dword) built per row (V2) or per library codebook (V2a, once
+//    per workgroup): one lookup and one v_dot2_f32_f16 serve two weights, and
+//    the address of an entry is one SDWA shift of an index byte (4-/2-bit) or a
+//    shift and a mask (3-bit).  V2a: the group's library id picks the table
+//    per lane; it is OR-ed into the lookup address.  The lookups of 64 lanes
+//    into one row's table are random and collide on the 32 banks (5.5 clocks
+//    per wave instruction against 2.6 conflict-free): this, not HBM, is what
+//    bounds the 4-bit kernel once the data is flowing.
 //  - Lookups are software-pipelined in groups of eight: the addresses and LDS
 //    reads of group t+1 are issued before the multiply-accumulates of group t.
 //  - fp32 accumulation in a fixed order, DPP reduction, no atomics: results
@@ -30,6 +32,9 @@
 //  - The CSR outliers of a batch of rows are contiguous; they are fetched with
 //    one bounds-checked buffer load per lane while the index stream is still
 //    in flight and folded into the owning row's sum before the reduction.
+//  - Variants (compile-time, one translation unit each): split-K for rows
+//    longer than a wave holds in registers, and a gate/up form that pairs each
+//    gate row with its up row in a batch and stores SiLU(gate) * up.
 #pragma once
 #include "xfp_device.h"
 
@@ -71,24 +76,14 @@ __device__ __forceinline__ uint32_t byte_shr(uint32_t m, int j, uint32_t amount)
     return r;
 }
 
-__device__ __forceinline__ float fma_h(_Float16 c, _Float16 x, float acc)
-{
-    return __builtin_fmaf((float)c, (float)x, acc);     // v_fma_mix_f32
-}
-
-#ifndef XFP_B4_PAIR
-#define XFP_B4_PAIR 1
-#endif
-
 // Geometry of the per-row LDS table for each bit width.  A pair table maps two
 // adjacent indices (4, 6 or 8 stream bits) to two fp16 values in one dword.
 template <int BITS>
 struct TableFmt {
     static constexpr int kEntries = 1 << BITS;
-    static constexpr bool kPair = BITS != 4 || XFP_B4_PAIR;
-    static constexpr int kRowBytes = kPair ? (4 << (2 * BITS)) : 2 * kEntries;   // 64, 256, 1024 (32 unpaired)
-    static constexpr int kRawBytes = 2 * kEntries;                              // 8, 16, 32
-    static constexpr int kGroupsPerLaneLoad = kPair ? 2 : 4;                    // groups of 8 lookups
+    static constexpr int kRowBytes = 4 << (2 * BITS);          // 64, 256, 1024
+    static constexpr int kRawBytes = 2 * kEntries;             // 8, 16, 32: the codebook itself
+    static constexpr int kGroupsPerLaneLoad = 2;               // groups of 8 lookups (16 pairs = 32 weights)
 };
 
 // Eight lookups of one lane-load: compute LDS addresses and issue the reads.
@@ -101,33 +96,15 @@ struct TableFmt {
 //         it is then OR-ed into the address instead of the index bytes.
 template <int BITS, bool BIASED, bool WIDE = false>
 __device__ __forceinline__ void issue_group(const LaneWords<BITS> &lw, int g, uint32_t tb, uint32_t bias,
-                                            uint32_t (&v)[8], uint32_t k1, uint32_t k2, uint32_t k3)
+                                            uint32_t (&v)[8], uint32_t k2)
 {
-    if constexpr (BITS == 4 && TableFmt<4>::kPair) {
+    if constexpr (BITS == 4) {
         // an index byte (two indices) selects one dword of the row's 256-entry pair table
         const uint32_t ab = BIASED ? bias * TableFmt<4>::kRowBytes : 0u;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const uint32_t a = byte_shl(lw.w[2 * g + (i >> 2)], i & 3, k2);   // byte * 4
             v[i] = *(lds_u32_t *)(uintptr_t)(tb + (BIASED ? (a | ab) : a));
-        }
-    } else if constexpr (BITS == 4) {
-        const uint32_t w = lw.w[g];
-        uint32_t m0, m1;
-        if constexpr (BIASED) {
-            const uint32_t bb = bias * 0x10101010u;
-            m0 = (w & 0x0F0F0F0Fu) | bb;
-            m1 = ((w >> 4) & 0x0F0F0F0Fu) | bb;
-        } else {
-            m0 = w & 0x0F0F0F0Fu;
-            m1 = w & 0xF0F0F0F0u;
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const uint32_t a0 = byte_shl(m0, j, k1);                       // index * 2
-            const uint32_t a1 = BIASED ? byte_shl(m1, j, k1) : byte_shr(m1, j, k3);
-            v[2 * j] = *(lds_u16_t *)(uintptr_t)(tb + a0);
-            v[2 * j + 1] = *(lds_u16_t *)(uintptr_t)(tb + a1);
         }
     } else if constexpr (BITS == 3) {
         const uint32_t ab = BIASED ? bias * TableFmt<3>::kRowBytes : 0u;
@@ -168,18 +145,8 @@ __device__ __forceinline__ void issue_group(const LaneWords<BITS> &lw, int g, ui
 template <int BITS>
 __device__ __forceinline__ void consume_group(int g, const uint32_t (&v)[8], const uint32_t *xw, float (&acc)[4])
 {
-    if constexpr (BITS == 4 && !TableFmt<4>::kPair) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const half2_t xp = as_half2(xw[g * 4 + j]);
-            acc[(2 * j) & 3] = fma_h(as_half2(v[2 * j]).x, xp.x, acc[(2 * j) & 3]);
-            acc[(2 * j + 1) & 3] = fma_h(as_half2(v[2 * j + 1]).x, xp.y, acc[(2 * j + 1) & 3]);
-        }
-    } else {
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-            acc[i & 3] = dot2(as_half2(v[i]), as_half2(xw[g * 8 + i]), acc[i & 3]);
-    }
+    for (int i = 0; i < 8; ++i) acc[i & 3] = dot2(as_half2(v[i]), as_half2(xw[g * 8 + i]), acc[i & 3]);
 }
 
 // NCH : 2048-wide chunks per row (RPC == 1), K <= NCH * 2048
@@ -200,7 +167,7 @@ struct StreamCfg {
     static constexpr int kBatchRows = kUnroll * RPC;           // rows a wave decodes at once
     static constexpr int kLanesPerRow = kWave / RPC;
     static constexpr int kTableBytes = (kBatchRows + 1) * TableFmt<BITS>::kRowBytes;   // + zero table
-    static constexpr int kRawBytes = TableFmt<BITS>::kPair ? kBatchRows * TableFmt<BITS>::kRawBytes : 0;
+    static constexpr int kRawBytes = kBatchRows * TableFmt<BITS>::kRawBytes;
     // registers: 16 per chunk for x, BITS per lane-load in flight, ~60 working
     static constexpr int kRegs = 16 * NCH + BITS * NCH * kUnroll + 60;
     static constexpr int kWavesPerSimd = kRegs <= 128 ? 4 : (kRegs <= 168 ? 3 : 2);
@@ -228,7 +195,6 @@ void decode_stream_kernel(DecodeArgs a, int y_f32)
     constexpr int kStreamWaves = stream_waves(MODE), kStreamThreads = kStreamWaves * kWave;
     using Cfg = StreamCfg<BITS, NCH, RPC, UNROLL>;
     using Fmt = TableFmt<BITS>;
-    static_assert(Fmt::kPair, "pair tables only");
     constexpr int U = Cfg::kUnroll, B = Cfg::kBatchRows, LPR = Cfg::kLanesPerRow;
     constexpr int ENT = Fmt::kEntries, GPL = Fmt::kGroupsPerLaneLoad;
     // V2: the wave's tables, a static array.  V2a: the library's tables fill the
@@ -288,7 +254,7 @@ void decode_stream_kernel(DecodeArgs a, int y_f32)
     auto cb_word = [&](uint32_t rb, uint32_t li) -> uint32_t {             // dword li of the batch's codebooks
         return min(arow(rb, li / (ENT / 2)) * (ENT / 2) + li % (ENT / 2), cb_last);
     };
-    const uint32_t k1 = 1, k2 = 2, k3 = 3;
+    const uint32_t k2 = 2;                                     // SDWA shift amount, kept in a VGPR
     constexpr int CBW = (B * (ENT / 2) + kWave - 1) / kWave;   // codebook dwords per lane per batch
 
     // a3: the index words (and V2a library ids) of one batch of rows; rows past
@@ -516,13 +482,13 @@ void decode_stream_kernel(DecodeArgs a, int y_f32)
                 const uint32_t tb = lds_base + u * RPC * Fmt::kRowBytes;
                 if constexpr (MODE == 1) {
                     const uint32_t dead = TAIL && c == NCH - 1 && !live_last;
-                    issue_group<BITS, true, true>(lw[u][c], g, lds_base, dead ? a.L : lib[u][c], v, k1, k2, k3);
+                    issue_group<BITS, true, true>(lw[u][c], g, lds_base, dead ? a.L : lib[u][c], v, k2);
                 } else if (RPC > 1)
-                    issue_group<BITS, true>(lw[u][c], g, tb, seg, v, k1, k2, k3);
+                    issue_group<BITS, true>(lw[u][c], g, tb, seg, v, k2);
                 else if (TAIL && c == NCH - 1)
-                    issue_group<BITS, true>(lw[u][c], g, tb, live_last ? 0u : (uint32_t)(B - u), v, k1, k2, k3);
+                    issue_group<BITS, true>(lw[u][c], g, tb, live_last ? 0u : (uint32_t)(B - u), v, k2);
                 else
-                    issue_group<BITS, false>(lw[u][c], g, tb, 0u, v, k1, k2, k3);
+                    issue_group<BITS, false>(lw[u][c], g, tb, 0u, v, k2);
             };
             issue(0, val[0]);
 #pragma unroll
