@@ -152,12 +152,16 @@ int xfp_gemv_moe_silu_mul(const xfp_weights *bank, const int32_t *expert_ids, in
 /*
  * Down projection of a routed-expert layer with the router's combine folded in:
  *     y[n] = sum over slots t of slot_weights[t] * (matrix expert_ids[t] applied to input row t)[n],
- * the slots added in ascending order in fp32, one rounding to y_dtype.  Like
+ * accumulated in fp32, one rounding to y_dtype.  Like
  * the gate/up epilogue this is the library's addition to what the paper
  * describes (sections 1 and 6.1 apply the decode to routed experts and name
- * launch overhead as what dominates them).  Today the per-slot results meet in
- * a static fp32 scratch plane (T * N <= 2^20, else XFP_ERR_UNSUPPORTED) and a
- * second small kernel adds them: one call and no fp16 round trip, two launches.
+ * launch overhead as what dominates them).  V2 banks with T <= 8 and
+ * T * K <= 16384 take one launch: an output row is decoded as the concatenation
+ * of the T experts' rows, each part scaled by its slot's weight (the slots are
+ * then added lane by lane and by a wave reduction, not in ascending order).
+ * Other shapes: the per-slot results meet in a static fp32 scratch plane
+ * (T * N <= 2^20, else XFP_ERR_UNSUPPORTED) and a second small kernel adds them
+ * in ascending slot order.
  *
  * slot_weights   device fp32 [T].   y  [N] of y_dtype.   T >= 1.
  * Everything else as for xfp_gemv_moe.

@@ -230,15 +230,28 @@ int xfp_gemv_moe_combine(const xfp_weights *bank, const int32_t *expert_ids, int
     if (rc) return rc;
     if (x_slot_stride != 0 && x_slot_stride < (int64_t)bank->K) return XFP_ERR_SHAPE;
     if (x_slot_stride % 8 != 0 || misaligned(expert_ids, 4) || misaligned(slot_weights, 4)) return XFP_ERR_ALIGN;
-    if ((uint64_t)T * bank->N > xfp::scratch_plane_floats()) return XFP_ERR_UNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (y_dtype & XFP_X_BF16) {
+        rc = convert_x(bank, x_slot_stride == 0 ? 1 : T, x, x_slot_stride, s);
+        if (rc) return rc;
+    }
+    const int yd = y_dtype & 0xFF;
+    if (xfp::combine_supports((int)bank->bits, (int)bank->mode, bank->K, T)) {
+        xfp::DecodeArgs a = base_args(bank);
+        a.x = static_cast<const uint16_t *>(x);
+        a.y = y;
+        a.eids = expert_ids;
+        a.x_stride = x_slot_stride;
+        return finish(xfp::launch_decode_combine((int)bank->bits, a, T, slot_weights, yd == XFP_F32, yd == XFP_BF16, s));
+    }
+    // other shapes: per-slot fp32 results in a scratch plane, added by a second kernel
+    if ((uint64_t)T * bank->N > xfp::scratch_plane_floats()) return XFP_ERR_UNSUPPORTED;
     hipError_t perr = hipSuccess;
     float *plane = xfp::scratch_plane(&perr);
     if (!plane) return finish(perr);
-    rc = decode(bank, expert_ids, T, x, x_slot_stride, plane, XFP_F32 | (y_dtype & XFP_X_BF16), (int64_t)bank->N, s);
+    rc = decode(bank, expert_ids, T, x, x_slot_stride, plane, XFP_F32, (int64_t)bank->N, s);
     if (rc) return rc;
-    return finish(xfp::launch_moe_combine(plane, slot_weights, bank->N, T, y, (y_dtype & 0xFF) == XFP_F32,
-                                          (y_dtype & 0xFF) == XFP_BF16, s));
+    return finish(xfp::launch_moe_combine(plane, slot_weights, bank->N, T, y, yd == XFP_F32, yd == XFP_BF16, s));
 }
 
 int xfp_convert_bf16_to_f16(const void *src, int64_t ld_src, void *dst, int rows, int cols, void *hip_stream)

@@ -59,6 +59,10 @@ float *scratch_plane(hipError_t *err);
 uint32_t scratch_plane_floats();
 hipError_t launch_silu_mul(const float *y, uint32_t half, int slots, void *h, int64_t h_stride, bool h_f32,
                            bool h_bf16, hipStream_t s);
+// Down projection with the router's weighted sum over the slots in one launch (V2, T <= 8, T * K <= 16384)
+bool combine_supports(int bits, int mode, uint32_t K, int T);
+hipError_t launch_decode_combine(int bits, const DecodeArgs &d, int T, const float *w, bool y_f32, bool y_bf16,
+                                 hipStream_t s);
 hipError_t launch_moe_combine(const float *part, const float *w, uint32_t N, int slots, void *y, bool y_f32,
                               bool y_bf16, hipStream_t s);
 // bf16 [rows][ld] -> fp16 [rows][K] (exact inside fp16's normal range, saturating beyond it)

@@ -439,7 +439,10 @@ def test_every_decode_call_replays_from_a_hip_graph():
 
 # ------------------------------------------------------------------ down projection with the router's combine
 @pytest.mark.parametrize("mode,bits,N,K,E,T", [(V2, 3, 256, 1024, 6, 8), (V2, 4, 100, 2048, 3, 2), (V2A, 3, 64, 512, 4, 5),
-                                               (V2, 3, 40, 20480, 2, 3), (V2, 2, 33, 768, 9, 8)])
+                                               (V2, 3, 40, 20480, 2, 3), (V2, 2, 33, 768, 9, 8),
+                                               (V2, 4, 50, 640, 5, 3), (V2, 3, 70, 1408, 4, 7), (V2, 4, 9, 128, 2, 1),
+                                               (V2, 4, 300, 2048, 4, 8), (V2, 3, 20, 1024, 3, 12),
+                                               (V2, 4, 2050, 1024, 3, 4), (V2, 3, 4099, 512, 2, 8), (V2, 2, 4100, 640, 3, 5)])
 def test_down_projection_with_combine(mode, bits, N, K, E, T):
     W = xi.random_weights(mode, bits, N, K, E=E, density=0.003, seed=N + T)
     rng = np.random.default_rng(T)
@@ -454,6 +457,24 @@ def test_down_projection_with_combine(mode, bits, N, K, E, T):
     y16 = host(xfp.xfp_gemv_moe_combine(*args, y_dtype=torch.float16))
     assert y32.shape == (N,)
     assert gated_rel_err(y32, ref) <= TOL_F32 and gated_rel_err(y16, ref) <= TOL_F16
+
+
+def test_down_projection_with_combine_rows_full_of_outliers():
+    K, E, T = 1024, 3, 4
+    W = xi.random_weights(V2, 3, 16, K, E=E, density=0.0, seed=61)
+    rp = np.zeros(E * 16 + 1, dtype=np.int32)
+    rp[16 + 5 + 1:] = K                      # expert 1, row 5 holds a whole row of entries
+    rp[32 + 5 + 1:] += 40                    # expert 2, row 5 holds 40
+    W.out_row_ptr = rp
+    W.out_col = np.concatenate([np.arange(K, dtype=np.int32), np.arange(40, dtype=np.int32) * 25])
+    W.out_val = xi.activations(np.random.default_rng(62), 1, K + 40).ravel()
+    ids = np.array([1, 2, 0, 1], dtype=np.int32)
+    w = np.array([0.4, 0.3, 0.2, 0.1], dtype=np.float32)
+    xb = xi.activations(np.random.default_rng(63), T, K)
+    ref = oracle.moe_combine(oracle.gemv_moe(W, ids, xb, shared_x=False), w)
+    got = host(xfp.xfp_gemv_moe_combine(xfp.upload(W), torch.from_numpy(ids).cuda(), dev_x(xb),
+                                        torch.from_numpy(w).cuda(), y_dtype=torch.float32))
+    assert gated_rel_err(got, ref) <= TOL_F32
 
 
 def test_workload_4_down_with_combine_full_bank():
