@@ -3,7 +3,8 @@
 
 A step is one pass of the whole hot path over one batch: one xfp_gemv call
 (workloads 1, 2, 3, 5) or one gate_up + one down xfp_gemv_moe call (workload
-4).  Weights are already resident in HBM; successive steps walk a ring of
+4).  Two more configurations measure what was added beyond the five: 6 (the
+expert layer of workload 4 with both epilogues fused) and 7 (split-K).  Weights are already resident in HBM; successive steps walk a ring of
 distinct device copies whose total size exceeds the last-level cache, so the
 weights of a step are never cache-resident.  The K timed steps are recorded
 into one HIP graph and replayed once between two events on the launch stream
@@ -31,7 +32,9 @@ def parse_args():
     p.add_argument("--gpus", type=int, default=1)
     p.add_argument("--steps", type=int, default=2000)
     p.add_argument("--warmup", type=int, default=200)
-    p.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2, the headline)")
+    p.add_argument("--config", type=int, default=2,
+                   help="workload 1..5 (default 2, the headline); beyond the five: 6 = workload 4 as a whole expert "
+                        "layer with both epilogues fused, 7 = a long-row matrix (8192x28672, 4-bit, M=1) through split-K")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-graph", action="store_true", help="time eager launches instead of a graph")
     p.add_argument("--no-plain-read", action="store_true", help="skip the read-only ceiling measurement")
@@ -113,6 +116,63 @@ def build_workload(cfg: int, ring_bytes: int):
         return dict(name=xi.CONFIG_NAMES[4], step=step, bytes=b1 + b2, ring=draws, oracle=oracle_once,
                     launches=2, kernel_bytes=b1, launch_bytes=[b1, b2], keep=(dgu, ddn, ids_dev, x1, x2, y1, y2), M=1,
                     N=gu.N, K=gu.K, bits=3, mode=0)
+    if cfg == 6:
+        # workload 4 as an expert layer: gate/up with SiLU(gate)*up in the store, then the down projection
+        # with the router's weighted sum; the intermediate h feeds the second call (two launches per step)
+        T = 8
+        gu, dn = xi.config_weights(4)
+        dgu, ddn = xfp.upload(gu), xfp.upload(dn)
+        draws = 64
+        ids_host = [xi.config_expert_ids(4, T, gu.E, draw=d) for d in range(draws)]
+        ids_dev = [torch.from_numpy(a).cuda() for a in ids_host]
+        x1b = xi.config_x(4, 1, gu.K)
+        x1 = dev_x(x1b)[0]
+        w_host = np.random.default_rng(xi.BASE_SEED + 406).random(T).astype(np.float32)
+        w_host /= w_host.sum()
+        w_dev = torch.from_numpy(w_host).cuda()
+        h = torch.empty((T, gu.N // 2), dtype=torch.float16, device="cuda")
+        y = torch.empty((dn.N,), dtype=torch.float16, device="cuda")
+        assert gu.N // 2 == dn.K
+        b1 = gu.algorithmic_bytes(experts=T, shared_x=True) - T * gu.N * 2 + T * (gu.N // 2) * 2   # h instead of y
+        b2 = dn.algorithmic_bytes(experts=T, shared_x=False) - T * dn.N * 2 + dn.N * 2 + T * 4     # one y, T weights
+
+        def step(i):
+            ids = ids_dev[i % draws]
+            xfp.xfp_gemv_moe_silu_mul(dgu, ids, x1, h=h)
+            xfp.xfp_gemv_moe_combine(ddn, ids, h, w_dev, y=y)
+
+        def oracle_once(threads=None):
+            import oracle
+            hh = oracle.silu_mul(oracle.gemv_moe(gu, ids_host[0], x1b, True, threads))
+            hb = hh.astype(np.float16).view(np.uint16)
+            return oracle.moe_combine(oracle.gemv_moe(dn, ids_host[0], hb, False, threads), w_host)
+
+        return dict(name="expert layer of workload 4: gate_up with SiLU(gate)*up, down with the router's combine",
+                    step=step, bytes=b1 + b2, ring=draws, oracle=oracle_once, launches=2, kernel_bytes=b1,
+                    launch_bytes=[b1, b2], keep=(dgu, ddn, ids_dev, x1, h, y, w_dev), M=1, N=gu.N, K=gu.K, bits=3,
+                    mode=0)
+
+    if cfg == 7:
+        W = xi.random_weights(xi.MODE_V2, 4, 8192, 28672, density=0.003, seed=xi.BASE_SEED + 7)
+        xb = xi.activations(np.random.default_rng(xi.BASE_SEED + 407), 1, W.K)
+        nbytes = W.algorithmic_bytes(M=1)
+        R = max(1, min(512, -(-ring_bytes // nbytes)))
+        ring = [xfp.upload(W)]
+        for _ in range(R - 1):
+            ring.append(clone_weights(ring[0]))
+        xd = dev_x(xb)
+        y = torch.empty((1, W.N), dtype=torch.float16, device="cuda")
+
+        def step(i):
+            xfp.xfp_gemv(ring[i % R], xd, y=y)
+
+        def oracle_once(threads=None):
+            import oracle
+            return oracle.gemv_weights(W, xb, threads)
+
+        return dict(name="V2 8192x28672 b4 M=1 (rows longer than 16384: split-K, two launches)", step=step,
+                    bytes=nbytes, ring=R, oracle=oracle_once, launches=2, kernel_bytes=nbytes,
+                    launch_bytes=[nbytes], keep=(ring, xd, y), M=1, N=W.N, K=W.K, bits=4, mode=0)
     raise SystemExit(f"no workload {cfg}")
 
 
