@@ -459,6 +459,21 @@ def test_down_projection_with_combine(mode, bits, N, K, E, T):
     assert gated_rel_err(y32, ref) <= TOL_F32 and gated_rel_err(y16, ref) <= TOL_F16
 
 
+def test_down_projection_with_combine_shared_input_and_bf16():
+    W = xi.random_weights(V2, 4, 72, 1024, E=4, density=0.004, seed=64)
+    ids = np.array([3, 1, 3, 0, 2], dtype=np.int32)
+    w = np.array([0.5, 0.2, 0.1, 0.1, 0.1], dtype=np.float32)
+    x16 = xi.activations(np.random.default_rng(65), 1, W.K) & np.uint16(0xFFF8)
+    ref = oracle.moe_combine(oracle.gemv_moe(W, ids, x16, shared_x=True), w)
+    dW, ids_d, w_d = xfp.upload(W), torch.from_numpy(ids).cuda(), torch.from_numpy(w).cuda()
+    got = host(xfp.xfp_gemv_moe_combine(dW, ids_d, dev_x(x16)[0], w_d, y_dtype=torch.float32))
+    assert gated_rel_err(got, ref) <= TOL_F32
+    xbf = ((x16.view(np.float16).astype(np.float32).view(np.uint32)) >> 16).astype(np.uint16)
+    xd = torch.from_numpy(xbf.view(np.int16)).cuda().view(torch.bfloat16)
+    got = host(xfp.xfp_gemv_moe_combine(dW, ids_d, xd[0], w_d, y_dtype=torch.bfloat16))
+    assert gated_rel_err(got, ref) <= TOL_BF16
+
+
 def test_down_projection_with_combine_rows_full_of_outliers():
     K, E, T = 1024, 3, 4
     W = xi.random_weights(V2, 3, 16, K, E=E, density=0.0, seed=61)
