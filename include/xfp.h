@@ -28,7 +28,13 @@
  *    below L, CSR row pointers ascending and columns in [0, K)) are the
  *    caller's contract; violating it is undefined behaviour.
  *    xfp_check_contents checks that contract on the device.
- *  - No global mutable state; calls from several host threads are safe.
+ *  - Calls from several host threads are safe.  The only state kept between
+ *    calls is a set of small static device rings used as scratch by some
+ *    paths (re-laid activations of the batched path: 16 slots; fp32 planes for
+ *    split-K partial sums, the unfused epilogues and converted bf16
+ *    activations: 4 slots of 4 MB).  A call takes the next slot, so calls on
+ *    ONE stream never interfere; calls that overlap on different streams do
+ *    only when more of them are in flight at once than the ring has slots.
  *
  * Data layout (all little-endian)
  *  - indices: per matrix, N rows of K*bits/32 uint32 words, no row padding.
