@@ -500,3 +500,29 @@ def test_workload_4_down_with_combine_full_bank():
     ref = oracle.moe_combine(oracle.gemv_moe(dn, ids, x2, shared_x=False), w)
     got = host(xfp.xfp_gemv_moe_combine(xfp.upload(dn), torch.from_numpy(ids).cuda(), dev_x(x2), torch.from_numpy(w).cuda()))
     assert gated_rel_err(got, ref) <= TOL_F16
+
+
+# ------------------------------------------------------------------ seeded sweep over shapes
+def _sweep_cases():
+    rng = np.random.default_rng(20260514)
+    ks = [128, 256, 384, 512, 640, 1024, 1152, 2048, 2176, 4096, 5120, 8192, 8320, 12288, 16384, 16512, 18432, 24576]
+    cases = []
+    for i in range(48):
+        mode = int(rng.integers(0, 2))
+        bits = int(rng.integers(2, 5))
+        K = int(ks[int(rng.integers(0, len(ks)))])
+        N = int(rng.integers(1, 200))
+        M = int([1, 1, 1, 2, 5, 16, 17][int(rng.integers(0, 7))])
+        if K * N * M > 40_000_000:
+            N = max(1, 40_000_000 // (K * M))
+        dens = float([0.0, 0.001, 0.003, 0.02][int(rng.integers(0, 4))])
+        cases.append((i, mode, bits, N, K, M, dens))
+    return cases
+
+
+@pytest.mark.parametrize("i,mode,bits,N,K,M,dens", _sweep_cases())
+def test_seeded_shape_sweep(i, mode, bits, N, K, M, dens):
+    """Every kernel family and its borders (short rows, tails, split-K, the general kernel, chunks of 16 tokens)
+    under one fixed list of drawn shapes."""
+    W = xi.random_weights(mode, bits, N, K, density=dens, seed=1000 + i)
+    check_gemv(W, xi.activations(np.random.default_rng(2000 + i), M, K))
