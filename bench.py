@@ -34,7 +34,8 @@ def parse_args():
     p.add_argument("--warmup", type=int, default=200)
     p.add_argument("--config", type=int, default=2,
                    help="workload 1..5 (default 2, the headline); beyond the five: 6 = workload 4 as a whole expert "
-                        "layer with both epilogues fused, 7 = a long-row matrix (8192x28672, 4-bit, M=1) through split-K")
+                        "layer with both epilogues fused, 7 = a long-row matrix (8192x28672, 4-bit, M=1) through split-K, "
+                        "8 = the same matrix with 16 tokens")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-graph", action="store_true", help="time eager launches instead of a graph")
     p.add_argument("--no-plain-read", action="store_true", help="skip the read-only ceiling measurement")
@@ -173,6 +174,27 @@ def build_workload(cfg: int, ring_bytes: int):
         return dict(name="V2 8192x28672 b4 M=1 (rows longer than 16384: split-K, two launches)", step=step,
                     bytes=nbytes, ring=R, oracle=oracle_once, launches=2, kernel_bytes=nbytes,
                     launch_bytes=[nbytes], keep=(ring, xd, y), M=1, N=W.N, K=W.K, bits=4, mode=0)
+    if cfg == 8:
+        W = xi.random_weights(xi.MODE_V2, 4, 8192, 28672, density=0.003, seed=xi.BASE_SEED + 7)
+        xb = xi.activations(np.random.default_rng(xi.BASE_SEED + 408), 16, W.K)
+        nbytes = W.algorithmic_bytes(M=16)
+        R = max(1, min(512, -(-ring_bytes // nbytes)))
+        ring = [xfp.upload(W)]
+        for _ in range(R - 1):
+            ring.append(clone_weights(ring[0]))
+        xd = dev_x(xb)
+        y = torch.empty((16, W.N), dtype=torch.float16, device="cuda")
+
+        def step(i):
+            xfp.xfp_gemv(ring[i % R], xd, y=y)
+
+        def oracle_once(threads=None):
+            import oracle
+            return oracle.gemv_weights(W, xb, threads)
+
+        return dict(name="V2 8192x28672 b4 M=16 (matrix-core kernel over four slices of K, three launches)", step=step,
+                    bytes=nbytes, ring=R, oracle=oracle_once, launches=3, kernel_bytes=nbytes,
+                    launch_bytes=[nbytes], keep=(ring, xd, y), M=16, N=W.N, K=W.K, bits=4, mode=0)
     raise SystemExit(f"no workload {cfg}")
 
 

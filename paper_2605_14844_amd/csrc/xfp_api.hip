@@ -98,6 +98,18 @@ uint32_t rows_per_block(uint32_t N, int slots)
     return r;
 }
 
+// One token through the M = 1 kernels (the odd token left over after chunks of 16).
+hipError_t single_token(const xfp_weights *W, xfp::DecodeArgs c, int y_dtype, hipStream_t s)
+{
+    const int bits = (int)W->bits, mode = (int)W->mode;
+    const bool y_f32 = y_dtype == XFP_F32;
+    if (xfp::stream_supports(bits, mode, W->K, W->L)) return xfp::launch_decode_stream(bits, mode, y_f32, c, 1, s);
+    if (const int S = xfp::splitk_slices(bits, mode, W->N, W->K, W->L, 1))
+        return xfp::launch_decode_splitk(bits, mode, y_f32, c, 1, S, s);
+    c.rows_per_block = rows_per_block(W->N, 1);
+    return xfp::launch_decode_rows(bits, mode, y_f32, c, 1, s);
+}
+
 int decode(const xfp_weights *W, const int32_t *eids, int slots, const void *x, int64_t x_stride,
            void *y, int y_dtype, int64_t ldy, hipStream_t s)
 {
@@ -113,16 +125,22 @@ int decode(const xfp_weights *W, const int32_t *eids, int slots, const void *x, 
     a.x_stride = x_stride;
     a.y_stride = ldy;
     a.y_bf16 = y_dtype == XFP_BF16;
-    if (!eids && xfp::batch_supports((int)W->bits, (int)W->mode, W->K, slots)) {
+    if (!eids && xfp::batch_supports((int)W->bits, (int)W->mode, W->N, W->K, slots)) {
         // batched tokens: the weights are read once per 16 tokens
         const size_t ysz = y_dtype == XFP_F32 ? 4 : 2;
+        float *part = nullptr;                                  // one plane for all chunks: they run in stream order
+        if (xfp::batch_is_split(W->K)) {
+            hipError_t perr = hipSuccess;
+            part = xfp::scratch_plane(&perr);
+            if (!part) return finish(perr);
+        }
         for (int m0 = 0; m0 < slots; m0 += 16) {
             xfp::DecodeArgs c = a;
             c.x = a.x + (int64_t)m0 * x_stride;
             c.y = static_cast<char *>(y) + (size_t)m0 * (size_t)ldy * ysz;
             const int mc = slots - m0 < 16 ? slots - m0 : 16;
-            hipError_t err = mc >= 2 ? xfp::launch_decode_batch(c, mc, y_dtype == XFP_F32, s)
-                                     : xfp::launch_decode_stream((int)W->bits, (int)W->mode, y_dtype == XFP_F32, c, 1, s);
+            hipError_t err = mc >= 2 ? xfp::launch_decode_batch(c, mc, y_dtype == XFP_F32, part, s)
+                                     : single_token(W, c, y_dtype, s);
             if (err != hipSuccess) return finish(err);
         }
         return XFP_OK;

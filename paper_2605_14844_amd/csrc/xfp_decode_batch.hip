@@ -1,6 +1,8 @@
 // Small-batch fused decode (2 <= M <= 16 tokens per launch) on the matrix cores:
-// V2 codebooks, 4-bit indices, K a multiple of 128 up to 8192.  The weights are
-// read from HBM once for all tokens.
+// V2 codebooks, 4-bit indices, K a multiple of 128.  The weights are read from
+// HBM once for all tokens.  Rows of up to 8192 columns are one launch; longer
+// rows (up to 32768) are cut into slices of at most 8192 columns, grid y =
+// slice, whose fp32 partial sums a second kernel adds in slice order.
 //
 // Work unit: a workgroup of 8 waves walks tiles of 16 output rows; wave w owns
 // NL consecutive 128-weight groups of every row (its K slice), so its share of
@@ -82,7 +84,7 @@ struct BatchLds {
 };
 
 constexpr int kXtSlots = 16;               // batched calls that may overlap on one GPU
-constexpr int kXtMaxK = 8192;
+constexpr int kXtMaxK = 32768;
 // Two re-laid copies of the 16 x K activations of a call, per ring slot:
 //   xt [k][16 tokens]           the outlier products read the 16 tokens of one column as 32 bytes;
 //   xb [k / 8][16 tokens][8 k]  the B operand of lane (m, q) for a k block is 16 contiguous bytes and
@@ -181,10 +183,14 @@ struct BatchArgs {
 };
 
 // NL: groups per wave per tile (K <= NL * 8 * 128).  RAGGED: K < NL * 8 * 128,
-// some waves own groups past the end of the row.
-template <int W, int NL, bool RAGGED>
+// some waves own groups past the end of the row.  SPLIT: a.K is the length of a
+// slice of the rows (NL * 8 groups), workgroup y decodes slice y, whose last one
+// may be shorter (so SPLIT implies RAGGED), folds an equal share of each tile's
+// outlier entries and writes fp32 to its own plane y + blockIdx.y * z_stride.
+template <int W, int NL, bool RAGGED, bool SPLIT>
 __global__ __launch_bounds__(W * kWave) void decode_batch4_kernel(BatchArgs ta)
 {
+    static_assert(!SPLIT || RAGGED, "the last slice may be short");
     using L = BatchLds<W>;
     constexpr int kRed = L::kRed, kRedOne = L::kRedOne, kProd = L::kProd, kProdOne = L::kProdOne;
     constexpr int RPW = kTile / W;                         // rows a wave finishes in the epilogue (2 or 1)
@@ -198,8 +204,10 @@ __global__ __launch_bounds__(W * kWave) void decode_batch4_kernel(BatchArgs ta)
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t i = lane & 15, q = lane >> 4;           // operand layout: A row / token, k block
     const uint32_t la = lane >> 2, lb = lane & 3;          // load layout: tile row, chunk of a group
-    const uint32_t N = a.N, K = a.K, G = K / kGroup;
-    const uint32_t wpr = K / 8;                            // dwords per row (4-bit)
+    const uint32_t N = a.N, K = a.K;
+    const uint32_t zg = SPLIT ? blockIdx.y * (K / kGroup) : 0u;                    // first group of this slice
+    const uint32_t G = SPLIT ? min(K / kGroup, a.row_words / 16 - zg) : K / kGroup;  // groups of this slice
+    const uint32_t wpr = SPLIT ? a.row_words : K / 8;      // dwords per row (4-bit)
     const uint32_t ntiles = (N + kTile - 1) / kTile;
     const uint32_t tstep = gridDim.x;
     const_i32_t *rp = (const_i32_t *)(uintptr_t)a.rp;
@@ -214,7 +222,7 @@ __global__ __launch_bounds__(W * kWave) void decode_batch4_kernel(BatchArgs ta)
     uint4 iw[NL];
     auto tile_base = [&](uint32_t tile, bool on) {
         const uint32_t row = min(tile * kTile + la, N - 1);
-        return reinterpret_cast<const uint4 *>(a.idx + (on ? (size_t)row * wpr : 0) + (size_t)(g0 * 4 + lb) * 4);
+        return reinterpret_cast<const uint4 *>(a.idx + (on ? (size_t)row * wpr : 0) + (size_t)((zg + g0) * 4 + lb) * 4);
     };
     auto load_group = [&](int c, const uint4 *base) {
         const uint4 *p = RAGGED ? base + 4 * ((int32_t)min(g0 + c, G - 1) - (int32_t)g0) : base + 4 * c;
@@ -229,10 +237,21 @@ __global__ __launch_bounds__(W * kWave) void decode_batch4_kernel(BatchArgs ta)
         TileRp r;
         r.base = rp[min(n0, N)];
         r.end = rp[min(n0 + kTile, N)];
+        if constexpr (SPLIT) {
+            // every slice sees all of x, so the tile's entries are dealt to the slices by
+            // position, an equal share each, whatever their columns
+            const uint32_t cnt = (uint32_t)(r.end - r.base), S = gridDim.y, z = blockIdx.y;
+            r.end = r.base + (int32_t)(cnt * (z + 1) / S);
+            r.base += (int32_t)(cnt * z / S);
+        }
 #pragma unroll
         for (int h = 0; h < RPW; ++h) {
             r.lo[h] = rp[min(n0 + wave + W * h, N)];
             r.hi[h] = rp[min(n0 + wave + W * h + 1, N)];
+            if constexpr (SPLIT) {
+                r.lo[h] = min(max(r.lo[h], r.base), r.end);
+                r.hi[h] = min(max(r.hi[h], r.base), r.end);
+            }
         }
         return r;
     };
@@ -289,8 +308,8 @@ __global__ __launch_bounds__(W * kWave) void decode_batch4_kernel(BatchArgs ta)
     // that each XCD has all of it in its L2 after one miss latency.
     uint4 warm;
     {
-        const uint32_t kib = ((blockIdx.x >> 3) * W + wave) % (K * kTile * 2 / 1024);
-        warm = ta.xb[(size_t)kib * 64 + lane];
+        const uint32_t kib = ((blockIdx.x >> 3) * W + wave) % (G * (kGroup * kTile * 2 / 1024));
+        warm = ta.xb[(size_t)(zg * (kGroup * kTile * 2 / 1024) + kib) * 64 + lane];
     }
     load_codebook(0, t);
     // a1: B operands.  Step s = 4 c + b contracts, in k block q, piece q of chunk b
@@ -304,7 +323,7 @@ __global__ __launch_bounds__(W * kWave) void decode_batch4_kernel(BatchArgs ta)
             for (int b = 0; b < 4; ++b) {
                 const int s = 4 * c + b;
                 const uint32_t g = g0 + c;
-                const uint32_t kb = min(g, G - 1) * (kGroup / 8) + b * 4 + q;         // k block of this lane
+                const uint32_t kb = (zg + min(g, G - 1)) * (kGroup / 8) + b * 4 + q;  // k block of this lane
                 const uint4 v = ta.xb[(size_t)kb * kTile + i];
                 const bool on = !RAGGED || g < G;
                 xr[s][0] = on ? v.x : 0u; xr[s][1] = on ? v.y : 0u; xr[s][2] = on ? v.z : 0u; xr[s][3] = on ? v.w : 0u;
@@ -395,7 +414,8 @@ __global__ __launch_bounds__(W * kWave) void decode_batch4_kernel(BatchArgs ta)
             s = dpp_add<0x4E>(s);                          // quad_perm [2,3,0,1]
             if (sub == 0 && n < N && em < (uint32_t)M) {
                 const int64_t oo = (int64_t)em * a.y_stride + n;
-                store_out(a.y, oo, s, ta.y_f32 != 0, a.y_bf16 != 0);
+                if constexpr (SPLIT) static_cast<float *>(a.y)[(int64_t)blockIdx.y * a.z_stride + oo] = s;
+                else store_out(a.y, oo, s, ta.y_f32 != 0, a.y_bf16 != 0);
             }
         }
     };
@@ -527,11 +547,13 @@ int device_cus()
     return c;
 }
 
-template <int W, int NL, bool RAGGED>
+// a.K: columns of a full row.  SPLIT: slices of NL * W groups, a.y an fp32 plane
+// buffer [slices][M][N].
+template <int W, int NL, bool RAGGED, bool SPLIT = false>
 hipError_t launch_batch_t(const DecodeArgs &a, int M, bool y_f32, hipStream_t s)
 {
     constexpr int kBatchLds = BatchLds<W>::kTotal;
-    auto kern = decode_batch4_kernel<W, NL, RAGGED>;
+    auto kern = decode_batch4_kernel<W, NL, RAGGED, SPLIT>;
     static std::atomic<int> configured{0};                 // idempotent attribute, benign race
     if (!configured.load(std::memory_order_relaxed)) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -558,8 +580,17 @@ hipError_t launch_batch_t(const DecodeArgs &a, int M, bool y_f32, hipStream_t s)
     ta.xt = reinterpret_cast<const uint4 *>(xc->xt);
     ta.xb = reinterpret_cast<const uint4 *>(xc->xb);
     const uint32_t ntiles = (a.N + kTile - 1) / kTile;
-    const uint32_t cus = (uint32_t)device_cus();
-    hipLaunchKernelGGL(kern, dim3(ntiles < cus ? ntiles : cus), dim3(W * kWave), kBatchLds, s, ta);
+    uint32_t wgs = (uint32_t)device_cus(), slices = 1;
+    if constexpr (SPLIT) {
+        constexpr uint32_t GS = NL * W;                    // groups per slice
+        slices = (a.K / kGroup + GS - 1) / GS;
+        ta.a.row_words = a.K / 8;
+        ta.a.K = GS * kGroup;
+        ta.a.y_stride = a.N;
+        ta.a.z_stride = (int64_t)M * a.N;
+        wgs = wgs / slices > 0 ? wgs / slices : 1;         // one workgroup per CU over all slices
+    }
+    hipLaunchKernelGGL(kern, dim3(ntiles < wgs ? ntiles : wgs, slices), dim3(W * kWave), kBatchLds, s, ta);
     return hipGetLastError();
 }
 
@@ -594,17 +625,51 @@ hipError_t launch_batch_w(const DecodeArgs &a, int M, bool y_f32, hipStream_t s)
 
 }  // namespace
 
-bool batch_supports(int bits, int mode, uint32_t K, int M)
+// Slices of a long row: S = ceil(G / 64) of them, each ceil(G / S) groups rounded
+// up to a multiple of 8 (one group more or less per wave), the last one shorter.
+// Returns groups per wave per slice, 0 if the row is not split.
+int batch_split_nl(uint32_t K)
 {
-    return bits == 4 && mode == 0 && M >= 2 && K % kGroup == 0 && K >= kGroup && K <= 8192;
+    const uint32_t G = K / kGroup;
+    if (G <= 64) return 0;
+    const uint32_t S = (G + 63) / 64;
+    return (int)(((G + S - 1) / S + 7) / 8);
+}
+
+bool batch_supports(int bits, int mode, uint32_t N, uint32_t K, int M)
+{
+    if (!(bits == 4 && mode == 0 && M >= 2 && K % kGroup == 0 && K >= kGroup && K <= (uint32_t)kXtMaxK)) return false;
+    if (K <= 8192) return true;
+    const uint32_t GS = (uint32_t)batch_split_nl(K) * 8;
+    const uint32_t S = (K / kGroup + GS - 1) / GS;
+    return (uint64_t)S * 16u * N <= scratch_plane_floats();          // the partial planes of 16 tokens fit
 }
 
 // M <= 16 tokens per launch; the caller loops over chunks of 16.  Eight waves
 // share a tile of 16 rows: with 16 waves (128 registers each) the compiler
 // spills the in-flight index words and the kernel runs at half the speed.
-hipError_t launch_decode_batch(const DecodeArgs &a, int M, bool y_f32, hipStream_t s)
+bool batch_is_split(uint32_t K) { return batch_split_nl(K) != 0; }
+
+// part: an fp32 scratch plane for the partial sums when batch_is_split(a.K) (calls
+// on one stream may share it), unused otherwise.
+hipError_t launch_decode_batch(const DecodeArgs &a, int M, bool y_f32, float *part, hipStream_t s)
 {
-    return launch_batch_w<8>(a, M, y_f32, s);
+    const int nl = batch_split_nl(a.K);
+    if (nl == 0) return launch_batch_w<8>(a, M, y_f32, s);
+    if (!part) return hipErrorInvalidValue;
+    hipError_t err = hipSuccess;
+    DecodeArgs c = a;
+    c.y = part;
+    switch (nl) {
+    case 5: err = launch_batch_t<8, 5, true, true>(c, M, true, s); break;
+    case 6: err = launch_batch_t<8, 6, true, true>(c, M, true, s); break;
+    case 7: err = launch_batch_t<8, 7, true, true>(c, M, true, s); break;
+    case 8: err = launch_batch_t<8, 8, true, true>(c, M, true, s); break;
+    default: return hipErrorInvalidValue;
+    }
+    if (err != hipSuccess) return err;
+    const uint32_t slices = (a.K / kGroup + (uint32_t)nl * 8 - 1) / ((uint32_t)nl * 8);
+    return launch_splitk_sum(part, slices, a.N, M, a.y, a.y_stride, y_f32, a.y_bf16 != 0, s);
 }
 
 }  // namespace xfp

@@ -95,8 +95,14 @@ hipError_t launch_decode_splitk(int bits, int mode, bool y_f32, const DecodeArgs
     c.z_stride = (int64_t)slots * a.N;
     hipError_t err = launch_decode_stream(bits, mode, true, c, slots, s);
     if (err != hipSuccess) return err;
-    hipLaunchKernelGGL(splitk_sum_kernel, dim3((a.N + 255) / 256, slots), dim3(256), 0, s, part, (uint32_t)slices, a.N,
-                       (uint32_t)slots, a.y, a.y_stride, (int)y_f32, (int)a.y_bf16);
+    return launch_splitk_sum(part, (uint32_t)slices, a.N, slots, a.y, a.y_stride, y_f32, a.y_bf16 != 0, s);
+}
+
+hipError_t launch_splitk_sum(const float *part, uint32_t slices, uint32_t N, int slots, void *y, int64_t y_stride,
+                             bool y_f32, bool y_bf16, hipStream_t s)
+{
+    hipLaunchKernelGGL(splitk_sum_kernel, dim3((N + 255) / 256, slots), dim3(256), 0, s, part, slices, N,
+                       (uint32_t)slots, y, y_stride, (int)y_f32, (int)y_bf16);
     return hipGetLastError();
 }
 

@@ -191,6 +191,25 @@ def test_batched_matches_oracle_and_single_calls(mode, bits, N, K, M):
         assert gated_rel_err(yb[m], y1[0]) <= TOL_F32
 
 
+# batched tokens on rows above 8192 columns: the matrix-core kernel in slices of K (equal, or the
+# last one short: 8320 = 40 + 25 groups, 11008 = 48 + 38, 27648 = 4 x 56 - 8), M = 17 and 33 leave
+# one token for the M = 1 kernels
+@pytest.mark.parametrize("N,K,M,dens", [(200, 16384, 16, 0.003), (90, 8320, 5, 0.003), (70, 11008, 16, 0.003),
+                                        (64, 28672, 16, 0.003), (50, 27648, 9, 0.0), (33, 32768, 2, 0.01),
+                                        (40, 20480, 17, 0.003), (24, 12288, 33, 0.003), (600, 14336, 16, 0.003)])
+def test_batched_long_rows_in_slices(N, K, M, dens):
+    W = xi.random_weights(V2, 4, N, K, density=dens, seed=N + M)
+    x = xi.activations(np.random.default_rng(K + M), M, K)
+    dW, xd, ref = check_gemv(W, x)
+    yb = host(xfp.xfp_gemv(dW, xd, y_dtype=torch.float32))
+    y1 = host(xfp.xfp_gemv(dW, xd[M - 1:M].contiguous(), y_dtype=torch.float32))
+    assert gated_rel_err(yb[M - 1], y1[0]) <= TOL_F32
+    xb = xd.to(torch.bfloat16)                                       # bf16 in and out through the same path
+    refb = oracle.gemv_weights(W, xb.to(torch.float16).cpu().numpy().view(np.uint16))
+    yb16 = xfp.xfp_gemv(dW, xb, y_dtype=torch.bfloat16)
+    assert gated_rel_err(host(yb16), refb) <= TOL_BF16
+
+
 def test_batched_with_more_outliers_than_a_tile_keeps_on_chip():
     """5 % outliers: a 16-row tile of K = 4096 holds about 3300 entries, far past the on-chip product
     buffer, and one row alone holds every entry of its tile."""
