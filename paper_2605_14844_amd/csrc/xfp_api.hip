@@ -139,7 +139,7 @@ int decode(const xfp_weights *W, const int32_t *eids, int slots, const void *x, 
             c.x = a.x + (int64_t)m0 * x_stride;
             c.y = static_cast<char *>(y) + (size_t)m0 * (size_t)ldy * ysz;
             const int mc = slots - m0 < 16 ? slots - m0 : 16;
-            hipError_t err = mc >= 2 ? xfp::launch_decode_batch(c, mc, y_dtype == XFP_F32, part, s)
+            hipError_t err = mc >= 2 ? xfp::launch_decode_batch((int)W->bits, c, mc, y_dtype == XFP_F32, part, s)
                                      : single_token(W, c, y_dtype, s);
             if (err != hipSuccess) return finish(err);
         }
