@@ -5,8 +5,10 @@
 
 namespace xfp {
 
-// defined in xfp_decode_batch3.hip
+// defined in xfp_decode_batch3.hip, xfp_decode_batch2.hip
 hipError_t launch_batch3(const DecodeArgs &a, int M, bool y_f32, float *part, const void *xt, const void *xb,
+                         hipStream_t s);
+hipError_t launch_batch2(const DecodeArgs &a, int M, bool y_f32, float *part, const void *xt, const void *xb,
                          hipStream_t s);
 
 namespace {
@@ -57,7 +59,7 @@ __global__ __launch_bounds__(256) void relayout_x_kernel(const uint16_t *x, int6
 
 bool batch_supports(int bits, int mode, uint32_t N, uint32_t K, int M)
 {
-    if (!((bits == 4 || bits == 3) && mode == 0 && M >= 2 && K % kGroup == 0 && K >= kGroup && K <= (uint32_t)kXtMaxK))
+    if (!(bits >= 2 && bits <= 4 && mode == 0 && M >= 2 && K % kGroup == 0 && K >= kGroup && K <= (uint32_t)kXtMaxK))
         return false;
     if (K <= 8192) return true;
     const uint32_t GS = (uint32_t)batch_split_nl(K) * 8;
@@ -84,7 +86,8 @@ hipError_t launch_decode_batch(int bits, const DecodeArgs &a, int M, bool y_f32,
                        a.x_stride, M, a.K, xs);
     const XCopies *xc = static_cast<const XCopies *>(p) + xs;
     if (bits == 4) return launch_batch_bits<4>(a, M, y_f32, part, xc->xt, xc->xb, s);
-    return launch_batch3(a, M, y_f32, part, xc->xt, xc->xb, s);
+    if (bits == 3) return launch_batch3(a, M, y_f32, part, xc->xt, xc->xb, s);
+    return launch_batch2(a, M, y_f32, part, xc->xt, xc->xb, s);
 }
 
 }  // namespace xfp

@@ -1,7 +1,7 @@
 // Small-batch fused decode (2 <= M <= 16 tokens per launch) on the matrix cores:
-// V2 codebooks, 4-bit or 3-bit indices, K a multiple of 128.  The weights are
+// V2 codebooks, 4-, 3- or 2-bit indices, K a multiple of 128.  The weights are
 // read from HBM once for all tokens.  (Kernel template; instantiated per bit
-// width in xfp_decode_batch.hip and xfp_decode_batch3.hip.)  Rows of up to 8192 columns are one launch; longer
+// width in xfp_decode_batch.hip, xfp_decode_batch3.hip and xfp_decode_batch2.hip.)  Rows of up to 8192 columns are one launch; longer
 // rows (up to 32768) are cut into slices of at most 8192 columns, grid y =
 // slice, whose fp32 partial sums a second kernel adds in slice order.
 //
@@ -16,10 +16,11 @@
 // Index stream.  Adjacent lanes of the A operand are different ROWS, which is
 // the worst case for a load (64 lanes, 64 cache lines).  So the loads use
 // another mapping: lane l reads row l / 4 of the tile, chunk l % 4 (32 weights:
-// 16 bytes at 4 bits, 12 at 3) of a group, i.e. every quad of lanes reads 64 (48)
-// contiguous bytes, every byte of the stream exactly once.  What a lane got is
-// four pieces d of 8 weights each (a dword at 4 bits; at 3 bits the 96 bits are
-// first cut into four 24-bit pieces with three funnel shifts), which are then
+// 16 bytes at 4 bits, 12 at 3, 8 at 2) of a group, i.e. every quad of lanes reads
+// 64 (48, 32) contiguous bytes, every byte of the stream exactly once.  What a
+// lane got is four pieces d of 8 weights each (a dword at 4 bits; at 3 bits the
+// 96 bits are first cut into four 24-bit pieces with three funnel shifts, at 2
+// bits the two dwords into halves), which are then
 // transposed IN REGISTERS to the operand layout by
 // exchanging lane-index bits with register-index bits:
 //     v_permlane32_swap, v_permlane16_swap   lane bits 5, 4  <->  register bits 1, 0
@@ -33,13 +34,13 @@
 // as they are transposed, so one tile of index words is always in flight.
 //
 // Dequantisation is one LDS lookup per PAIR of weights: a per-row table maps an
-// index pair (a byte at 4 bits, 6 bits at 3) to two fp16 values, the packed form
+// index pair (a byte at 4 bits, 6 bits at 3, 4 at 2) to two fp16 values, the packed form
 // the A operand wants.  Entry e of slot s lives at byte e*256 + s*4; slot =
 // buffer*32 + i + 16*(q & 1), i.e. every row's table is stored twice so that
 // the 32 lanes the LDS serves per clock hit 32 different banks, and the tables
 // of the next tile are built (other buffer) while this one is decoded.  A
 // lookup address is ONE v_perm_b32 at 4 bits (index byte -> address byte 1), a
-// bit-field extract and a shift-or at 3 bits.
+// bit-field extract and a shift-or at 3 and 2 bits.
 //
 // Per tile, the 8 partial D blocks meet in LDS and are summed in a fixed order
 // (deterministic, no atomics) by 256 threads, which also add the CSR outlier
@@ -83,7 +84,7 @@ struct BatchLds {
     static constexpr int kProdOne = (kProdCap + kProdPad) * 16 * 4;
     static constexpr int kRed = kTabBytes;
     static constexpr int kProd = kRed + 2 * kRedOne;
-    static constexpr int kTotal = kProd + 2 * kProdOne;               // 140 KB at 4 bits, 92 KB at 3 (W = 8)
+    static constexpr int kTotal = kProd + 2 * kProdOne;               // 140 KB at 4 bits, 92 KB at 3, 80 KB at 2 (W = 8)
 };
 
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits
@@ -152,7 +153,7 @@ struct BatchArgs {
 template <int BITS, int W, int NL, bool RAGGED, bool SPLIT>
 __global__ __launch_bounds__(W * kWave) void decode_batch_kernel(BatchArgs ta)
 {
-    static_assert(BITS == 3 || BITS == 4, "pair tables of 64 or 256 entries");
+    static_assert(BITS >= 2 && BITS <= 4, "pair tables of 16, 64 or 256 entries");
     static_assert(!SPLIT || RAGGED, "the last slice may be short");
     using L = BatchLds<BITS, W>;
     constexpr int CW = BITS;                               // dwords of a lane's chunk of 32 weights
@@ -238,7 +239,8 @@ __global__ __launch_bounds__(W * kWave) void decode_batch_kernel(BatchArgs ta)
     //   4 bits: the 16 entries whose first index is 4 ra + u and second index
     //           4 rb + v (u, v = 0..3): 4 + 4 codebook values, two 8-byte loads;
     //   3 bits: the 4 entries whose first index is 4 (ra & 1) + u and second index
-    //           2 rb + ra / 2: 4 + 1 codebook values (cbh.x holds the one, low half).
+    //           2 rb + ra / 2: 4 + 1 codebook values (cbh.x holds the one, low half);
+    //   2 bits: the entry (first index ra, second index rb): cbl.x and cbh.x, low halves.
     static_assert(W == 8, "32 slots x 16 builder roles = 512 threads");
     constexpr int NB = (1 << (2 * BITS)) / 16;             // table entries a thread writes per tile
     const uint32_t tb_slot = tid & 31, tb_ra = (tid >> 5) & 3, tb_rb = tid >> 7;
@@ -250,10 +252,13 @@ __global__ __launch_bounds__(W * kWave) void decode_batch_kernel(BatchArgs ta)
         if constexpr (BITS == 4) {
             cbl[set] = *reinterpret_cast<const uint2 *>(p + 4 * tb_ra);
             cbh[set] = *reinterpret_cast<const uint2 *>(p + 4 * tb_rb);
-        } else {
+        } else if constexpr (BITS == 3) {
             cbl[set] = *reinterpret_cast<const uint2 *>(p + 4 * (tb_ra & 1));
             cbh[set].x = p[tb_i1];
             cbh[set].y = 0u;
+        } else {
+            cbl[set] = make_uint2(p[tb_ra], 0u);
+            cbh[set] = make_uint2(p[tb_rb], 0u);
         }
     };
     auto build_step = [&](uint32_t buf, int set, int j) {
@@ -264,11 +269,14 @@ __global__ __launch_bounds__(W * kWave) void decode_batch_kernel(BatchArgs ta)
             const uint32_t lo = (u & 1) ? lw >> 16 : lw & 0xFFFFu;
             const uint32_t hi = (v & 1) ? hw & 0xFFFF0000u : hw << 16;
             *(lds_u32_t *)(uintptr_t)(base + (u + 16 * v) * 256) = lo | hi;
-        } else {                                           // j = u
+        } else if constexpr (BITS == 3) {                  // j = u
             const uint32_t base = lds0 + (4 * (tb_ra & 1) + 8 * tb_i1) * 256 + (buf * 32 + tb_slot) * 4;
             const uint32_t lw = j < 2 ? cbl[set].x : cbl[set].y;
             const uint32_t lo = (j & 1) ? lw >> 16 : lw & 0xFFFFu;
             *(lds_u32_t *)(uintptr_t)(base + j * 256) = lo | (cbh[set].x << 16);
+        } else {
+            const uint32_t base = lds0 + (tb_ra + 4 * tb_rb) * 256 + (buf * 32 + tb_slot) * 4;
+            *(lds_u32_t *)(uintptr_t)base = cbl[set].x | (cbh[set].x << 16);
         }
     };
 
@@ -425,11 +433,13 @@ __global__ __launch_bounds__(W * kWave) void decode_batch_kernel(BatchArgs ta)
             uint32_t (&v)[4] = pw[c & 1];
             if constexpr (BITS == 4) {
                 v[0] = iw[c][0]; v[1] = iw[c][1]; v[2] = iw[c][2]; v[3] = iw[c][3];
-            } else {                                       // piece d = bits [24 d, 24 d + 24) of the 96; bits above 24 are ignored
+            } else if constexpr (BITS == 3) {              // piece d = bits [24 d, 24 d + 24) of the 96; bits above 24 are ignored
                 v[0] = iw[c][0];
                 v[1] = __builtin_amdgcn_alignbit(iw[c][1], iw[c][0], 24);
                 v[2] = __builtin_amdgcn_alignbit(iw[c][2], iw[c][1], 16);
                 v[3] = iw[c][2] >> 8;
+            } else {                                       // piece d = 16 bits; bits above 16 are ignored
+                v[0] = iw[c][0]; v[1] = iw[c][0] >> 16; v[2] = iw[c][1]; v[3] = iw[c][1] >> 16;
             }
             to_operand_layout(v);
             load_group(c, nbase);                          // the registers are free: next tile's words
@@ -444,7 +454,7 @@ __global__ __launch_bounds__(W * kWave) void decode_batch_kernel(BatchArgs ta)
             } else {
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    v[j] = *(lds_cu32_t *)(uintptr_t)((((w >> (6 * j)) & 63u) << 8) | sel);
+                    v[j] = *(lds_cu32_t *)(uintptr_t)((((w >> (2 * BITS * j)) & ((1u << (2 * BITS)) - 1u)) << 8) | sel);
             }
         };
         // a7: outlier products of the first kProdCap entries -> LDS

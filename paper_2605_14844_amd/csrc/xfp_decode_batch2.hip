@@ -1,0 +1,12 @@
+// 2-bit instantiation of the small-batch matrix-core kernel.
+#include "xfp_decode_batch.inc.h"
+
+namespace xfp {
+
+hipError_t launch_batch2(const DecodeArgs &a, int M, bool y_f32, float *part, const void *xt, const void *xb,
+                         hipStream_t s)
+{
+    return launch_batch_bits<2>(a, M, y_f32, part, xt, xb, s);
+}
+
+}  // namespace xfp

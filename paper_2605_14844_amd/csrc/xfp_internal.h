@@ -54,7 +54,7 @@ hipError_t launch_decode_splitk(int bits, int mode, bool y_f32, const DecodeArgs
 // y[slot][n] = sum over slices z, in order, of part[z][slot][n]
 hipError_t launch_splitk_sum(const float *part, uint32_t slices, uint32_t N, int slots, void *y, int64_t y_stride,
                              bool y_f32, bool y_bf16, hipStream_t s);
-// Matrix-core kernel for 2..16 tokens per launch (V2, 4- or 3-bit, K <= 32768; rows
+// Matrix-core kernel for 2..16 tokens per launch (V2, 2..4-bit, K <= 32768; rows
 // above 8192 columns in slices whose partial sums go through a scratch plane).
 bool batch_supports(int bits, int mode, uint32_t N, uint32_t K, int M);
 bool batch_is_split(uint32_t K);

@@ -210,14 +210,15 @@ def test_batched_long_rows_in_slices(N, K, M, dens):
     assert gated_rel_err(host(yb16), refb) <= TOL_BF16
 
 
-# 3-bit rows through the matrix-core kernel: every count of groups per wave (1..8), ragged, long rows in slices
+# 3-bit and 2-bit rows through the matrix-core kernel: every count of groups per wave (1..8), ragged, long rows in slices
 @pytest.mark.parametrize("N,K,M,dens", [(200, 8192, 16, 0.003), (77, 1024, 5, 0.003), (64, 4096, 16, 0.003),
                                         (33, 128, 2, 0.01), (90, 1408, 16, 0.003), (50, 5120, 7, 0.0),
                                         (35, 7296, 3, 0.003), (41, 3072, 16, 0.003), (40, 6144, 9, 0.003),
                                         (40, 2048, 33, 0.003), (4500, 256, 16, 0.003), (70, 11008, 16, 0.003),
                                         (64, 28672, 16, 0.003), (24, 12288, 17, 0.003), (80, 4096, 16, 0.05)])
-def test_batched_3bit_matches_oracle_and_single_calls(N, K, M, dens):
-    W = xi.random_weights(V2, 3, N, K, density=dens, seed=3 * N + M)
+@pytest.mark.parametrize("bits", [3, 2])
+def test_batched_3bit_2bit_matches_oracle_and_single_calls(bits, N, K, M, dens):
+    W = xi.random_weights(V2, bits, N, K, density=dens, seed=3 * N + M)
     x = xi.activations(np.random.default_rng(K + 3 * M), M, K)
     dW, xd, ref = check_gemv(W, x)
     yb = host(xfp.xfp_gemv(dW, xd, y_dtype=torch.float32))
