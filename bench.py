@@ -35,7 +35,7 @@ def parse_args():
     p.add_argument("--config", type=int, default=2,
                    help="workload 1..5 (default 2, the headline); beyond the five: 6 = workload 4 as a whole expert "
                         "layer with both epilogues fused, 7 = a long-row matrix (8192x28672, 4-bit, M=1) through split-K, "
-                        "8 = the same matrix with 16 tokens, 9 = workload 5's shape at 3 bits")
+                        "8 = the same matrix with 16 tokens, 9 = workload 5's shape at 3 bits, 10 = the same as V2a")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-graph", action="store_true", help="time eager launches instead of a graph")
     p.add_argument("--no-plain-read", action="store_true", help="skip the read-only ceiling measurement")
@@ -174,11 +174,13 @@ def build_workload(cfg: int, ring_bytes: int):
         return dict(name="V2 8192x28672 b4 M=1 (rows longer than 16384: split-K, two launches)", step=step,
                     bytes=nbytes, ring=R, oracle=oracle_once, launches=2, kernel_bytes=nbytes,
                     launch_bytes=[nbytes], keep=(ring, xd, y), M=1, N=W.N, K=W.K, bits=4, mode=0)
-    if cfg in (8, 9):
+    if cfg in (8, 9, 10):
         if cfg == 8:
             W = xi.random_weights(xi.MODE_V2, 4, 8192, 28672, density=0.003, seed=xi.BASE_SEED + 7)
-        else:
+        elif cfg == 9:
             W = xi.random_weights(xi.MODE_V2, 3, 28672, 8192, density=0.003, seed=xi.BASE_SEED + 9)
+        else:
+            W = xi.random_weights(xi.MODE_V2A, 3, 28672, 8192, L=32, density=0.003, seed=xi.BASE_SEED + 10)
         xb = xi.activations(np.random.default_rng(xi.BASE_SEED + 400 + cfg), 16, W.K)
         nbytes = W.algorithmic_bytes(M=16)
         R = max(1, min(512, -(-ring_bytes // nbytes)))
@@ -195,11 +197,12 @@ def build_workload(cfg: int, ring_bytes: int):
             import oracle
             return oracle.gemv_weights(W, xb, threads)
 
-        name = ("V2 8192x28672 b4 M=16 (matrix-core kernel over four slices of K, three launches)" if cfg == 8 else
-                "V2 28672x8192 b3 M=16 (workload 5's shape at 3 bits, two launches)")
+        name = {8: "V2 8192x28672 b4 M=16 (matrix-core kernel over four slices of K, three launches)",
+                9: "V2 28672x8192 b3 M=16 (workload 5's shape at 3 bits, two launches)",
+                10: "V2a 28672x8192 b3 L=32 M=16 (workload 5's shape in workload 3's format, two launches)"}[cfg]
         return dict(name=name, step=step, bytes=nbytes, ring=R, oracle=oracle_once, launches=3 if cfg == 8 else 2,
                     kernel_bytes=nbytes, launch_bytes=[nbytes], keep=(ring, xd, y), M=16, N=W.N, K=W.K, bits=W.bits,
-                    mode=0)
+                    mode=W.mode)
     raise SystemExit(f"no workload {cfg}")
 
 

@@ -125,7 +125,7 @@ int decode(const xfp_weights *W, const int32_t *eids, int slots, const void *x, 
     a.x_stride = x_stride;
     a.y_stride = ldy;
     a.y_bf16 = y_dtype == XFP_BF16;
-    if (!eids && xfp::batch_supports((int)W->bits, (int)W->mode, W->N, W->K, slots)) {
+    if (!eids && xfp::batch_supports((int)W->bits, (int)W->mode, W->L, W->N, W->K, slots)) {
         // batched tokens: the weights are read once per 16 tokens
         const size_t ysz = y_dtype == XFP_F32 ? 4 : 2;
         float *part = nullptr;                                  // one plane for all chunks: they run in stream order
@@ -139,7 +139,7 @@ int decode(const xfp_weights *W, const int32_t *eids, int slots, const void *x, 
             c.x = a.x + (int64_t)m0 * x_stride;
             c.y = static_cast<char *>(y) + (size_t)m0 * (size_t)ldy * ysz;
             const int mc = slots - m0 < 16 ? slots - m0 : 16;
-            hipError_t err = mc >= 2 ? xfp::launch_decode_batch((int)W->bits, c, mc, y_dtype == XFP_F32, part, s)
+            hipError_t err = mc >= 2 ? xfp::launch_decode_batch((int)W->bits, (int)W->mode, c, mc, y_dtype == XFP_F32, part, s)
                                      : single_token(W, c, y_dtype, s);
             if (err != hipSuccess) return finish(err);
         }

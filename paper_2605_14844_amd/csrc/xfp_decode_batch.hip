@@ -10,6 +10,11 @@ hipError_t launch_batch3(const DecodeArgs &a, int M, bool y_f32, float *part, co
                          hipStream_t s);
 hipError_t launch_batch2(const DecodeArgs &a, int M, bool y_f32, float *part, const void *xt, const void *xb,
                          hipStream_t s);
+// defined in xfp_decode_batch_lib3.hip, xfp_decode_batch_lib4.hip
+hipError_t launch_batch_lib3(const DecodeArgs &a, int M, bool y_f32, float *part, const void *xt, const void *xb,
+                             hipStream_t s);
+hipError_t launch_batch_lib4(const DecodeArgs &a, int M, bool y_f32, float *part, const void *xt, const void *xb,
+                             hipStream_t s);
 
 namespace {
 
@@ -57,9 +62,12 @@ __global__ __launch_bounds__(256) void relayout_x_kernel(const uint16_t *x, int6
 
 }  // namespace
 
-bool batch_supports(int bits, int mode, uint32_t N, uint32_t K, int M)
+// V2 at every bit width; V2a at 3 and 4 bits when the library's pair tables fit the 64 KB table region.
+bool batch_supports(int bits, int mode, uint32_t L, uint32_t N, uint32_t K, int M)
 {
-    if (!(bits >= 2 && bits <= 4 && mode == 0 && M >= 2 && K % kGroup == 0 && K >= kGroup && K <= (uint32_t)kXtMaxK))
+    const bool format = mode == 0 ? bits >= 2 && bits <= 4
+                                  : mode == 1 && (bits == 3 || bits == 4) && L >= 1 && ((size_t)L << (2 * bits)) * 4 <= 64 * 1024;
+    if (!(format && M >= 2 && K % kGroup == 0 && K >= kGroup && K <= (uint32_t)kXtMaxK))
         return false;
     if (K <= 8192) return true;
     const uint32_t GS = (uint32_t)batch_split_nl(K) * 8;
@@ -71,7 +79,7 @@ bool batch_is_split(uint32_t K) { return batch_split_nl(K) != 0; }
 
 // M <= 16 tokens per launch; the caller loops over chunks of 16.  part: an fp32
 // scratch plane when batch_is_split(a.K) (calls on one stream may share it).
-hipError_t launch_decode_batch(int bits, const DecodeArgs &a, int M, bool y_f32, float *part, hipStream_t s)
+hipError_t launch_decode_batch(int bits, int mode, const DecodeArgs &a, int M, bool y_f32, float *part, hipStream_t s)
 {
     static std::atomic<void *> ring{nullptr};              // device address of g_x (one GPU per process)
     void *p = ring.load(std::memory_order_relaxed);
@@ -85,6 +93,10 @@ hipError_t launch_decode_batch(int bits, const DecodeArgs &a, int M, bool y_f32,
     hipLaunchKernelGGL(relayout_x_kernel, dim3((a.K + 255) / 256 + (a.K * 2 + 255) / 256), dim3(256), 0, s, a.x,
                        a.x_stride, M, a.K, xs);
     const XCopies *xc = static_cast<const XCopies *>(p) + xs;
+    if (mode == 1) {
+        if (bits == 4) return launch_batch_lib4(a, M, y_f32, part, xc->xt, xc->xb, s);
+        return launch_batch_lib3(a, M, y_f32, part, xc->xt, xc->xb, s);
+    }
     if (bits == 4) return launch_batch_bits<4>(a, M, y_f32, part, xc->xt, xc->xb, s);
     if (bits == 3) return launch_batch3(a, M, y_f32, part, xc->xt, xc->xb, s);
     return launch_batch2(a, M, y_f32, part, xc->xt, xc->xb, s);

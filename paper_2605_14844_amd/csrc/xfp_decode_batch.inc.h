@@ -42,6 +42,13 @@
 // lookup address is ONE v_perm_b32 at 4 bits (index byte -> address byte 1), a
 // bit-field extract and a shift-or at 3 and 2 bits.
 //
+// V2a (MODE 1): a group's codebook is the library entry its id names, so the
+// tables are per library entry, not per row: L pair tables (entry e of library
+// entry l at byte (l * entries + e) * 4) are built once per workgroup, and every
+// lane carries the table base of its row's current group (ids of the next tile
+// are requested as those of this one are consumed).  Lookups of the 64 lanes
+// then fall on banks at random, as in the streaming kernel.
+//
 // Per tile, the 8 partial D blocks meet in LDS and are summed in a fixed order
 // (deterministic, no atomics) by 256 threads, which also add the CSR outlier
 // products of the tile.  One thread per outlier entry computes its 16
@@ -77,9 +84,10 @@ constexpr int kRd = 8;                     // product reads per lane issued unco
 static_assert(4 * kRd <= kProdPad, "unmasked reads stay inside the buffer");
 
 // W waves per workgroup, each owning 1/W of K.
-template <int BITS, int W>
+template <int BITS, int MODE, int W>
 struct BatchLds {
-    static constexpr int kTabBytes = (1 << (2 * BITS)) * 256;         // [pair entries][2 buffers x 32 slots] dwords
+    // V2: [pair entries][2 buffers x 32 slots] dwords; V2a: [L][pair entries] dwords, at most 64 KB
+    static constexpr int kTabBytes = MODE == 1 ? 64 * 1024 : (1 << (2 * BITS)) * 256;
     static constexpr int kRedOne = W * 256 * 4;                       // partial D blocks of a tile
     static constexpr int kProdOne = (kProdCap + kProdPad) * 16 * 4;
     static constexpr int kRed = kTabBytes;
@@ -150,12 +158,14 @@ struct BatchArgs {
 // slice of the rows (NL * 8 groups), workgroup y decodes slice y, whose last one
 // may be shorter (so SPLIT implies RAGGED), folds an equal share of each tile's
 // outlier entries and writes fp32 to its own plane y + blockIdx.y * z_stride.
-template <int BITS, int W, int NL, bool RAGGED, bool SPLIT>
+template <int BITS, int MODE, int W, int NL, bool RAGGED, bool SPLIT>
 __global__ __launch_bounds__(W * kWave) void decode_batch_kernel(BatchArgs ta)
 {
+    static_assert(MODE == 0 || MODE == 1, "V2 or V2a");
+    constexpr uint32_t ENT = 1u << (2 * BITS);             // entries of a pair table
     static_assert(BITS >= 2 && BITS <= 4, "pair tables of 16, 64 or 256 entries");
     static_assert(!SPLIT || RAGGED, "the last slice may be short");
-    using L = BatchLds<BITS, W>;
+    using L = BatchLds<BITS, MODE, W>;
     constexpr int CW = BITS;                               // dwords of a lane's chunk of 32 weights
     constexpr int kRed = L::kRed, kRedOne = L::kRedOne, kProd = L::kProd, kProdOne = L::kProdOne;
     constexpr int RPW = kTile / W;                         // rows a wave finishes in the epilogue (2 or 1)
@@ -173,6 +183,7 @@ __global__ __launch_bounds__(W * kWave) void decode_batch_kernel(BatchArgs ta)
     const uint32_t zg = SPLIT ? blockIdx.y * (K / kGroup) : 0u;                    // first group of this slice
     const uint32_t G = SPLIT ? min(K / kGroup, a.row_words / (4 * CW) - zg) : K / kGroup;  // groups of this slice
     const uint32_t wpr = SPLIT ? a.row_words : K / 32 * CW;    // dwords per row
+    const uint32_t Gtot = wpr / (4 * CW);                  // groups of a full row
     const uint32_t ntiles = (N + kTile - 1) / kTile;
     const uint32_t tstep = gridDim.x;
     const_i32_t *rp = (const_i32_t *)(uintptr_t)a.rp;
@@ -231,6 +242,15 @@ __global__ __launch_bounds__(W * kWave) void decode_batch_kernel(BatchArgs ta)
     auto load_val = [&](const TileRp &r, uint32_t &val) {
         __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc((void *)(a.val + r.base), 0, (r.end - r.base) * 2, 0x00020000);
         val = __builtin_amdgcn_raw_buffer_load_b16(rv, tid * 2, 0, 0);
+    };
+    // V2a: library ids of the groups g0 .. g0 + NL of this lane's operand row.
+    uint32_t gidr[NL];
+    auto gid_base = [&](uint32_t tile, bool on) {
+        const uint32_t row = min(tile * kTile + 4 * (i & 3) + (i >> 2), N - 1);
+        return a.gid + (on ? (size_t)row * Gtot : 0) + zg + g0;
+    };
+    auto load_gid = [&](int c, const uint8_t *base) {
+        gidr[c] = base[RAGGED ? (int32_t)min(g0 + c, G - 1) - (int32_t)g0 : c];
     };
     // Table builder role of this thread: slot tid % 32 (operand row i = slot % 16,
     // i.e. tile row pi(i)) and role tid / 32 = 4 rb + ra.  Two register sets of
@@ -301,7 +321,7 @@ __global__ __launch_bounds__(W * kWave) void decode_batch_kernel(BatchArgs ta)
         const uint32_t kib = ((blockIdx.x >> 3) * W + wave) % (G * (kGroup * kTile * 2 / 1024));
         warm = ta.xb[(size_t)(zg * (kGroup * kTile * 2 / 1024) + kib) * 64 + lane];
     }
-    load_codebook(0, t);
+    if constexpr (MODE == 0) load_codebook(0, t);
     // a1: B operands.  Step s = 4 c + b contracts, in k block q, piece q of chunk b
     // of group g0 + c.
     uint32_t xr[NS][4];
@@ -321,11 +341,27 @@ __global__ __launch_bounds__(W * kWave) void decode_batch_kernel(BatchArgs ta)
             load_group(c, b0);
         }
     }
+    if constexpr (MODE == 1) {
+        const uint8_t *gb0 = gid_base(t, true);
+#pragma unroll
+        for (int c = 0; c < NL; ++c) load_gid(c, gb0);
+    }
     asm volatile("" :: "v"(warm.x), "v"(warm.y), "v"(warm.z), "v"(warm.w));
     // a2: tables of the first tile.
+    if constexpr (MODE == 0) {
 #pragma unroll
-    for (int j = 0; j < NB; ++j) build_step(0, 0, j);
-    load_codebook(1, have1 ? t + tstep : t);
+        for (int j = 0; j < NB; ++j) build_step(0, 0, j);
+        load_codebook(1, have1 ? t + tstep : t);
+    } else {
+        // the library's pair tables, once: entry e = (second index, first index) of library entry l
+        const uint32_t total = a.L * ENT;
+#pragma unroll 4
+        for (uint32_t e = tid; e < total; e += W * kWave) {
+            const uint16_t *cbk = a.cb + (size_t)(e / ENT) * (1u << BITS);
+            const uint32_t lo = cbk[e & ((1u << BITS) - 1u)], hi = cbk[(e % ENT) >> BITS];
+            *(lds_u32_t *)(uintptr_t)(lds0 + e * 4) = lo | (hi << 16);
+        }
+    }
     uint32_t ocol = 0, oval = 0;
     load_col(rp_c, ocol);
     load_val(rp_c, oval);
@@ -421,11 +457,13 @@ __global__ __launch_bounds__(W * kWave) void decode_batch_kernel(BatchArgs ta)
         const bool have_next = t1 < ntiles, have2 = t2 < ntiles;
         const TileRp rp_f = load_rp(have2 ? t2 : tile);    // two tiles ahead (scalar cache)
         const uint32_t *nbase = tile_base(t1, have_next);
+        const uint8_t *ngid = MODE == 1 ? gid_base(t1, have_next) : nullptr;
 
         // ---- a3-a6: transpose, depack, pair lookup, MFMA; lookups run two steps ahead ----
         float4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
         const uint32_t sel = bank4 + P * 128;
         uint32_t pw[2][4];                                 // transposed pieces of the current and the next group
+        uint32_t gtab[2];                                  // V2a: table base of the current and the next group
         constexpr int LA = 2;                              // steps the lookups run ahead of the MFMAs
         static_assert(LA >= 1 && LA <= 3, "a group is transposed while the previous one is still being looked up");
         uint32_t av[LA + 1][4];
@@ -443,10 +481,19 @@ __global__ __launch_bounds__(W * kWave) void decode_batch_kernel(BatchArgs ta)
             }
             to_operand_layout(v);
             load_group(c, nbase);                          // the registers are free: next tile's words
+            if constexpr (MODE == 1) {
+                gtab[c & 1] = gidr[c] * (ENT * 4);
+                load_gid(c, ngid);
+            }
         };
         auto lookup = [&](int s, uint32_t (&v)[4]) {
             const uint32_t w = pw[(s / 4) & 1][s & 3];
-            if constexpr (BITS == 4) {
+            if constexpr (MODE == 1) {
+                const uint32_t gb = gtab[(s / 4) & 1];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    v[j] = *(lds_cu32_t *)(uintptr_t)((((w >> (2 * BITS * j)) & (ENT - 1u)) << 2) | gb);
+            } else if constexpr (BITS == 4) {
                 v[0] = *(lds_cu32_t *)(uintptr_t)__builtin_amdgcn_perm(w, sel, 0x0c0c0400u);
                 v[1] = *(lds_cu32_t *)(uintptr_t)__builtin_amdgcn_perm(w, sel, 0x0c0c0500u);
                 v[2] = *(lds_cu32_t *)(uintptr_t)__builtin_amdgcn_perm(w, sel, 0x0c0c0600u);
@@ -493,9 +540,9 @@ __global__ __launch_bounds__(W * kWave) void decode_batch_kernel(BatchArgs ta)
             }
             if (s == AHEAD_STEP) {
                 load_col(rp_n, ocol);                      // next tile's columns
-                load_codebook(P, have2 ? t2 : tile);       // two tiles ahead: this parity's registers are free
+                if constexpr (MODE == 0) load_codebook(P, have2 ? t2 : tile);   // two tiles ahead: this parity's registers are free
             }
-            if (s >= BUILD_FROM && s < BUILD_FROM + BUILD_STEPS) {
+            if (MODE == 0 && s >= BUILD_FROM && s < BUILD_FROM + BUILD_STEPS) {
 #pragma unroll
                 for (int j = (s - BUILD_FROM) * BPS; j < (s - BUILD_FROM + 1) * BPS && j < NB; ++j) build_step(P ^ 1, P ^ 1, j);
             }
@@ -565,11 +612,11 @@ inline int batch_split_nl(uint32_t K)
 
 // a.K: columns of a full row; xt, xb: the two re-laid copies of x.  SPLIT: slices
 // of NL * W groups, a.y an fp32 plane buffer [slices][M][N].
-template <int BITS, int W, int NL, bool RAGGED, bool SPLIT = false>
+template <int BITS, int MODE, int W, int NL, bool RAGGED, bool SPLIT = false>
 hipError_t launch_batch_t(const DecodeArgs &a, int M, bool y_f32, const void *xt, const void *xb, hipStream_t s)
 {
-    constexpr int kBatchLds = BatchLds<BITS, W>::kTotal;
-    auto kern = decode_batch_kernel<BITS, W, NL, RAGGED, SPLIT>;
+    constexpr int kBatchLds = BatchLds<BITS, MODE, W>::kTotal;
+    auto kern = decode_batch_kernel<BITS, MODE, W, NL, RAGGED, SPLIT>;
     static std::atomic<int> configured{0};                 // idempotent attribute, benign race
     if (!configured.load(std::memory_order_relaxed)) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -598,32 +645,32 @@ hipError_t launch_batch_t(const DecodeArgs &a, int M, bool y_f32, const void *xt
     return hipGetLastError();
 }
 
-template <int BITS, int NL>
+template <int BITS, int MODE, int NL>
 hipError_t launch_batch_n(const DecodeArgs &a, int M, bool y_f32, const void *xt, const void *xb, hipStream_t s)
 {
-    if (a.K / kGroup == (uint32_t)NL * 8) return launch_batch_t<BITS, 8, NL, false>(a, M, y_f32, xt, xb, s);
-    return launch_batch_t<BITS, 8, NL, true>(a, M, y_f32, xt, xb, s);
+    if (a.K / kGroup == (uint32_t)NL * 8) return launch_batch_t<BITS, MODE, 8, NL, false>(a, M, y_f32, xt, xb, s);
+    return launch_batch_t<BITS, MODE, 8, NL, true>(a, M, y_f32, xt, xb, s);
 }
 
 // One launch of up to 16 tokens for one bit width.  Eight waves share a tile of
 // 16 rows: with 16 waves (128 registers each) the compiler spills the in-flight
 // index words and the kernel runs at half the speed.  part: an fp32 scratch plane
 // for the partial sums of a row cut into slices (K > 8192), unused otherwise.
-template <int BITS>
+template <int BITS, int MODE = 0>
 hipError_t launch_batch_bits(const DecodeArgs &a, int M, bool y_f32, float *part, const void *xt, const void *xb,
                              hipStream_t s)
 {
     const int nl = batch_split_nl(a.K);
     if (nl == 0) {
         switch ((a.K / kGroup + 7) / 8) {
-        case 1: return launch_batch_n<BITS, 1>(a, M, y_f32, xt, xb, s);
-        case 2: return launch_batch_n<BITS, 2>(a, M, y_f32, xt, xb, s);
-        case 3: return launch_batch_n<BITS, 3>(a, M, y_f32, xt, xb, s);
-        case 4: return launch_batch_n<BITS, 4>(a, M, y_f32, xt, xb, s);
-        case 5: return launch_batch_n<BITS, 5>(a, M, y_f32, xt, xb, s);
-        case 6: return launch_batch_n<BITS, 6>(a, M, y_f32, xt, xb, s);
-        case 7: return launch_batch_n<BITS, 7>(a, M, y_f32, xt, xb, s);
-        case 8: return launch_batch_n<BITS, 8>(a, M, y_f32, xt, xb, s);
+        case 1: return launch_batch_n<BITS, MODE, 1>(a, M, y_f32, xt, xb, s);
+        case 2: return launch_batch_n<BITS, MODE, 2>(a, M, y_f32, xt, xb, s);
+        case 3: return launch_batch_n<BITS, MODE, 3>(a, M, y_f32, xt, xb, s);
+        case 4: return launch_batch_n<BITS, MODE, 4>(a, M, y_f32, xt, xb, s);
+        case 5: return launch_batch_n<BITS, MODE, 5>(a, M, y_f32, xt, xb, s);
+        case 6: return launch_batch_n<BITS, MODE, 6>(a, M, y_f32, xt, xb, s);
+        case 7: return launch_batch_n<BITS, MODE, 7>(a, M, y_f32, xt, xb, s);
+        case 8: return launch_batch_n<BITS, MODE, 8>(a, M, y_f32, xt, xb, s);
         default: return hipErrorInvalidValue;
         }
     }
@@ -632,10 +679,10 @@ hipError_t launch_batch_bits(const DecodeArgs &a, int M, bool y_f32, float *part
     DecodeArgs c = a;
     c.y = part;
     switch (nl) {
-    case 5: err = launch_batch_t<BITS, 8, 5, true, true>(c, M, true, xt, xb, s); break;
-    case 6: err = launch_batch_t<BITS, 8, 6, true, true>(c, M, true, xt, xb, s); break;
-    case 7: err = launch_batch_t<BITS, 8, 7, true, true>(c, M, true, xt, xb, s); break;
-    case 8: err = launch_batch_t<BITS, 8, 8, true, true>(c, M, true, xt, xb, s); break;
+    case 5: err = launch_batch_t<BITS, MODE, 8, 5, true, true>(c, M, true, xt, xb, s); break;
+    case 6: err = launch_batch_t<BITS, MODE, 8, 6, true, true>(c, M, true, xt, xb, s); break;
+    case 7: err = launch_batch_t<BITS, MODE, 8, 7, true, true>(c, M, true, xt, xb, s); break;
+    case 8: err = launch_batch_t<BITS, MODE, 8, 8, true, true>(c, M, true, xt, xb, s); break;
     default: return hipErrorInvalidValue;
     }
     if (err != hipSuccess) return err;

@@ -54,11 +54,12 @@ hipError_t launch_decode_splitk(int bits, int mode, bool y_f32, const DecodeArgs
 // y[slot][n] = sum over slices z, in order, of part[z][slot][n]
 hipError_t launch_splitk_sum(const float *part, uint32_t slices, uint32_t N, int slots, void *y, int64_t y_stride,
                              bool y_f32, bool y_bf16, hipStream_t s);
-// Matrix-core kernel for 2..16 tokens per launch (V2, 2..4-bit, K <= 32768; rows
+// Matrix-core kernel for 2..16 tokens per launch (V2 at 2..4 bits, V2a at 3 and 4 bits
+// with a library whose pair tables fit 64 KB of LDS; K <= 32768; rows
 // above 8192 columns in slices whose partial sums go through a scratch plane).
-bool batch_supports(int bits, int mode, uint32_t N, uint32_t K, int M);
+bool batch_supports(int bits, int mode, uint32_t L, uint32_t N, uint32_t K, int M);
 bool batch_is_split(uint32_t K);
-hipError_t launch_decode_batch(int bits, const DecodeArgs &a, int M, bool y_f32, float *part, hipStream_t s);
+hipError_t launch_decode_batch(int bits, int mode, const DecodeArgs &a, int M, bool y_f32, float *part, hipStream_t s);
 // fp32 scratch plane from a small static ring (split-K partial sums, unfused epilogues)
 float *scratch_plane(hipError_t *err);
 uint32_t scratch_plane_floats();

@@ -227,6 +227,30 @@ def test_batched_3bit_2bit_matches_oracle_and_single_calls(bits, N, K, M, dens):
         assert gated_rel_err(yb[m], y1[0]) <= TOL_F32
 
 
+# V2a (library tables, ids per group) through the matrix-core kernel, 3 and 4 bits
+@pytest.mark.parametrize("bits", [3, 4])
+@pytest.mark.parametrize("N,K,M,dens", [(200, 8192, 16, 0.003), (77, 1024, 5, 0.003), (64, 4096, 16, 0.003),
+                                        (33, 128, 2, 0.01), (90, 1408, 16, 0.003), (50, 5120, 7, 0.0),
+                                        (35, 7296, 3, 0.003), (40, 2048, 33, 0.003), (70, 11008, 16, 0.003),
+                                        (48, 28672, 16, 0.003), (24, 12288, 17, 0.003)])
+def test_batched_library_mode_matches_oracle_and_single_calls(bits, N, K, M, dens):
+    W = xi.random_weights(V2A, bits, N, K, density=dens, seed=5 * N + M + bits)
+    x = xi.activations(np.random.default_rng(K + 5 * M), M, K)
+    dW, xd, ref = check_gemv(W, x)
+    yb = host(xfp.xfp_gemv(dW, xd, y_dtype=torch.float32))
+    for m in (0, M - 1):
+        y1 = host(xfp.xfp_gemv(dW, xd[m:m + 1].contiguous(), y_dtype=torch.float32))
+        assert gated_rel_err(yb[m], y1[0]) <= TOL_F32
+
+
+@pytest.mark.parametrize("bits,L", [(4, 64), (4, 65), (3, 200), (3, 1), (4, 7)])
+def test_batched_library_sizes(bits, L):
+    """Libraries up to the 64 KB of pair tables the kernel holds (64 entries at 4 bits), and one past it, which
+    takes the per-token kernels."""
+    W = xi.random_weights(V2A, bits, 70, 2048, L=L, density=0.003, seed=L + bits)
+    check_gemv(W, xi.activations(np.random.default_rng(L), 16, 2048))
+
+
 def test_batched_with_more_outliers_than_a_tile_keeps_on_chip():
     """5 % outliers: a 16-row tile of K = 4096 holds about 3300 entries, far past the on-chip product
     buffer, and one row alone holds every entry of its tile."""
