@@ -75,6 +75,21 @@ def pack(q: np.ndarray, bits: int) -> np.ndarray:
     return words.reshape(*q.shape[:-1], K * bits // 32)
 
 
+def unpack_word10(words: np.ndarray, K: int) -> np.ndarray:
+    """3-bit indices in the ten-per-uint32 packing (paper table 2): words [..., ceil(K/10)] -> uint8 [..., K]."""
+    words = _c(words, np.uint32)
+    wpr = (K + 9) // 10
+    rows = words.size // wpr
+    q = np.empty((rows, K), dtype=np.uint8)
+    _load().xfp_oracle_unpack_word10(_p(words), ctypes.c_int64(rows), ctypes.c_int64(K), _p(q))
+    return q.reshape(*words.shape[:-1], K)
+
+
+def repack_word10(words: np.ndarray, K: int) -> np.ndarray:
+    """The same indices as the dense 3-bit stream: unpack every value, pack it again."""
+    return pack(unpack_word10(words, K), 3)
+
+
 def dequant_bulk(mode, bits, N, K, words, codebooks, group_ids=None, want_double=True):
     """Bulk term Codebook[Q] of one matrix: (fp16 bit patterns [N,K], doubles or None)."""
     words, codebooks = _c(words, np.uint32), _c(codebooks, np.uint16)

@@ -21,7 +21,8 @@
  *
  * Pins (tests/test_oracle_pins.py): hand-written packed words including a
  * field that straddles two words, pack/unpack round trips, the per-word
- * counts of the paper's packing table, all 65536 fp16 patterns against an
+ * counts of the paper's packing table (also for the ten-per-word 3-bit form:
+ * a hand-written word, reserved bits ignored, an independent packer), all 65536 fp16 patterns against an
  * independent converter, all-ones codebooks (row sums of x), zero codebooks
  * (outlier term alone against a dense scatter), a uniform-grid codebook
  * against textbook symmetric int4 dequantisation, V2a with one id against V2,
@@ -83,6 +84,19 @@ void xfp_oracle_unpack(const uint32_t *words, int64_t rows, int64_t K, int bits,
     for (int64_t r = 0; r < rows; ++r)
         for (int64_t k = 0; k < K; ++k)
             q[r * K + k] = (uint8_t)stream_field(words + r * wpr, k, bits);
+}
+
+/* The word packing of 3-bit indices in the paper's packing table (section 3.3,
+ * table 2): ten values per uint32, 30 bits used, 2 reserved.  Reading taken:
+ * value k of a row sits in word k / 10 at bits [3 (k % 10), 3 (k % 10) + 3),
+ * value 0 in the low bits as for the other widths, the reserved bits on top and
+ * ignored; a row of K values takes ceil(K / 10) words, the last one part-filled. */
+void xfp_oracle_unpack_word10(const uint32_t *words, int64_t rows, int64_t K, uint8_t *q)
+{
+    int64_t wpr = (K + 9) / 10;
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t k = 0; k < K; ++k)
+            q[r * K + k] = (uint8_t)((words[r * wpr + k / 10] >> (3 * (k % 10))) & 7u);
 }
 
 void xfp_oracle_pack(const uint8_t *q, int64_t rows, int64_t K, int bits, uint32_t *words)

@@ -90,6 +90,38 @@ def test_pack_unpack_round_trip(bits, K):
     assert np.array_equal(oracle.pack(oracle.unpack(words, K, bits), bits), words)
 
 
+# ten 3-bit values per uint32 (paper table 2: 30 bits used, 2 reserved)
+def test_word10_hand_vector_and_reserved_bits():
+    vals, word, used, reserve = 10, 32, 30, 2
+    assert vals * 3 == used and used + reserve == word
+    # octal digits are 3-bit fields: 0o1076543210 holds values 0..7, 0, 1 with value 0 in the low bits
+    w = np.array([[0o1076543210, 0o0000000052]], dtype=np.uint32)
+    q = oracle.unpack_word10(w, 12)
+    assert q.tolist() == [[0, 1, 2, 3, 4, 5, 6, 7, 0, 1, 2, 5]]
+    w_res = w | np.uint32(0xC0000000)                                 # the reserved bits carry nothing
+    assert np.array_equal(oracle.unpack_word10(w_res, 12), q)
+    # a row of K values takes ceil(K / 10) words: 128 values -> 13 words, the last holds 8
+    q = (np.arange(256, dtype=np.uint8) * 5 % 8).reshape(2, 128)
+    w = xi.pack_word10(q)
+    assert w.shape == (2, 13) and not (w >> np.uint32(30)).any() and not (w[:, 12] >> np.uint32(24)).any()
+    assert np.array_equal(oracle.unpack_word10(w, 128), q)
+    assert int(w[1, 3]) == sum(int(q[1, 30 + j]) << (3 * j) for j in range(10))
+
+
+@pytest.mark.parametrize("K", [128, 384, 4096])
+def test_word10_repack_is_the_dense_stream_of_the_same_indices(K):
+    rng = np.random.default_rng(K)
+    q = rng.integers(0, 8, size=(7, K), dtype=np.uint8)
+    w10 = xi.pack_word10(q)
+    dense = oracle.repack_word10(w10, K)
+    assert dense.shape == (7, K * 3 // 32)
+    assert np.array_equal(dense, xi.pack_bitstream(q, 3))             # the generators' dense encoder
+    assert np.array_equal(dense[0], bigint_pack(q[0], 3))             # independent encoder
+    assert np.array_equal(np_unpack(dense, K, 3), q)                  # independent decoder
+    junk = rng.integers(0, 4, size=w10.shape, dtype=np.uint32) << np.uint32(30)
+    assert np.array_equal(oracle.repack_word10(w10 | junk, K), dense)
+
+
 # ------------------------------------------------------------------ bulk term
 @pytest.mark.parametrize("mode,bits", [(V2, 2), (V2, 3), (V2, 4), (V2A, 3), (V2A, 4)])
 def test_all_ones_codebooks_give_row_sums(mode, bits):

@@ -106,6 +106,20 @@ def pack_bitstream(q: np.ndarray, bits: int) -> np.ndarray:
     return out.view("<u4").reshape(*lead, K * bits // 32)
 
 
+def pack_word10(q: np.ndarray) -> np.ndarray:
+    """Encode 3-bit indices q [..., K] ten to a uint32 (paper table 2): value k in word k // 10 at bit
+    3 * (k % 10), the top two bits of every word and the unused tail of a row's last word zero."""
+    q = np.ascontiguousarray(q, dtype=np.uint8)
+    K = q.shape[-1]
+    wpr = (K + 9) // 10
+    q2 = np.zeros((q.size // K, wpr * 10), dtype=np.uint32)
+    q2[:, :K] = q.reshape(-1, K)
+    w = np.zeros((q2.shape[0], wpr), dtype=np.uint32)
+    for j in range(10):
+        w |= q2[:, j::10] << np.uint32(3 * j)
+    return w.reshape(*q.shape[:-1], wpr)
+
+
 def random_words(rng: np.random.Generator, shape) -> np.ndarray:
     """Uniform random packed words = uniform random indices for any bit width."""
     return rng.integers(0, 1 << 32, size=shape, dtype=np.uint32)
