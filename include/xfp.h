@@ -187,6 +187,19 @@ int xfp_gemv_moe_combine(const xfp_weights *bank, const int32_t *expert_ids, int
 int xfp_convert_bf16_to_f16(const void *src, int64_t ld_src, void *dst, int rows, int cols, void *hip_stream);
 
 /*
+ * Load-time conversion of 3-bit indices from the word packing of the paper's
+ * packing table (section 3.3, table 2: ten values per uint32, 30 bits used, 2
+ * reserved) to the dense 3-bit stream that xfp_weights.indices holds.
+ * Reading taken: value k of a row sits in word k / 10 at bits [3 (k % 10),
+ * 3 (k % 10) + 3), value 0 in the low bits; the two top bits of every word are
+ * ignored; a row takes ceil(K / 10) words, rows stored back to back.
+ * src [rows][ceil(K/10)] and dst [rows][K*3/32] are DEVICE pointers, 4-byte
+ * aligned, distinct buffers (the caller owns both).  K % 128 == 0, rows >= 0
+ * (rows = E * N for a bank), rows * K*3/32 < 2^40.  Integer work, bit-exact.
+ */
+int xfp_repack_word10(const uint32_t *src, int64_t rows, int K, uint32_t *dst, void *hip_stream);
+
+/*
  * Parity hooks: the first two fused steps on their own (paper section 5,
  * steps 1 and 2), so that they can be compared bit for bit.
  * xfp_unpack_indices writes every index as one byte, idx_out [E*N][K].

@@ -63,13 +63,14 @@ def load_library():
     lib.xfp_unpack_indices.argtypes = [wp, vp, vp]
     lib.xfp_gemv_moe_combine.argtypes = [wp, vp, i32, vp, i64, vp, vp, i32, vp]
     lib.xfp_convert_bf16_to_f16.argtypes = [vp, i64, vp, i32, i32, vp]
+    lib.xfp_repack_word10.argtypes = [vp, i64, i32, vp, vp]
     lib.xfp_check_contents.argtypes = [wp, i64, vp, i32, vp, vp]
     lib.xfp_dequant_bulk.argtypes = [wp, vp, vp]
     lib.xfp_probe_read.argtypes = [vp, u64, vp, vp]
     lib.xfp_probe_copy.argtypes = [vp, vp, u64, vp]
     lib.xfp_strerror.argtypes = [i32]
     lib.xfp_strerror.restype = ctypes.c_char_p
-    for name in ("xfp_gemv", "xfp_gemv_moe", "xfp_gemv_moe_silu_mul", "xfp_gemv_moe_combine", "xfp_check_contents", "xfp_convert_bf16_to_f16", "xfp_unpack_indices", "xfp_dequant_bulk",
+    for name in ("xfp_gemv", "xfp_gemv_moe", "xfp_gemv_moe_silu_mul", "xfp_gemv_moe_combine", "xfp_check_contents", "xfp_convert_bf16_to_f16", "xfp_repack_word10", "xfp_unpack_indices", "xfp_dequant_bulk",
                  "xfp_probe_read", "xfp_probe_copy", "xfp_version"):
         getattr(lib, name).restype = i32
     _lib = lib
@@ -251,6 +252,18 @@ def xfp_convert_bf16_to_f16(src: torch.Tensor, stream=None) -> torch.Tensor:
     _check(load_library().xfp_convert_bf16_to_f16(_ptr(s2), s2.stride(0) if rows > 1 else cols, _ptr(dst), rows, cols,
                                                   _stream(stream)))
     return dst if src.dim() == 2 else dst[0]
+
+
+def xfp_repack_word10(words: torch.Tensor, K: int, stream=None) -> torch.Tensor:
+    """Dense 3-bit stream [rows, K*3/32] (int32 tensor) of indices stored ten to a uint32 [rows, ceil(K/10)]
+    (paper table 2); a one-time conversion at load."""
+    w2 = words.reshape(-1, words.shape[-1]).contiguous()
+    rows = int(w2.shape[0])
+    if w2.element_size() != 4 or int(w2.shape[1]) != (K + 9) // 10:
+        raise XfpError(-2, "words must be 32-bit, [rows, ceil(K/10)]")
+    dst = torch.empty((rows, K * 3 // 32), dtype=torch.int32, device=words.device)
+    _check(load_library().xfp_repack_word10(_ptr(w2), rows, int(K), _ptr(dst), _stream(stream)))
+    return dst.reshape(*words.shape[:-1], K * 3 // 32)
 
 
 def xfp_unpack_indices(W: DeviceWeights, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:

@@ -272,6 +272,16 @@ int xfp_gemv_moe_combine(const xfp_weights *bank, const int32_t *expert_ids, int
     return finish(xfp::launch_moe_combine(plane, slot_weights, bank->N, T, y, yd == XFP_F32, yd == XFP_BF16, s));
 }
 
+int xfp_repack_word10(const uint32_t *src, int64_t rows, int K, uint32_t *dst, void *hip_stream)
+{
+    if (!src || !dst) return XFP_ERR_NULL;
+    if (rows < 0 || K <= 0 || K % xfp::kGroup != 0) return XFP_ERR_SHAPE;
+    if ((uint64_t)rows * (uint64_t)(K / 32 * 3) >= (1ull << 40)) return XFP_ERR_SHAPE;
+    if (misaligned(src, 4) || misaligned(dst, 4)) return XFP_ERR_ALIGN;
+    if (rows == 0) return XFP_OK;
+    return finish(xfp::launch_repack_word10(src, (uint64_t)rows, (uint32_t)K, dst, static_cast<hipStream_t>(hip_stream)));
+}
+
 int xfp_convert_bf16_to_f16(const void *src, int64_t ld_src, void *dst, int rows, int cols, void *hip_stream)
 {
     if (!src || !dst) return XFP_ERR_NULL;

@@ -73,6 +73,8 @@ hipError_t launch_moe_combine(const float *part, const float *w, uint32_t N, int
                               bool y_bf16, hipStream_t s);
 // bf16 [rows][ld] -> fp16 [rows][K] (exact inside fp16's normal range, saturating beyond it)
 hipError_t launch_bf16_to_f16(const void *src, int64_t ld, void *dst, uint32_t rows, uint32_t K, hipStream_t s);
+// 3-bit indices, ten per uint32 [rows][ceil(K/10)] -> dense stream [rows][K*3/32]
+hipError_t launch_repack_word10(const uint32_t *src, uint64_t rows, uint32_t K, uint32_t *dst, hipStream_t s);
 hipError_t launch_unpack(int bits, const uint32_t *idx, uint64_t rows, uint32_t K, uint8_t *out,
                          hipStream_t s);
 hipError_t launch_dequant(int bits, int mode, const DecodeArgs &a, uint32_t E, uint16_t *out,

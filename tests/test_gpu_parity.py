@@ -59,6 +59,28 @@ def test_unpack_and_dequant_bit_exact(mode, bits, N, K, E):
         assert np.array_equal(w[e * N:(e + 1) * N], ref)
 
 
+# ten-per-word 3-bit packing (paper table 2) -> dense stream, bit-exact; decode of the converted tensor
+@pytest.mark.parametrize("rows,K", [(1, 128), (37, 384), (70, 4096), (300, 1152), (5, 32768)])
+def test_repack_word10_bit_exact(rows, K):
+    rng = np.random.default_rng(rows + K)
+    q = rng.integers(0, 8, size=(rows, K), dtype=np.uint8)
+    w10 = xi.pack_word10(q) | (rng.integers(0, 4, size=(rows, (K + 9) // 10), dtype=np.uint32) << np.uint32(30))
+    got = xfp.xfp_repack_word10(torch.from_numpy(w10.view(np.int32)).cuda(), K)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy().view(np.uint32), oracle.repack_word10(w10, K))
+
+
+def test_decode_of_a_matrix_loaded_from_the_word_packing():
+    W = xi.random_weights(V2, 3, 150, 2048, density=0.003, seed=10)
+    q = oracle.unpack(W.indices, W.K, 3)
+    w10 = xi.pack_word10(q)                                           # what an encoder following table 2 writes
+    dW = xfp.upload(W)
+    dense = xfp.xfp_repack_word10(torch.from_numpy(w10.view(np.int32)).cuda(), W.K)
+    assert torch.equal(dense.reshape(-1), dW.tensors["indices"].view(torch.int32).reshape(-1))
+    x = xi.activations(np.random.default_rng(11), 1, W.K)
+    assert gated_rel_err(host(xfp.xfp_gemv(dW, dev_x(x), y_dtype=torch.float32)), oracle.gemv_weights(W, x)) <= TOL_F32
+
+
 # ------------------------------------------------------------------ y, M = 1
 @pytest.mark.parametrize("mode,bits,N,K", [
     (V2, 4, 512, 1024), (V2, 4, 37, 128), (V2, 4, 300, 4096), (V2, 4, 131, 8192), (V2, 4, 65, 5120),

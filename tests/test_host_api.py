@@ -40,7 +40,7 @@ def moe(d, ids=FAKE, T=2, x=FAKE, xs=0, y=FAKE, dt=0, ldy=64):
 def test_library_exports_every_declared_symbol():
     lib = xfp.load_library()
     names = declared_functions()
-    assert {"xfp_gemv", "xfp_gemv_moe", "xfp_gemv_moe_silu_mul", "xfp_gemv_moe_combine", "xfp_check_contents", "xfp_convert_bf16_to_f16", "xfp_unpack_indices", "xfp_dequant_bulk", "xfp_strerror",
+    assert {"xfp_gemv", "xfp_gemv_moe", "xfp_gemv_moe_silu_mul", "xfp_gemv_moe_combine", "xfp_check_contents", "xfp_convert_bf16_to_f16", "xfp_repack_word10", "xfp_unpack_indices", "xfp_dequant_bulk", "xfp_strerror",
             "xfp_version", "xfp_probe_read", "xfp_probe_copy"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
@@ -142,6 +142,11 @@ def test_new_entry_points_reject_bad_arguments():
     assert cvt(cols=100) == -2 and cvt(ld=128) == -2 and cvt(rows=-1) == -2
     assert cvt(src=FAKE + 2) == -4 and cvt(ld=260) == -4
     assert cvt(rows=0) == 0
+    rpk = lambda src=FAKE, rows=4, K=256, dst=FAKE: lib.xfp_repack_word10(src, rows, K, dst, None)
+    assert rpk(src=None) == -1 and rpk(dst=None) == -1
+    assert rpk(K=100) == -2 and rpk(K=0) == -2 and rpk(rows=-1) == -2 and rpk(rows=1 << 40) == -2
+    assert rpk(src=FAKE + 2) == -4 and rpk(dst=FAKE + 1) == -4
+    assert rpk(rows=0) == 0
     chk = lambda dd=d, cap=10, ids=None, T=0, rep=FAKE: lib.xfp_check_contents(ctypes.byref(dd), cap, ids, T, rep, None)
     assert chk(rep=None) == -1 and chk(cap=-1) == -2 and chk(rep=FAKE + 4) == -4
     assert chk(dd=desc(out_col=None)) == -1                   # entries claimed but no column array
