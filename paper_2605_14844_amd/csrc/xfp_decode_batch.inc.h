@@ -432,10 +432,13 @@ __global__ __launch_bounds__(W * kWave) void decode_batch_kernel(BatchArgs ta)
             const int32_t nv = e.hi[h] - e.lo[h] - (int32_t)sub;       // entry 4 j of this lane is valid iff 4 j < nv
 #pragma unroll
             for (int j = 0; j < kRd; ++j) s += 4 * j < nv ? e.pv[h][j] : 0.f;
-            for (int32_t en = e.lo[h] + (int32_t)sub + 4 * kRd; en < e.hi[h]; en += 4)                    // long rows: rare
-                s += *(lds_f32_t *)(uintptr_t)(pbase + en * 64 + em * 4);
-            for (int32_t en = max(e.lo[h], (int32_t)kProdCap) + (int32_t)sub; en < e.hf[h]; en += 4)      // > kProdCap per tile: rare
-                s = fmaf(half_bits_to_float(a.val[ob + en]), half_bits_to_float(xrow[a.col[ob + en]]), s);
+            // both rare paths hang on wave-uniform conditions, so that skipping them costs a scalar branch each
+            if (e.hi[h] - e.lo[h] > 4 * kRd)                                                              // long rows
+                for (int32_t en = e.lo[h] + (int32_t)sub + 4 * kRd; en < e.hi[h]; en += 4)
+                    s += *(lds_f32_t *)(uintptr_t)(pbase + en * 64 + em * 4);
+            if (e.hf[h] > (int32_t)kProdCap)                                                              // > kProdCap per tile
+                for (int32_t en = max(e.lo[h], (int32_t)kProdCap) + (int32_t)sub; en < e.hf[h]; en += 4)
+                    s = fmaf(half_bits_to_float(a.val[ob + en]), half_bits_to_float(xrow[a.col[ob + en]]), s);
             s = dpp_add<0xB1>(s);                          // quad_perm [1,0,3,2]
             s = dpp_add<0x4E>(s);                          // quad_perm [2,3,0,1]
             if (sub == 0 && n < N && em < (uint32_t)M) {
