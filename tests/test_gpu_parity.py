@@ -298,6 +298,19 @@ def test_workload_5_full_size():
     check_gemv(W, xi.config_x(5, 16, W.K))
 
 
+@pytest.mark.parametrize("cfg", [8, 9, 10])
+def test_batched_bench_configurations_full_size(cfg):
+    """The 16-token configurations bench.py offers beyond the five workloads, at the size and with the inputs it times:
+    8 = 8192 x 28672 4-bit in four slices of K, 9 = 28672 x 8192 3-bit, 10 = the same as V2a with 32 library entries."""
+    if cfg == 8:
+        W = xi.random_weights(V2, 4, 8192, 28672, density=0.003, seed=xi.BASE_SEED + 7)
+    elif cfg == 9:
+        W = xi.random_weights(V2, 3, 28672, 8192, density=0.003, seed=xi.BASE_SEED + 9)
+    else:
+        W = xi.random_weights(V2A, 3, 28672, 8192, L=32, density=0.003, seed=xi.BASE_SEED + 10)
+    check_gemv(W, xi.activations(np.random.default_rng(xi.BASE_SEED + 400 + cfg), 16, W.K))
+
+
 # ------------------------------------------------------------------ expert-indexed
 @pytest.mark.parametrize("mode,bits,N,K,E", [(V2, 3, 128, 4096, 6), (V2, 3, 256, 1024, 6),
                                              (V2A, 4, 65, 512, 4), (V2, 4, 40, 2048, 3)])
