@@ -504,6 +504,9 @@ def test_every_decode_call_replays_from_a_hip_graph():
         ("batched", xi.random_weights(V2, 4, 64, 4096, density=0.003, seed=2), 16),
         ("split-K", xi.random_weights(V2, 3, 40, 20480, density=0.003, seed=3), 2),
         ("v2a", xi.random_weights(V2A, 3, 80, 1024, density=0.003, seed=4), 1),
+        ("batched in slices", xi.random_weights(V2, 4, 48, 16384, density=0.003, seed=5), 16),
+        ("batched 3-bit", xi.random_weights(V2, 3, 64, 2048, density=0.003, seed=6), 8),
+        ("batched v2a", xi.random_weights(V2A, 4, 48, 4096, density=0.003, seed=7), 16),
     ]
     side = torch.cuda.Stream()
     for name, W, M in cases:
