@@ -108,8 +108,13 @@ typedef struct xfp_weights {
  * W      one matrix (W->E must be 1).
  * x      fp16 [M][ldx], ldx >= K, ldx % 8 == 0, 16-byte aligned.
  * y      [M][ldy] of y_dtype, ldy >= N, 16-byte aligned base.
- * M      1 .. 65535.  M = 1 is the decode case; 2 <= M <= 16 takes a
- *        matrix-core (MFMA) path that reads the weights once.
+ * M      1 .. 65535.  M = 1 is the decode case.  M >= 2 takes a matrix-core
+ *        (MFMA) path that reads the weights once per 16 tokens, for V2 at
+ *        every bit width and V2a at 3 or 4 bits with L * 4^bits * 4 bytes
+ *        <= 64 KB, K <= 32768 (rows above 8192 columns in slices of K whose
+ *        partial sums go through a static scratch plane, 4 * S * 16 * N bytes
+ *        <= 4 MB for S = ceil(K / 8192) slices); any other shape runs the
+ *        M = 1 path once per token.  Same results either way, to rounding.
  */
 int xfp_gemv(const xfp_weights *W, const void *x, int M, int64_t ldx,
              void *y, int y_dtype, int64_t ldy, void *hip_stream);
