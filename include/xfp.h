@@ -30,9 +30,11 @@
  *    xfp_check_contents checks that contract on the device.
  *  - Calls from several host threads are safe.  The only state kept between
  *    calls is a set of small static device rings used as scratch by some
- *    paths (re-laid activations of the batched path: 16 slots; fp32 planes for
- *    split-K partial sums, the unfused epilogues and converted bf16
- *    activations: 4 slots of 4 MB).  A call takes the next slot, so calls on
+ *    paths (re-laid activations of the batched path: 16 slots of 2 MB; fp32
+ *    planes for split-K partial sums, the unfused epilogues and converted bf16
+ *    activations: 4 slots of 4 MB; every GPU the process uses holds its own
+ *    copy, and a call uses the one of the current device, which must be the
+ *    device of its pointers and stream).  A call takes the next slot, so calls on
  *    ONE stream never interfere; calls that overlap on different streams do
  *    only when more of them are in flight at once than the ring has slots.
  *

@@ -81,12 +81,14 @@ bool batch_is_split(uint32_t K) { return batch_split_nl(K) != 0; }
 // scratch plane when batch_is_split(a.K) (calls on one stream may share it).
 hipError_t launch_decode_batch(int bits, int mode, const DecodeArgs &a, int M, bool y_f32, float *part, hipStream_t s)
 {
-    static std::atomic<void *> ring{nullptr};              // device address of g_x (one GPU per process)
-    void *p = ring.load(std::memory_order_relaxed);
+    static std::atomic<void *> ring[kMaxDevices];          // device address of g_x, per device (each holds its own copy)
+    const int dev = current_device();
+    if (dev < 0) return hipErrorInvalidDevice;
+    void *p = ring[dev].load(std::memory_order_relaxed);
     if (!p) {
         hipError_t err = hipGetSymbolAddress(&p, HIP_SYMBOL(g_x));
         if (err != hipSuccess) return err;
-        ring.store(p, std::memory_order_relaxed);
+        ring[dev].store(p, std::memory_order_relaxed);
     }
     static std::atomic<unsigned> next_slot{0};
     const int xs = (int)(next_slot.fetch_add(1, std::memory_order_relaxed) % kXtSlots);

@@ -620,12 +620,14 @@ hipError_t launch_batch_t(const DecodeArgs &a, int M, bool y_f32, const void *xt
 {
     constexpr int kBatchLds = BatchLds<BITS, MODE, W>::kTotal;
     auto kern = decode_batch_kernel<BITS, MODE, W, NL, RAGGED, SPLIT>;
-    static std::atomic<int> configured{0};                 // idempotent attribute, benign race
-    if (!configured.load(std::memory_order_relaxed)) {
+    static std::atomic<int> configured[kMaxDevices];       // per device; idempotent attribute, benign race
+    const int dev = current_device();
+    if (dev < 0) return hipErrorInvalidDevice;
+    if (!configured[dev].load(std::memory_order_relaxed)) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kBatchLds);
         if (err != hipSuccess) return err;
-        configured.store(1, std::memory_order_relaxed);
+        configured[dev].store(1, std::memory_order_relaxed);
     }
     BatchArgs ta;
     ta.a = a;

@@ -66,12 +66,17 @@ int splitk_slices(int bits, int mode, uint32_t N, uint32_t K, uint32_t L, int sl
 // nullptr with *err set.
 float *scratch_plane(hipError_t *err)
 {
-    static std::atomic<void *> ring{nullptr};          // device address of g_partial (one GPU per process)
-    void *p = ring.load(std::memory_order_relaxed);
+    static std::atomic<void *> ring[kMaxDevices];      // device address of g_partial, per device (each holds its own copy)
+    const int dev = current_device();
+    if (dev < 0) {
+        *err = hipErrorInvalidDevice;
+        return nullptr;
+    }
+    void *p = ring[dev].load(std::memory_order_relaxed);
     if (!p) {
         *err = hipGetSymbolAddress(&p, HIP_SYMBOL(g_partial));
         if (*err != hipSuccess) return nullptr;
-        ring.store(p, std::memory_order_relaxed);
+        ring[dev].store(p, std::memory_order_relaxed);
     }
     static std::atomic<unsigned> next_slot{0};
     return static_cast<float *>(p) + (size_t)(next_slot.fetch_add(1, std::memory_order_relaxed) % kSplitSlots) * kSplitFloats;

@@ -7,6 +7,7 @@ namespace xfp {
 
 constexpr int kGroup = 128;
 constexpr int kWave = 64;
+constexpr int kMaxDevices = 64;   // GPUs of one process whose static scratch addresses are remembered
 constexpr int kLaneWeights = 32;   // weights one lane decodes per index load (all bit widths)
 
 // Everything a decode kernel needs, passed by value.  gridDim.y enumerates
@@ -36,6 +37,13 @@ struct DecodeArgs {
     uint32_t fuse_half;
     uint32_t y_bf16;       // the 16-bit output type is bf16 instead of fp16
 };
+
+// Index of the current device for per-device host-side state, or -1.
+inline int current_device()
+{
+    int d = 0;
+    return hipGetDevice(&d) == hipSuccess && d >= 0 && d < kMaxDevices ? d : -1;
+}
 
 // Launchers, one per kernel family (defined in the .hip files).
 hipError_t launch_decode_rows(int bits, int mode, bool y_f32, const DecodeArgs &a, int slots,
