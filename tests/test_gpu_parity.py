@@ -624,3 +624,44 @@ def test_seeded_shape_sweep(i, mode, bits, N, K, M, dens):
     under one fixed list of drawn shapes."""
     W = xi.random_weights(mode, bits, N, K, density=dens, seed=1000 + i)
     check_gemv(W, xi.activations(np.random.default_rng(2000 + i), M, K))
+
+
+def _moe_sweep_cases():
+    rng = np.random.default_rng(20260515)
+    ks = [128, 256, 384, 512, 640, 896, 1024, 1408, 2048, 2176, 4096, 5120, 8192, 16384, 20480]
+    cases = []
+    for i in range(36):
+        mode = int(rng.integers(0, 2))
+        bits = int(rng.integers(2, 5))
+        K = int(ks[int(rng.integers(0, len(ks)))])
+        N = 2 * int(rng.integers(1, 150))
+        E = int(rng.integers(1, 6))
+        T = int(rng.integers(1, 10))
+        dens = float([0.0, 0.001, 0.003, 0.02][int(rng.integers(0, 4))])
+        cases.append((i, mode, bits, N, K, E, T, dens, bool(rng.integers(0, 2)), i % 3))
+    return cases
+
+
+@pytest.mark.parametrize("i,mode,bits,N,K,E,T,dens,shared,kind", _moe_sweep_cases())
+def test_seeded_moe_sweep(i, mode, bits, N, K, E, T, dens, shared, kind):
+    """The expert-indexed call and its two fused epilogues over one fixed list of drawn shapes, routings (duplicates
+    included) and input forms (one shared activation row or one per slot)."""
+    rng = np.random.default_rng(3000 + i)
+    W = xi.random_weights(mode, bits, N, K, E=E, density=dens, seed=3000 + i)
+    ids = rng.integers(0, E, size=T).astype(np.int32)
+    ids_d = torch.from_numpy(ids).cuda()
+    xb = xi.activations(np.random.default_rng(4000 + i), 1 if shared else T, K)
+    ref = oracle.gemv_moe(W, ids, xb, shared_x=shared)
+    dW, xd = xfp.upload(W), dev_x(xb)
+    xin = xd[0] if shared else xd
+    if kind == 0:
+        assert gated_rel_err(host(xfp.xfp_gemv_moe(dW, ids_d, xin, y_dtype=torch.float32)), ref) <= TOL_F32
+        assert gated_rel_err(host(xfp.xfp_gemv_moe(dW, ids_d, xin, y_dtype=torch.float16)), ref) <= TOL_F16
+    elif kind == 1:
+        h = host(xfp.xfp_gemv_moe_silu_mul(dW, ids_d, xin, h_dtype=torch.float32))
+        assert gated_rel_err(h, oracle.silu_mul(ref)) <= TOL_F32
+    else:
+        w = rng.random(T).astype(np.float32)
+        xt = xd.expand(T, K).contiguous() if shared else xd
+        y = host(xfp.xfp_gemv_moe_combine(dW, ids_d, xt, torch.from_numpy(w).cuda(), y_dtype=torch.float32))
+        assert gated_rel_err(y[None, :], oracle.moe_combine(ref, w)[None, :]) <= TOL_F32
