@@ -155,6 +155,25 @@ def test_results_are_run_to_run_deterministic():
         assert torch.equal(a, xfp.xfp_gemv(dW, xd, y_dtype=torch.float32))
 
 
+@pytest.mark.parametrize("mode,bits,N,K,M,E", [(V2A, 4, 10, 5120, 1, 2), (V2A, 3, 300, 4096, 1, 1), (V2, 4, 200, 8192, 16, 1),
+                                               (V2, 3, 64, 20480, 2, 1), (V2A, 3, 90, 2048, 16, 1), (V2, 4, 48, 16384, 16, 1)])
+def test_every_kernel_family_is_bitwise_repeatable(mode, bits, N, K, M, E):
+    """Fixed summation orders and no float atomics: the same call gives the same bits every time (streaming kernel
+    with a shared library and expert ids, batched kernel, split-K, batched kernel in slices)."""
+    W = xi.random_weights(mode, bits, N, K, E=E, density=0.003, seed=N + K)
+    dW = xfp.upload(W)
+    if E > 1:
+        ids_d = torch.from_numpy(np.array([0, 1, 1, 0, 1, 1, 0, 0], dtype=np.int32)).cuda()
+        xd = dev_x(xi.activations(np.random.default_rng(3), 1, K))[0]
+        call = lambda: xfp.xfp_gemv_moe(dW, ids_d, xd, y_dtype=torch.float32)
+    else:
+        xd = dev_x(xi.activations(np.random.default_rng(3), M, K))
+        call = lambda: xfp.xfp_gemv(dW, xd, y_dtype=torch.float32)
+    first = call().clone()
+    for _ in range(20):
+        assert torch.equal(first, call())
+
+
 # ------------------------------------------------------------------ edge cases
 def test_no_outliers_with_null_csr_arrays():
     W = xi.random_weights(V2, 4, 64, 512, density=0.0, seed=5)
