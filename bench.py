@@ -262,7 +262,7 @@ def main():
     args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build covers the single-GPU decode kernel only; run with --gpus 1 "
-              "(sharding across GPUs is by output rows and is described in DESIGN.md).", file=sys.stderr)
+              "(across GPUs the matrices would be sharded by output rows; no collective is involved).", file=sys.stderr)
         raise SystemExit(2)
     import torch
 
