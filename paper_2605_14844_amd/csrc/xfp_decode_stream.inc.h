@@ -430,7 +430,22 @@ void decode_stream_kernel(DecodeArgs a, int y_f32)
             // entry e = (first index) | (second index) << BITS; this lane builds e = lane, lane+64, ...
             constexpr int PE = 1 << (2 * BITS);                // pair entries per row (16, 64 or 256)
             constexpr int PR = PE >= kWave ? PE / kWave : 1;
-            if (PE >= kWave || lane < PE) {
+            if constexpr (BITS == 4 && NCH <= 4) {
+                // 256 entries: this lane builds the four consecutive entries 4 lane .. 4 lane + 3 (second index
+                // lane / 4, first indices 4 (lane % 4) ..): one 8-byte and one 2-byte read, one 16-byte write per row
+                // instead of five reads and four writes (measured: 1 % on 8192x4096, 8 % on split-K slices, which
+                // rebuild every row's table; with more than four chunks of x in registers it is slower)
+                typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+                typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+                typedef __attribute__((address_space(3))) const u2 lds_u2_t;
+#pragma unroll
+                for (int r = 0; r < B; ++r) {
+                    const u2 w = *(lds_u2_t *)(uintptr_t)(raw_base + r * Fmt::kRawBytes + (lane & 3) * 8);
+                    const uint32_t hs = (uint32_t)*(lds_u16_t *)(uintptr_t)(raw_base + r * Fmt::kRawBytes + (lane >> 2) * 2) << 16;
+                    *(__attribute__((address_space(3))) u4 *)(uintptr_t)(lds_base + r * Fmt::kRowBytes + lane * 16) =
+                        u4{(w.x & 0xFFFFu) | hs, (w.x >> 16) | hs, (w.y & 0xFFFFu) | hs, (w.y >> 16) | hs};
+                }
+            } else if (PE >= kWave || lane < PE) {
 #pragma unroll
                 for (int r = 0; r < B; ++r) {
                     // 64 is a multiple of the codebook size, so the first index of every
