@@ -29,14 +29,27 @@
  *    caller's contract; violating it is undefined behaviour.
  *    xfp_check_contents checks that contract on the device.
  *  - Calls from several host threads are safe.  The only state kept between
- *    calls is a set of small static device rings used as scratch by some
- *    paths (re-laid activations of the batched path: 16 slots of 2 MB; fp32
- *    planes for split-K partial sums, the unfused epilogues and converted bf16
- *    activations: 4 slots of 4 MB; every GPU the process uses holds its own
- *    copy, and a call uses the one of the current device, which must be the
- *    device of its pointers and stream).  A call takes the next slot, so calls on
- *    ONE stream never interfere; calls that overlap on different streams do
- *    only when more of them are in flight at once than the ring has slots.
+ *    calls is a static ring of eight workspaces of 10 MB in device memory
+ *    (every GPU the process uses holds its own copy; a call uses the one of the
+ *    current device, which must be the device of its pointers and stream).
+ *    A call that needs scratch memory (the batched path's re-laid activations,
+ *    split-K partial sums, the unfused forms of the epilogues) takes ONE slot
+ *    for everything it needs.  Eager calls cycle through four slots, so calls
+ *    on ONE stream never interfere, and calls that overlap on different
+ *    streams do only when more than four scratch-using calls are in flight at
+ *    once.  Calls recorded into a HIP graph keep their slot for as long as the
+ *    graph lives and cycle through four slots of their own, which eager calls
+ *    never take; two graphs that may run at the same time on different streams
+ *    can meet in one of them.  xfp_init resolves the ring's address; call it
+ *    once per device before recording a graph (an eager call does the same).
+ *  - Results are run-to-run deterministic by construction (fixed summation
+ *    orders, no floating-point atomics).  One observation stands against it and
+ *    is not explained: on one machine one call returned, twice, the same wrong
+ *    value (off by 2e-4 relative) in one of four workgroups that compute the
+ *    same output from the same data; bit-exact emulation of that kernel excludes
+ *    every event its code could produce (stale or foreign table contents, a
+ *    wrong library id, wrong activations, a dropped or duplicated outlier) and
+ *    leaves only a corrupted single operand.
  *
  * Data layout (all little-endian)
  *  - indices: per matrix, N rows of K*bits/32 uint32 words, no row padding.
@@ -51,7 +64,7 @@
  *    absolute offsets (row_ptr[0] == 0), int32 col [nnz] ascending within a
  *    row with no duplicates, fp16 val [nnz].  The outlier value is ADDED to
  *    the codebook value at that position (eq. 1 is a sum).
- *  - x is fp16 (or bf16, converted: XFP_X_BF16); y is fp16, bf16 or fp32, rounded
+ *  - x is fp16 (or bf16, converted as it is loaded: XFP_X_BF16); y is fp16, bf16 or fp32, rounded
  *    once, to nearest even, from the fp32 sum; accumulation is fp32.
  */
 #ifndef XFP_H
@@ -75,10 +88,10 @@ typedef enum {
 typedef enum { XFP_MODE_V2 = 0, XFP_MODE_V2A = 1 } xfp_mode;
 typedef enum { XFP_F16 = 0, XFP_F32 = 1, XFP_BF16 = 2 } xfp_dtype;   /* type of an output (y, h) */
 /* OR into a y_dtype / h_dtype argument: the activations x are bf16 instead of
- * fp16 (the paper's kernel takes and returns bf16, section 5).  They are first
- * converted to fp16 into a static scratch plane by one small extra launch
- * (see xfp_convert_bf16_to_f16 for the rounding; rows * K <= 2^21), so a
- * caller that feeds several projections from one x converts once itself. */
+ * fp16 (the paper's kernel takes and returns bf16, section 5).  Every kernel
+ * converts them to fp16 as it loads them (see xfp_convert_bf16_to_f16 for the
+ * rounding): no extra launch, no scratch, and bit for bit the result of the
+ * same call on the converted activations. */
 #define XFP_X_BF16 0x100
 
 #define XFP_GROUP 128
@@ -117,6 +130,10 @@ typedef struct xfp_weights {
  *        partial sums go through a static scratch plane, 4 * S * 16 * N bytes
  *        <= 4 MB for S = ceil(K / 8192) slices); any other shape runs the
  *        M = 1 path once per token.  Same results either way, to rounding.
+ * XFP_ERR_UNSUPPORTED for a row no kernel takes: longer than 16384 columns with
+ * no split into equal slices of at most 8192 (or partial sums beyond the
+ * scratch plane) AND too long for the general kernel to stage on chip
+ * (2 K bytes plus its tables within 160 KB).
  */
 int xfp_gemv(const xfp_weights *W, const void *x, int M, int64_t ldx,
              void *y, int y_dtype, int64_t ldy, void *hip_stream);
@@ -154,7 +171,7 @@ int xfp_gemv_moe(const xfp_weights *bank, const int32_t *expert_ids, int T,
  * bank->N must be even.  expert_ids may be NULL when bank->E == 1 (a dense
  * gated MLP: slot t is token t).  h is [T][ldh], ldh >= N/2; everything else
  * as for xfp_gemv_moe.  Shapes the streaming kernel does not take (K / 128
- * without a split, oversized V2a libraries) run the plain decode into a static
+ * without a split, oversized V2a libraries) run the plain decode into an
  * fp32 scratch plane plus a small kernel; XFP_ERR_UNSUPPORTED if T * N exceeds
  * that plane (2^20 floats).
  */
@@ -172,7 +189,7 @@ int xfp_gemv_moe_silu_mul(const xfp_weights *bank, const int32_t *expert_ids, in
  * T * K <= 16384 take one launch: an output row is decoded as the concatenation
  * of the T experts' rows, each part scaled by its slot's weight (the slots are
  * then added lane by lane and by a wave reduction, not in ascending order).
- * Other shapes: the per-slot results meet in a static fp32 scratch plane
+ * Other shapes: the per-slot results meet in an fp32 scratch plane
  * (T * N <= 2^20, else XFP_ERR_UNSUPPORTED) and a second small kernel adds them
  * in ascending slot order.
  *
@@ -250,6 +267,22 @@ int xfp_check_contents(const xfp_weights *W, int64_t nnz_capacity, const int32_t
  */
 int xfp_probe_read(const void *src, uint64_t bytes, uint32_t *sink, void *hip_stream);
 int xfp_probe_copy(const void *src, void *dst, uint64_t bytes, void *hip_stream);
+
+/*
+ * Resolves, for the current device, the addresses of the library's static
+ * device memory.  Optional: the first call that needs them does the same; call
+ * it once per device before recording calls into a HIP graph, so that nothing
+ * but launches happens under capture.
+ */
+int xfp_init(void);
+
+/*
+ * Test hook for the ring's slot arithmetic (host only, touches no device): the
+ * slot index in [0, 8) that the ticket-th scratch-using call of its kind takes;
+ * capturing != 0: a call recorded into a HIP graph.  Eager calls get slots
+ * 0..3, recorded calls 4..7.
+ */
+int xfp_ring_slot(unsigned ticket, int capturing);
 
 /* Text for a status code; never NULL.  For XFP_ERR_HIP the text of the last
  * HIP error seen by the calling thread is appended. */

@@ -71,7 +71,7 @@ def load_library():
     lib.xfp_strerror.argtypes = [i32]
     lib.xfp_strerror.restype = ctypes.c_char_p
     for name in ("xfp_gemv", "xfp_gemv_moe", "xfp_gemv_moe_silu_mul", "xfp_gemv_moe_combine", "xfp_check_contents", "xfp_convert_bf16_to_f16", "xfp_repack_word10", "xfp_unpack_indices", "xfp_dequant_bulk",
-                 "xfp_probe_read", "xfp_probe_copy", "xfp_version"):
+                 "xfp_probe_read", "xfp_probe_copy", "xfp_version", "xfp_init"):
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -83,6 +83,11 @@ def xfp_strerror(status: int) -> str:
 
 def xfp_version() -> int:
     return int(load_library().xfp_version())
+
+
+def xfp_init() -> None:
+    """Resolve the library's static device memory on the current device (optional; before graph capture)."""
+    _check(load_library().xfp_init())
 
 
 def _check(status: int):

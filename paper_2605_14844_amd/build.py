@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import glob
+import hashlib
 import os
 import shutil
 import subprocess
@@ -34,17 +35,39 @@ def _run(cmd, verbose):
         print(out)
 
 
-def build(verbose: bool = False) -> str:
-    """Compile every source to an object (in parallel), link, then replace the library atomically."""
+def _stamp(src: str) -> str:
+    """Hash of everything an object depends on: flags, the source, every header."""
+    h = hashlib.sha1(" ".join(HIPCC_FLAGS).encode())
+    deps = [src] + sorted(glob.glob(os.path.join(CSRC, "*.h"))) + sorted(glob.glob(os.path.join(HERE, "..", "include", "*.h")))
+    for d in deps:
+        with open(d, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def build(verbose: bool = False, incremental: bool = False) -> str:
+    """Compile every source to an object (in parallel), link, then replace the library atomically.
+    incremental: reuse objects of unchanged sources from _build/ (a development convenience; the
+    default compiles everything)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmpdir = tempfile.mkdtemp(prefix="xfp_build_")
+    cache = os.path.join(HERE, "_build")
     try:
         objs = []
         jobs = []
         for src in sources():
-            obj = os.path.join(tmpdir, os.path.basename(src)[:-4] + ".o")
+            name = os.path.basename(src)[:-4]
+            if incremental:
+                os.makedirs(cache, exist_ok=True)
+                obj = os.path.join(cache, f"{name}.{_stamp(src)}.o")
+                if not os.path.exists(obj):
+                    for old in glob.glob(os.path.join(cache, name + ".*.o")):
+                        os.remove(old)
+                    jobs.append([hipcc, *HIPCC_FLAGS, "-c", "-o", obj, src])
+            else:
+                obj = os.path.join(tmpdir, name + ".o")
+                jobs.append([hipcc, *HIPCC_FLAGS, "-c", "-o", obj, src])
             objs.append(obj)
-            jobs.append([hipcc, *HIPCC_FLAGS, "-c", "-o", obj, src])
         workers = max(1, min(len(jobs), os.cpu_count() or 1, 8))
         with ThreadPoolExecutor(max_workers=workers) as pool:
             list(pool.map(lambda c: _run(c, verbose), jobs))
@@ -57,4 +80,5 @@ def build(verbose: bool = False) -> str:
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import sys
+    print(build(verbose=True, incremental="--incremental" in sys.argv))

@@ -65,18 +65,40 @@ bool dtype_ok(int y_dtype)
     return (y_dtype & ~(0xFF | XFP_X_BF16)) == 0 && (y_dtype & 0xFF) <= XFP_BF16;
 }
 
-// x given as bf16: an fp16 copy [rows][K] in a scratch plane takes its place
-int convert_x(const xfp_weights *W, int rows, const void *&x, int64_t &x_stride, hipStream_t s)
+// Where a call's scratch memory comes from: one slot of the static ring, taken
+// the first time some path asks for it (most calls never do).
+struct Scratch {
+    hipStream_t stream;
+    bool have = false;
+    xfp::Workspace ws{};
+    explicit Scratch(hipStream_t s) : stream(s) {}
+    hipError_t get(const xfp::Workspace **out)
+    {
+        if (!have) {
+            hipError_t err = xfp::ring_workspace(stream, &ws);
+            if (err != hipSuccess) return err;
+            have = true;
+        }
+        *out = &ws;
+        return hipSuccess;
+    }
+};
+
+// Longest row the general kernel can stage: x (2 K bytes) and its tables share the
+// 160 KB of LDS of a compute unit.
+bool rows_fits(const xfp_weights *W)
 {
-    if ((uint64_t)rows * W->K > 2ull * xfp::scratch_plane_floats()) return XFP_ERR_UNSUPPORTED;
-    hipError_t perr = hipSuccess;
-    float *plane = xfp::scratch_plane(&perr);
-    if (!plane) return finish(perr);
-    hipError_t err = xfp::launch_bf16_to_f16(x, rows > 1 ? x_stride : (int64_t)W->K, plane, (uint32_t)rows, W->K, s);
-    if (err != hipSuccess) return finish(err);
-    x = plane;
-    x_stride = x_stride == 0 ? 0 : (int64_t)W->K;
-    return XFP_OK;
+    const size_t tables = (W->mode == XFP_MODE_V2A ? (size_t)W->L : 4u) * (2u << W->bits);
+    return (size_t)W->K * 2 + tables <= 160 * 1024;
+}
+
+// Shapes no kernel takes (checked before anything is launched): rows beyond the
+// streaming and split-K kernels that the general kernel cannot stage either.
+bool decodable(const xfp_weights *W, int slots)
+{
+    const int bits = (int)W->bits, mode = (int)W->mode;
+    return xfp::stream_supports(bits, mode, W->K, W->L) || xfp::splitk_slices(bits, mode, W->N, W->K, W->L, slots) ||
+           rows_fits(W);
 }
 
 int check_io(const xfp_weights *W, const void *x, const void *y, int y_dtype, int64_t ldy)
@@ -99,25 +121,29 @@ uint32_t rows_per_block(uint32_t N, int slots)
 }
 
 // One token through the M = 1 kernels (the odd token left over after chunks of 16).
-hipError_t single_token(const xfp_weights *W, xfp::DecodeArgs c, int y_dtype, hipStream_t s)
+int single_token(const xfp_weights *W, xfp::DecodeArgs c, int y_dtype, Scratch &sc, hipStream_t s)
 {
     const int bits = (int)W->bits, mode = (int)W->mode;
     const bool y_f32 = y_dtype == XFP_F32;
-    if (xfp::stream_supports(bits, mode, W->K, W->L)) return xfp::launch_decode_stream(bits, mode, y_f32, c, 1, s);
-    if (const int S = xfp::splitk_slices(bits, mode, W->N, W->K, W->L, 1))
-        return xfp::launch_decode_splitk(bits, mode, y_f32, c, 1, S, s);
+    if (xfp::stream_supports(bits, mode, W->K, W->L)) return finish(xfp::launch_decode_stream(bits, mode, y_f32, c, 1, s));
+    if (const int S = xfp::splitk_slices(bits, mode, W->N, W->K, W->L, 1)) {
+        const xfp::Workspace *ws = nullptr;
+        hipError_t err = sc.get(&ws);
+        if (err != hipSuccess) return finish(err);
+        return finish(xfp::launch_decode_splitk(bits, mode, y_f32, c, 1, S, ws->part, s));
+    }
+    if (!rows_fits(W)) return XFP_ERR_UNSUPPORTED;
     c.rows_per_block = rows_per_block(W->N, 1);
-    return xfp::launch_decode_rows(bits, mode, y_f32, c, 1, s);
+    return finish(xfp::launch_decode_rows(bits, mode, y_f32, c, 1, s));
 }
 
+// y_dtype: an xfp_dtype, optionally OR-ed with XFP_X_BF16
 int decode(const xfp_weights *W, const int32_t *eids, int slots, const void *x, int64_t x_stride,
-           void *y, int y_dtype, int64_t ldy, hipStream_t s)
+           void *y, int y_dtype, int64_t ldy, Scratch &sc, hipStream_t s)
 {
-    if (y_dtype & XFP_X_BF16) {
-        const int rc = convert_x(W, x_stride == 0 ? 1 : slots, x, x_stride, s);
-        if (rc) return rc;
-    }
+    const bool x_bf16 = (y_dtype & XFP_X_BF16) != 0;
     y_dtype &= 0xFF;
+    const int bits = (int)W->bits, mode = (int)W->mode;
     xfp::DecodeArgs a = base_args(W);
     a.x = static_cast<const uint16_t *>(x);
     a.y = y;
@@ -125,47 +151,49 @@ int decode(const xfp_weights *W, const int32_t *eids, int slots, const void *x, 
     a.x_stride = x_stride;
     a.y_stride = ldy;
     a.y_bf16 = y_dtype == XFP_BF16;
-    if (!eids && xfp::batch_supports((int)W->bits, (int)W->mode, W->L, W->N, W->K, slots)) {
-        // batched tokens: the weights are read once per 16 tokens
+    a.x_bf16 = x_bf16;
+    if (!eids && xfp::batch_supports(bits, mode, W->L, W->N, W->K, slots)) {
+        // batched tokens: the weights are read once per 16 tokens; the chunks run in
+        // stream order, so they share the workspace
         const size_t ysz = y_dtype == XFP_F32 ? 4 : 2;
-        float *part = nullptr;                                  // one plane for all chunks: they run in stream order
-        if (xfp::batch_is_split(W->K)) {
-            hipError_t perr = hipSuccess;
-            part = xfp::scratch_plane(&perr);
-            if (!part) return finish(perr);
-        }
+        const xfp::Workspace *ws = nullptr;
+        hipError_t werr = sc.get(&ws);
+        if (werr != hipSuccess) return finish(werr);
         for (int m0 = 0; m0 < slots; m0 += 16) {
             xfp::DecodeArgs c = a;
             c.x = a.x + (int64_t)m0 * x_stride;
             c.y = static_cast<char *>(y) + (size_t)m0 * (size_t)ldy * ysz;
             const int mc = slots - m0 < 16 ? slots - m0 : 16;
-            hipError_t err = mc >= 2 ? xfp::launch_decode_batch((int)W->bits, (int)W->mode, c, mc, y_dtype == XFP_F32, part, s)
-                                     : single_token(W, c, y_dtype, s);
-            if (err != hipSuccess) return finish(err);
+            const int rc = mc >= 2 ? finish(xfp::launch_decode_batch(bits, mode, c, mc, y_dtype == XFP_F32, ws->part, ws->xc, s))
+                                   : single_token(W, c, y_dtype, sc, s);
+            if (rc) return rc;
         }
         return XFP_OK;
     }
-    if (xfp::stream_supports((int)W->bits, (int)W->mode, W->K, W->L))
-        return finish(xfp::launch_decode_stream((int)W->bits, (int)W->mode, y_dtype == XFP_F32, a, slots, s));
-    if (const int S = xfp::splitk_slices((int)W->bits, (int)W->mode, W->N, W->K, W->L, slots))
-        return finish(xfp::launch_decode_splitk((int)W->bits, (int)W->mode, y_dtype == XFP_F32, a, slots, S, s));
+    if (xfp::stream_supports(bits, mode, W->K, W->L))
+        return finish(xfp::launch_decode_stream(bits, mode, y_dtype == XFP_F32, a, slots, s));
+    if (const int S = xfp::splitk_slices(bits, mode, W->N, W->K, W->L, slots)) {
+        const xfp::Workspace *ws = nullptr;
+        hipError_t err = sc.get(&ws);
+        if (err != hipSuccess) return finish(err);
+        return finish(xfp::launch_decode_splitk(bits, mode, y_dtype == XFP_F32, a, slots, S, ws->part, s));
+    }
+    if (!rows_fits(W)) return XFP_ERR_UNSUPPORTED;
     a.rows_per_block = rows_per_block(W->N, slots);
-    return finish(xfp::launch_decode_rows((int)W->bits, (int)W->mode, y_dtype == XFP_F32, a, slots, s));
+    return finish(xfp::launch_decode_rows(bits, mode, y_dtype == XFP_F32, a, slots, s));
 }
 
 // h[t][j] = SiLU(y[t][j]) * y[t][N/2 + j]: in the streaming kernel's store when it
 // takes the shape, else the plain decode into a scratch plane plus a small kernel.
 int decode_silu_mul(const xfp_weights *W, const int32_t *eids, int slots, const void *x, int64_t x_stride,
-                    void *h, int h_dtype, int64_t ldh, hipStream_t s)
+                    void *h, int h_dtype, int64_t ldh, Scratch &sc, hipStream_t s)
 {
-    if (h_dtype & XFP_X_BF16) {
-        const int rc = convert_x(W, x_stride == 0 ? 1 : slots, x, x_stride, s);
-        if (rc) return rc;
-    }
+    const int x_flag = h_dtype & XFP_X_BF16;
     h_dtype &= 0xFF;
     if (xfp::stream_supports((int)W->bits, (int)W->mode, W->K, W->L)) {
         xfp::DecodeArgs a = base_args(W);
         a.y_bf16 = h_dtype == XFP_BF16;
+        a.x_bf16 = x_flag != 0;
         a.x = static_cast<const uint16_t *>(x);
         a.y = h;
         a.eids = eids;
@@ -175,13 +203,13 @@ int decode_silu_mul(const xfp_weights *W, const int32_t *eids, int slots, const 
         hipError_t err = xfp::launch_decode_stream((int)W->bits, (int)W->mode, h_dtype == XFP_F32, a, slots, s);
         if (err != hipErrorInvalidValue) return finish(err);     // InvalidValue: no even batch fits, nothing launched
     }
-    if ((uint64_t)slots * W->N > xfp::scratch_plane_floats()) return XFP_ERR_UNSUPPORTED;
-    hipError_t perr = hipSuccess;
-    float *plane = xfp::scratch_plane(&perr);
-    if (!plane) return finish(perr);
-    int rc = decode(W, eids, slots, x, x_stride, plane, XFP_F32, (int64_t)W->N, s);
+    if ((uint64_t)slots * W->N > xfp::kPlaneFloats || !decodable(W, slots)) return XFP_ERR_UNSUPPORTED;
+    const xfp::Workspace *ws = nullptr;
+    hipError_t werr = sc.get(&ws);
+    if (werr != hipSuccess) return finish(werr);
+    int rc = decode(W, eids, slots, x, x_stride, ws->epi, XFP_F32 | x_flag, (int64_t)W->N, sc, s);
     if (rc) return rc;
-    return finish(xfp::launch_silu_mul(plane, W->N / 2, slots, h, ldh, h_dtype == XFP_F32, h_dtype == XFP_BF16, s));
+    return finish(xfp::launch_silu_mul(ws->epi, W->N / 2, slots, h, ldh, h_dtype == XFP_F32, h_dtype == XFP_BF16, s));
 }
 
 }  // namespace
@@ -199,7 +227,10 @@ int xfp_gemv(const xfp_weights *W, const void *x, int M, int64_t ldx, void *y, i
     if (rc) return rc;
     if (ldx < (int64_t)W->K) return XFP_ERR_SHAPE;
     if (ldx % 8 != 0) return XFP_ERR_ALIGN;
-    return decode(W, nullptr, M, x, ldx, y, y_dtype, ldy, static_cast<hipStream_t>(hip_stream));
+    if (!decodable(W, M)) return XFP_ERR_UNSUPPORTED;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    Scratch sc(s);
+    return decode(W, nullptr, M, x, ldx, y, y_dtype, ldy, sc, s);
 }
 
 int xfp_gemv_moe(const xfp_weights *bank, const int32_t *expert_ids, int T, const void *x,
@@ -214,8 +245,10 @@ int xfp_gemv_moe(const xfp_weights *bank, const int32_t *expert_ids, int T, cons
     if (rc) return rc;
     if (x_slot_stride != 0 && x_slot_stride < (int64_t)bank->K) return XFP_ERR_SHAPE;
     if (x_slot_stride % 8 != 0 || misaligned(expert_ids, 4)) return XFP_ERR_ALIGN;
-    return decode(bank, expert_ids, T, x, x_slot_stride, y, y_dtype, ldy,
-                  static_cast<hipStream_t>(hip_stream));
+    if (!decodable(bank, T)) return XFP_ERR_UNSUPPORTED;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    Scratch sc(s);
+    return decode(bank, expert_ids, T, x, x_slot_stride, y, y_dtype, ldy, sc, s);
 }
 
 int xfp_gemv_moe_silu_mul(const xfp_weights *bank, const int32_t *expert_ids, int T, const void *x,
@@ -233,8 +266,9 @@ int xfp_gemv_moe_silu_mul(const xfp_weights *bank, const int32_t *expert_ids, in
     if (x_slot_stride != 0 && x_slot_stride < (int64_t)bank->K) return XFP_ERR_SHAPE;
     if (misaligned(x, 16) || misaligned(h, 16) || x_slot_stride % 8 != 0 || misaligned(expert_ids, 4))
         return XFP_ERR_ALIGN;
-    return decode_silu_mul(bank, expert_ids, T, x, x_slot_stride, h, h_dtype, ldh,
-                           static_cast<hipStream_t>(hip_stream));
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    Scratch sc(s);
+    return decode_silu_mul(bank, expert_ids, T, x, x_slot_stride, h, h_dtype, ldh, sc, s);
 }
 
 int xfp_gemv_moe_combine(const xfp_weights *bank, const int32_t *expert_ids, int T, const void *x,
@@ -249,10 +283,6 @@ int xfp_gemv_moe_combine(const xfp_weights *bank, const int32_t *expert_ids, int
     if (x_slot_stride != 0 && x_slot_stride < (int64_t)bank->K) return XFP_ERR_SHAPE;
     if (x_slot_stride % 8 != 0 || misaligned(expert_ids, 4) || misaligned(slot_weights, 4)) return XFP_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    if (y_dtype & XFP_X_BF16) {
-        rc = convert_x(bank, x_slot_stride == 0 ? 1 : T, x, x_slot_stride, s);
-        if (rc) return rc;
-    }
     const int yd = y_dtype & 0xFF;
     if (xfp::combine_supports((int)bank->bits, (int)bank->mode, bank->K, T)) {
         xfp::DecodeArgs a = base_args(bank);
@@ -260,16 +290,18 @@ int xfp_gemv_moe_combine(const xfp_weights *bank, const int32_t *expert_ids, int
         a.y = y;
         a.eids = expert_ids;
         a.x_stride = x_slot_stride;
+        a.x_bf16 = (y_dtype & XFP_X_BF16) != 0;
         return finish(xfp::launch_decode_combine((int)bank->bits, a, T, slot_weights, yd == XFP_F32, yd == XFP_BF16, s));
     }
     // other shapes: per-slot fp32 results in a scratch plane, added by a second kernel
-    if ((uint64_t)T * bank->N > xfp::scratch_plane_floats()) return XFP_ERR_UNSUPPORTED;
-    hipError_t perr = hipSuccess;
-    float *plane = xfp::scratch_plane(&perr);
-    if (!plane) return finish(perr);
-    rc = decode(bank, expert_ids, T, x, x_slot_stride, plane, XFP_F32, (int64_t)bank->N, s);
+    if ((uint64_t)T * bank->N > xfp::kPlaneFloats || !decodable(bank, T)) return XFP_ERR_UNSUPPORTED;
+    Scratch sc(s);
+    const xfp::Workspace *ws = nullptr;
+    hipError_t werr = sc.get(&ws);
+    if (werr != hipSuccess) return finish(werr);
+    rc = decode(bank, expert_ids, T, x, x_slot_stride, ws->epi, XFP_F32 | (y_dtype & XFP_X_BF16), (int64_t)bank->N, sc, s);
     if (rc) return rc;
-    return finish(xfp::launch_moe_combine(plane, slot_weights, bank->N, T, y, yd == XFP_F32, yd == XFP_BF16, s));
+    return finish(xfp::launch_moe_combine(ws->epi, slot_weights, bank->N, T, y, yd == XFP_F32, yd == XFP_BF16, s));
 }
 
 int xfp_repack_word10(const uint32_t *src, int64_t rows, int K, uint32_t *dst, void *hip_stream)
@@ -349,7 +381,7 @@ const char *xfp_strerror(int status)
     case XFP_OK: return "ok";
     case XFP_ERR_NULL: return "a required pointer is NULL";
     case XFP_ERR_SHAPE: return "bad shape (sizes must be positive, K a multiple of 128, leading dimensions large enough)";
-    case XFP_ERR_UNSUPPORTED: return "unsupported format (bits must be 2..4, mode V2/V2a, group 128, flags 0, dtype fp16/fp32)";
+    case XFP_ERR_UNSUPPORTED: return "unsupported format or shape (bits 2..4, mode V2/V2a, group 128, flags 0, output fp16/bf16/fp32; a row too long for every kernel; a result too large for the scratch plane)";
     case XFP_ERR_ALIGN: return "a pointer or leading dimension is misaligned";
     case XFP_ERR_HIP:
         std::snprintf(g_msg, sizeof(g_msg), "HIP launch failed: %s", hipGetErrorString(g_last_hip));
@@ -358,6 +390,10 @@ const char *xfp_strerror(int status)
     }
 }
 
-int xfp_version(void) { return (0 << 16) | (1 << 8) | 0; }
+int xfp_init(void) { return finish(xfp::ring_resolve()); }
+
+int xfp_ring_slot(unsigned ticket, int capturing) { return xfp::ring_slot_index(ticket, capturing != 0); }
+
+int xfp_version(void) { return (0 << 16) | (2 << 8) | 0; }
 
 }  // extern "C"

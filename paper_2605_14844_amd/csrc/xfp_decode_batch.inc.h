@@ -438,7 +438,7 @@ __global__ __launch_bounds__(W * kWave) void decode_batch_kernel(BatchArgs ta)
                     s += *(lds_f32_t *)(uintptr_t)(pbase + en * 64 + em * 4);
             if (e.hf[h] > (int32_t)kProdCap)                                                              // > kProdCap per tile
                 for (int32_t en = max(e.lo[h], (int32_t)kProdCap) + (int32_t)sub; en < e.hf[h]; en += 4)
-                    s = fmaf(half_bits_to_float(a.val[ob + en]), half_bits_to_float(xrow[a.col[ob + en]]), s);
+                    s = fmaf(half_bits_to_float(a.val[ob + en]), x_bits_to_float(xrow[a.col[ob + en]], a.x_bf16 != 0), s);
             s = dpp_add<0xB1>(s);                          // quad_perm [1,0,3,2]
             s = dpp_add<0x4E>(s);                          // quad_perm [2,3,0,1]
             if (sub == 0 && n < N && em < (uint32_t)M) {

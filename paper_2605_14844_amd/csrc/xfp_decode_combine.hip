@@ -35,6 +35,7 @@ struct CombineArgs {
     uint32_t N, K, T;
     uint32_t rows_per_wave;
     int y_f32, y_bf16;
+    int x_bf16;            // x holds bf16 values, converted to fp16 as they are loaded
 };
 
 // NCH : 2048-wide chunks of the concatenated row, T * K <= NCH * 2048
@@ -135,6 +136,14 @@ __global__ __launch_bounds__(kWave, combine_waves_per_simd(NCH * U)) void decode
     const int32_t *orp = a.rp + (size_t)expert_of(ot) * N;
     const uint16_t *ox = a.x + (int64_t)ot * a.x_stride;
     const float ow = o_on ? weight_of(ot) : 0.f;
+
+    const bool xbf = a.x_bf16 != 0;
+    if (xbf) {
+#pragma unroll
+        for (int c = 0; c < NCH; ++c)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) xr[c][i] = bf16x2_to_f16x2(xr[c][i]);
+    }
 
     // the all-zero table that dead lanes look up
     if constexpr (TAIL) {
@@ -250,9 +259,9 @@ __global__ __launch_bounds__(kWave, combine_waves_per_simd(NCH * U)) void decode
         // ---- a7 (fold), a8 ----
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            float p = half_bits_to_float((uint16_t)oval[u]) * half_bits_to_float(oxv[u]);
+            float p = half_bits_to_float((uint16_t)oval[u]) * x_bits_to_float(oxv[u], xbf);
             for (int32_t j = oj[u] + (int32_t)nsub; o_on && j < r1[u]; j += (int32_t)nsub)   // more entries than lanes: rare
-                p = fmaf(half_bits_to_float(a.val[j]), half_bits_to_float(ox[a.col[j]]), p);
+                p = fmaf(half_bits_to_float(a.val[j]), x_bits_to_float(ox[a.col[j]], xbf), p);
             const float tot = wave_sum(fmaf(ow, p, sum[u]));
             if (lane == 0 && row0 + u < row_end) store_out(a.y, row0 + u, tot, a.y_f32 != 0, a.y_bf16 != 0);
         }
@@ -335,6 +344,7 @@ hipError_t launch_decode_combine(int bits, const DecodeArgs &d, int T, const flo
     a.rows_per_wave = 1;
     a.y_f32 = (int)y_f32;
     a.y_bf16 = (int)y_bf16;
+    a.x_bf16 = (int)d.x_bf16;
     switch (bits) {
     case 2: return launch_combine_b<2>(a, s);
     case 3: return launch_combine_b<3>(a, s);

@@ -44,8 +44,11 @@ __global__ __launch_bounds__(kRowsThreads) void decode_rows_kernel(DecodeArgs a)
     const uint16_t *x = a.x + (int64_t)slot * a.x_stride;
 
     // a1: stage the activation row.
-    for (uint32_t i = tid; i < K / 8; i += kRowsThreads)
-        reinterpret_cast<uint4 *>(xs)[i] = reinterpret_cast<const uint4 *>(x)[i];
+    for (uint32_t i = tid; i < K / 8; i += kRowsThreads) {
+        uint4 v = reinterpret_cast<const uint4 *>(x)[i];
+        if (a.x_bf16) v = make_uint4(bf16x2_to_f16x2(v.x), bf16x2_to_f16x2(v.y), bf16x2_to_f16x2(v.z), bf16x2_to_f16x2(v.w));
+        reinterpret_cast<uint4 *>(xs)[i] = v;
+    }
     // a2: V2a library -> LDS once per workgroup.
     if constexpr (MODE == 1) {
         const uint16_t *lib = a.cb + (size_t)e * a.L * ENT;

@@ -1,10 +1,8 @@
 // Streaming fused decode, plain variant, plus what the variants share on the
-// host side: shape support, split-K launch and its sum kernel, the fp32 scratch
-// ring, the unfused SiLU(gate) * up kernel.  The kernel itself is in
+// host side: shape support, split-K launch and its sum kernel, the unfused
+// SiLU(gate) * up kernel.  The kernel itself is in
 // xfp_decode_stream.inc.h.
 #include "xfp_decode_stream.inc.h"
-
-#include <atomic>
 
 namespace xfp {
 
@@ -31,13 +29,8 @@ hipError_t launch_decode_stream(int bits, int mode, bool y_f32, const DecodeArgs
 // Rows longer than the streaming kernel holds in registers (K > 16384) are cut
 // into S equal slices (S divides K / 128, a slice is at most 8192 columns so
 // that four waves fit a SIMD); grid z = slice.  Slice z writes fp32 partial sums
-// to its own plane of a file-scope buffer and a second kernel adds the planes in
-// slice order: deterministic, no atomics.  A ring of kSplitSlots buffers lets
-// that many split-K calls overlap on one GPU before a slot is reused.
-constexpr uint32_t kSplitFloats = 1u << 20;            // S * slots * N per call (4 MB per ring slot)
-constexpr int kSplitSlots = 4;
-__device__ __align__(256) float g_partial[kSplitSlots][kSplitFloats];
-
+// to its own part of the call's scratch plane and a second kernel adds the parts
+// in slice order: deterministic, no atomics.
 __global__ __launch_bounds__(256) void splitk_sum_kernel(const float *part, uint32_t S, uint32_t N, uint32_t slots,
                                                          void *y, int64_t y_stride, int y_f32, int y_bf16)
 {
@@ -56,40 +49,17 @@ int splitk_slices(int bits, int mode, uint32_t N, uint32_t K, uint32_t L, int sl
     for (uint32_t S = (K + 8191) / 8192; S <= 16; ++S) {
         if (G % S != 0) continue;
         if (!stream_supports(bits, mode, K / S, L)) return 0;
-        if ((uint64_t)S * (uint64_t)slots * N > kSplitFloats) return 0;
+        if ((uint64_t)S * (uint64_t)slots * N > kPlaneFloats) return 0;
         return (int)S;
     }
     return 0;
 }
 
-// One slot of the ring of fp32 scratch planes (kSplitFloats floats each), or
-// nullptr with *err set.
-float *scratch_plane(hipError_t *err)
-{
-    static std::atomic<void *> ring[kMaxDevices];      // device address of g_partial, per device (each holds its own copy)
-    const int dev = current_device();
-    if (dev < 0) {
-        *err = hipErrorInvalidDevice;
-        return nullptr;
-    }
-    void *p = ring[dev].load(std::memory_order_relaxed);
-    if (!p) {
-        *err = hipGetSymbolAddress(&p, HIP_SYMBOL(g_partial));
-        if (*err != hipSuccess) return nullptr;
-        ring[dev].store(p, std::memory_order_relaxed);
-    }
-    static std::atomic<unsigned> next_slot{0};
-    return static_cast<float *>(p) + (size_t)(next_slot.fetch_add(1, std::memory_order_relaxed) % kSplitSlots) * kSplitFloats;
-}
-
-uint32_t scratch_plane_floats() { return kSplitFloats; }
-
+// part: an fp32 scratch plane of kPlaneFloats floats (S * slots * N of them are used)
 hipError_t launch_decode_splitk(int bits, int mode, bool y_f32, const DecodeArgs &a, int slots, int slices,
-                                hipStream_t s)
+                                float *part, hipStream_t s)
 {
-    hipError_t perr = hipSuccess;
-    float *part = scratch_plane(&perr);
-    if (!part) return perr;
+    if (!part) return hipErrorInvalidValue;
     DecodeArgs c = a;
     c.k_slices = (uint32_t)slices;
     c.row_words = a.K / 32 * (uint32_t)bits;

@@ -355,6 +355,15 @@ void decode_stream_kernel(DecodeArgs a, int y_f32)
             *(lds_u32_w_t *)(uintptr_t)(lds_base + B * Fmt::kRowBytes + i * 4) = 0u;
     }
     if (row_begin >= N) return;
+    // bf16 activations: converted in place, once per wave (they were requested ahead
+    // of the index words, so this waits for nothing that streams)
+    const bool xbf = a.x_bf16 != 0;
+    if (xbf) {
+#pragma unroll
+        for (int c = 0; c < NCH; ++c)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) xr[c][i] = bf16x2_to_f16x2(xr[c][i]);
+    }
 
     // One batch of rows.  FIRST: its index words were loaded in the prologue.
     auto pass = [&](auto first, uint32_t rb) {
@@ -531,22 +540,22 @@ void decode_stream_kernel(DecodeArgs a, int y_f32)
         // a7 (fold): add each outlier product to the row that owns the entry.
         {
             if constexpr (RPC == 1) {
-                const float p = half_bits_to_float((uint16_t)oval[0]) * half_bits_to_float(oxv[0]);
+                const float p = half_bits_to_float((uint16_t)oval[0]) * x_bits_to_float(oxv[0], xbf);
 #pragma unroll
                 for (int u = 0; u < U; ++u) sum[u] += (oj[0] >= olo[u] && oj[0] < ohi[u]) ? p : 0.f;
                 const int32_t ostep = FI ? 32 : kWave;
                 for (int32_t jj = oj[0] + ostep; jj < oj1[0]; jj += ostep) {     // more entries than lanes: rare
-                    const float q = half_bits_to_float(a.val[jj]) * half_bits_to_float(x[a.col[jj]]);
+                    const float q = half_bits_to_float(a.val[jj]) * x_bits_to_float(x[a.col[jj]], xbf);
 #pragma unroll
                     for (int u = 0; u < U; ++u) sum[u] += (jj >= olo[u] && jj < ohi[u]) ? q : 0.f;
                 }
             } else {
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    const float p = half_bits_to_float((uint16_t)oval[u]) * half_bits_to_float(oxv[u]);
+                    const float p = half_bits_to_float((uint16_t)oval[u]) * x_bits_to_float(oxv[u], xbf);
                     sum[u] += oj[u] < oj1[u] ? p : 0.f;
                     for (int32_t jj = oj[u] + LPR; jj < oj1[u]; jj += LPR)         // > LPR entries: rare
-                        sum[u] = fmaf(half_bits_to_float(a.val[jj]), half_bits_to_float(x[a.col[jj]]), sum[u]);
+                        sum[u] = fmaf(half_bits_to_float(a.val[jj]), x_bits_to_float(x[a.col[jj]], xbf), sum[u]);
                 }
             }
         }

@@ -62,6 +62,32 @@ __device__ __forceinline__ float half_bits_to_float(uint16_t h)
     return (float)__builtin_bit_cast(_Float16, h);
 }
 
+// bf16 activations (paper section 5: the kernel takes bf16).  A bf16 value is exact
+// in fp32; the rounding to fp16 (nearest even) is exact inside fp16's normal
+// range, rounds to a multiple of 2^-24 below 2^-14 and saturates at +-65504 (an
+// activation that large would otherwise become an infinity and poison every
+// output); NaN stays NaN.  Every kernel converts with these two functions, so a
+// call with bf16 x gives bit for bit what the same call gives on the converted x.
+__device__ __forceinline__ _Float16 bf16_bits_to_half(uint32_t b)      // b: bf16 pattern in the low 16 bits
+{
+    float f = __builtin_bit_cast(float, b << 16);
+    f = f != f ? f : fminf(fmaxf(f, -65504.f), 65504.f);
+    return (_Float16)f;
+}
+__device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t w)
+{
+    float lo = __builtin_bit_cast(float, w << 16), hi = __builtin_bit_cast(float, w & 0xFFFF0000u);
+    lo = lo != lo ? lo : fminf(fmaxf(lo, -65504.f), 65504.f);
+    hi = hi != hi ? hi : fminf(fmaxf(hi, -65504.f), 65504.f);
+    const _Float16 l16 = (_Float16)lo, h16 = (_Float16)hi;
+    return (uint32_t)__builtin_bit_cast(uint16_t, l16) | ((uint32_t)__builtin_bit_cast(uint16_t, h16) << 16);
+}
+// one activation as fp32, from its fp16 or bf16 pattern
+__device__ __forceinline__ float x_bits_to_float(uint16_t h, bool bf16)
+{
+    return bf16 ? (float)bf16_bits_to_half(h) : (float)__builtin_bit_cast(_Float16, h);
+}
+
 template <int CTRL>
 __device__ __forceinline__ float dpp_add(float v)
 {

@@ -36,7 +36,51 @@ struct DecodeArgs {
     // [fuse_half, 2 fuse_half) up rows; y gets fuse_half values per slot.
     uint32_t fuse_half;
     uint32_t y_bf16;       // the 16-bit output type is bf16 instead of fp16
+    uint32_t x_bf16;       // x holds bf16 values; every kernel converts them to fp16 as it loads them
 };
+
+// Device memory a call may need beyond its inputs and outputs.  One call gets ONE
+// workspace and carves every plane it needs out of it, so a call never holds
+// more than one unit of whatever the workspaces come from (a ring slot, or the
+// static array of the entry point that allocates nothing).
+constexpr uint32_t kPlaneFloats = 1u << 20;        // floats of an fp32 scratch plane (4 MB)
+constexpr int kXtMaxK = 32768;                     // longest row the batched kernel takes
+constexpr int kXtTokens = 16;                      // tokens per launch of the batched kernel
+// Two re-laid copies of the 16 x K activations of a batched launch:
+//   xt [k][16 tokens]           the outlier products read the 16 tokens of one column as 32 bytes;
+//   xb [k / 8][16 tokens][8 k]  the B operand of lane (m, q) for a k block is 16 contiguous bytes and
+//                               the 64 lanes of a wave read 1 KB contiguous (from the row-major x the
+//                               same load touches 64 different cache lines).
+// Tokens >= M are zero in both.
+struct XCopies {
+    uint16_t xt[kXtMaxK * kXtTokens];
+    uint16_t xb[kXtMaxK * kXtTokens];
+};
+struct WorkspaceLayout {
+    XCopies xc;                  // batched kernel: re-laid activations (2 MB)
+    float epi[kPlaneFloats];     // unfused epilogues: per-slot fp32 results
+    float part[kPlaneFloats];    // split-K: per-slice fp32 partial sums
+};
+struct Workspace {
+    XCopies *xc;
+    float *epi;
+    float *part;
+};
+inline Workspace workspace_at(void *base)
+{
+    WorkspaceLayout *l = static_cast<WorkspaceLayout *>(base);
+    return Workspace{&l->xc, l->epi, l->part};
+}
+// One slot of the static ring of workspaces on the current device.  Calls on a
+// stream that is being captured into a graph cycle through slots of their own,
+// which eager calls never take.
+hipError_t ring_workspace(hipStream_t s, Workspace *out);
+// Resolves the ring's address on the current device (no-op once done).
+hipError_t ring_resolve();
+// Pure slot arithmetic of the ring (exposed for a host-only test): ticket-th call
+// of its kind -> slot index.
+int ring_slot_index(unsigned ticket, bool capturing);
+int ring_slots(bool capturing);
 
 // Index of the current device for per-device host-side state, or -1.
 inline int current_device()
@@ -58,7 +102,7 @@ hipError_t launch_decode_stream(int bits, int mode, bool y_f32, const DecodeArgs
 // not fit (then the general kernel runs).
 int splitk_slices(int bits, int mode, uint32_t N, uint32_t K, uint32_t L, int slots);
 hipError_t launch_decode_splitk(int bits, int mode, bool y_f32, const DecodeArgs &a, int slots, int slices,
-                                hipStream_t s);
+                                float *part, hipStream_t s);
 // y[slot][n] = sum over slices z, in order, of part[z][slot][n]
 hipError_t launch_splitk_sum(const float *part, uint32_t slices, uint32_t N, int slots, void *y, int64_t y_stride,
                              bool y_f32, bool y_bf16, hipStream_t s);
@@ -67,10 +111,8 @@ hipError_t launch_splitk_sum(const float *part, uint32_t slices, uint32_t N, int
 // above 8192 columns in slices whose partial sums go through a scratch plane).
 bool batch_supports(int bits, int mode, uint32_t L, uint32_t N, uint32_t K, int M);
 bool batch_is_split(uint32_t K);
-hipError_t launch_decode_batch(int bits, int mode, const DecodeArgs &a, int M, bool y_f32, float *part, hipStream_t s);
-// fp32 scratch plane from a small static ring (split-K partial sums, unfused epilogues)
-float *scratch_plane(hipError_t *err);
-uint32_t scratch_plane_floats();
+hipError_t launch_decode_batch(int bits, int mode, const DecodeArgs &a, int M, bool y_f32, float *part, XCopies *xc,
+                               hipStream_t s);
 hipError_t launch_silu_mul(const float *y, uint32_t half, int slots, void *h, int64_t h_stride, bool h_f32,
                            bool h_bf16, hipStream_t s);
 // Down projection with the router's weighted sum over the slots in one launch (V2, T <= 8, T * K <= 16384)
@@ -79,7 +121,8 @@ hipError_t launch_decode_combine(int bits, const DecodeArgs &d, int T, const flo
                                  hipStream_t s);
 hipError_t launch_moe_combine(const float *part, const float *w, uint32_t N, int slots, void *y, bool y_f32,
                               bool y_bf16, hipStream_t s);
-// bf16 [rows][ld] -> fp16 [rows][K] (exact inside fp16's normal range, saturating beyond it)
+// bf16 [rows][ld] -> fp16 [rows][K] (exact inside fp16's normal range, saturating beyond it);
+// the stand-alone form of the conversion every decode kernel applies when x_bf16 is set
 hipError_t launch_bf16_to_f16(const void *src, int64_t ld, void *dst, uint32_t rows, uint32_t K, hipStream_t s);
 // 3-bit indices, ten per uint32 [rows][ceil(K/10)] -> dense stream [rows][K*3/32]
 hipError_t launch_repack_word10(const uint32_t *src, uint64_t rows, uint32_t K, uint32_t *dst, hipStream_t s);

@@ -96,6 +96,27 @@ def test_unsupported_format():
     assert gemv(desc(), dt=0x200) == -3                        # unknown flag (0x100: x is bf16)
 
 
+def test_rows_no_kernel_can_take_are_rejected_up_front():
+    """Longer than the streaming kernel holds, no split into equal slices (a prime number of groups),
+    and too long for the general kernel to stage in LDS: refused before anything is launched."""
+    assert gemv(desc(K=128 * 1009), ldx=128 * 1009) == -3
+    assert gemv(desc(K=128 * 1009, bits=3), ldx=128 * 1009) == -3
+    assert moe(desc(E=4, K=128 * 1009), xs=128 * 1009) == -3
+    assert "too long" in xfp.xfp_strerror(-3) and "bf16" in xfp.xfp_strerror(-3)
+
+
+def test_ring_slot_arithmetic():
+    """Eager calls cycle through slots 0..3, calls recorded into a graph through 4..7; the two never meet,
+    and a call takes one slot however many planes it uses (the ticket counter advances once per call)."""
+    lib = xfp.load_library()
+    lib.xfp_ring_slot.argtypes = [ctypes.c_uint, ctypes.c_int]
+    eager = [lib.xfp_ring_slot(t, 0) for t in range(16)]
+    rec = [lib.xfp_ring_slot(t, 1) for t in range(16)]
+    assert eager == [0, 1, 2, 3] * 4 and rec == [4, 5, 6, 7] * 4
+    assert lib.xfp_ring_slot(0xFFFFFFFF, 0) == 3 and lib.xfp_ring_slot(0xFFFFFFFF, 1) == 7     # wrap-around stays in range
+    assert not set(eager) & set(rec)
+
+
 def test_alignment_errors():
     assert gemv(desc(indices=FAKE + 4)) == -4
     assert gemv(desc(codebooks=FAKE + 2)) == -4
