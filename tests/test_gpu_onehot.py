@@ -84,7 +84,7 @@ def test_streaming_kernel_one_hot_sweep(mode, bits, N, K, dens, T):
 
 def test_streaming_kernel_one_hot_single_call_per_column():
     """The plain xfp_gemv M = 1 call (one slot, the batch size of a small launch), a call per column."""
-    for mode, bits, N, K in ((V2, 4, 7, 1024), (V2, 3, 9, 640), (V2A, 4, 4, 2176)):
+    for mode, bits, N, K in ((V2, 4, 8, 1024), (V2, 3, 12, 640), (V2A, 4, 4, 2176)):
         W = xi.random_weights(mode, bits, N, K, density=0.003, seed=7100 + K)
         dW = xfp.upload(W)
         want = expected_dense(W)
@@ -166,8 +166,8 @@ def test_gate_up_form_one_hot_sweep(mode, bits, half, K):
 
 
 # ------------------------------------------------------------------ combine kernel (weighted sum over slots)
-@pytest.mark.parametrize("bits,N,K,E,T", [(3, 4, 1024, 5, 8), (4, 3, 640, 3, 5), (2, 4, 512, 4, 8), (4, 2, 2048, 9, 8),
-                                          (3, 5, 384, 2, 7), (4, 4, 1024, 6, 2)])
+@pytest.mark.parametrize("bits,N,K,E,T", [(3, 4, 1024, 5, 8), (4, 4, 640, 3, 5), (2, 4, 512, 4, 8), (4, 4, 2048, 9, 8),
+                                          (3, 8, 384, 2, 7), (4, 4, 1024, 6, 2)])
 def test_combine_kernel_one_hot_sweep(bits, N, K, E, T):
     """One-hot router weights and one one-hot activation row per slot: slot t0 of the call reads column k of its
     expert, every other slot is multiplied by an exact zero.  Each call checks column k of T different
