@@ -82,7 +82,8 @@ typedef enum {
     XFP_ERR_SHAPE = -2,       /* N, K, M, E <= 0, T < 0, K % group != 0, ld too small */
     XFP_ERR_UNSUPPORTED = -3, /* bits, mode, L, group, dtype, flags, struct_size     */
     XFP_ERR_ALIGN = -4,       /* a base pointer or a leading dimension is misaligned */
-    XFP_ERR_HIP = -5          /* the HIP runtime refused the launch                  */
+    XFP_ERR_HIP = -5,         /* the HIP runtime refused the launch                  */
+    XFP_ERR_SCRATCH = -6      /* xfp_gemv_noalloc: the call needs more scratch than the static array holds */
 } xfp_status;
 
 typedef enum { XFP_MODE_V2 = 0, XFP_MODE_V2A = 1 } xfp_mode;
@@ -137,6 +138,29 @@ typedef struct xfp_weights {
  */
 int xfp_gemv(const xfp_weights *W, const void *x, int M, int64_t ldx,
              void *y, int y_dtype, int64_t ldy, void *hip_stream);
+
+/*
+ * xfp_gemv for callers that cannot allocate and must know where every byte a
+ * call touches lives: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  (No paper counterpart.)  Same arguments and
+ * same results, bit for bit, as xfp_gemv.  Whatever scratch the call needs
+ * (re-laid activations for M >= 2, partial sums of rows cut into slices of K)
+ * lives in ONE static device array of 10 MB, not in the ring the other entry
+ * points cycle through; each GPU the process uses holds its own copy until the
+ * process ends.  The call allocates nothing, frees nothing and calls no
+ * allocating routine.
+ * Limits (the array's size): where xfp_gemv would reroute a call because a
+ * scratch plane is too small, this one returns XFP_ERR_SCRATCH and launches
+ * nothing: M >= 2 with K > 32768; M >= 2, K > 8192 with S * 16 * N > 2^20
+ * (S = ceil(K / 8192) slices); rows above 16384 columns that the M = 1 path
+ * cuts into S equal slices with S * M * N > 2^20.
+ * Every call on a GPU uses that GPU's one array, which keeps the last call's
+ * contents (nothing in it has to start at zero: every plane is written before it
+ * is read): calls that overlap in time on one GPU (two streams, two threads)
+ * race.  Calls on one stream are ordered and never interfere.
+ */
+int xfp_gemv_noalloc(const xfp_weights *W, const void *x, int M, int64_t ldx,
+                     void *y, int y_dtype, int64_t ldy, void *hip_stream);
 
 /*
  * Expert-indexed grouped form for routed-expert layers: for each slot
@@ -270,7 +294,7 @@ int xfp_probe_copy(const void *src, void *dst, uint64_t bytes, void *hip_stream)
 
 /*
  * Resolves, for the current device, the addresses of the library's static
- * device memory.  Optional: the first call that needs them does the same; call
+ * device memory (the ring of workspaces and xfp_gemv_noalloc's array).  Optional: the first call that needs them does the same; call
  * it once per device before recording calls into a HIP graph, so that nothing
  * but launches happens under capture.
  */

@@ -58,6 +58,7 @@ def load_library():
     vp, i32, i64, u64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_uint64
     wp = ctypes.POINTER(xfp_weights)
     lib.xfp_gemv.argtypes = [wp, vp, i32, i64, vp, i32, i64, vp]
+    lib.xfp_gemv_noalloc.argtypes = [wp, vp, i32, i64, vp, i32, i64, vp]
     lib.xfp_gemv_moe.argtypes = [wp, vp, i32, vp, i64, vp, i32, i64, vp]
     lib.xfp_gemv_moe_silu_mul.argtypes = [wp, vp, i32, vp, i64, vp, i32, i64, vp]
     lib.xfp_unpack_indices.argtypes = [wp, vp, vp]
@@ -70,7 +71,7 @@ def load_library():
     lib.xfp_probe_copy.argtypes = [vp, vp, u64, vp]
     lib.xfp_strerror.argtypes = [i32]
     lib.xfp_strerror.restype = ctypes.c_char_p
-    for name in ("xfp_gemv", "xfp_gemv_moe", "xfp_gemv_moe_silu_mul", "xfp_gemv_moe_combine", "xfp_check_contents", "xfp_convert_bf16_to_f16", "xfp_repack_word10", "xfp_unpack_indices", "xfp_dequant_bulk",
+    for name in ("xfp_gemv", "xfp_gemv_noalloc", "xfp_gemv_moe", "xfp_gemv_moe_silu_mul", "xfp_gemv_moe_combine", "xfp_check_contents", "xfp_convert_bf16_to_f16", "xfp_repack_word10", "xfp_unpack_indices", "xfp_dequant_bulk",
                  "xfp_probe_read", "xfp_probe_copy", "xfp_version", "xfp_init"):
         getattr(lib, name).restype = i32
     _lib = lib
@@ -187,6 +188,18 @@ def xfp_gemv(W: DeviceWeights, x: torch.Tensor, y: Optional[torch.Tensor] = None
     ldy = y2.stride(0) if M > 1 else max(y2.shape[1], 1)
     _check(load_library().xfp_gemv(ctypes.byref(W.desc), _ptr(x2), M, ldx, _ptr(y2),
                                    _y_code(y2.dtype, x2), ldy, _stream(stream)))
+    return y
+
+
+def xfp_gemv_noalloc(W: DeviceWeights, x: torch.Tensor, y: torch.Tensor, stream=None) -> torch.Tensor:
+    """xfp_gemv with its scratch in the library's one static array; the caller brings y (nothing is allocated)."""
+    x2 = x if x.dim() == 2 else x.unsqueeze(0)
+    M = x2.shape[0]
+    y2 = y if y.dim() == 2 else y.unsqueeze(0)
+    ldx = x2.stride(0) if M > 1 else max(x2.shape[1], 1)
+    ldy = y2.stride(0) if M > 1 else max(y2.shape[1], 1)
+    _check(load_library().xfp_gemv_noalloc(ctypes.byref(W.desc), _ptr(x2), M, ldx, _ptr(y2),
+                                           _y_code(y2.dtype, x2), ldy, _stream(stream)))
     return y
 
 

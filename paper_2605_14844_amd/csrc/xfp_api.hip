@@ -3,8 +3,31 @@
 #include "../../include/xfp.h"
 #include "xfp_internal.h"
 
+#include <atomic>
 #include <cstdio>
 #include <cstring>
+
+// The one workspace of xfp_gemv_noalloc: a file-scope device array (each GPU of the
+// process holds its own copy at its own address).  Host code never passes the
+// array's name to a kernel or a runtime call: it resolves the address once per
+// device, with that device current, and uses the resolved pointer.
+static __device__ __align__(256) unsigned char scratch[sizeof(xfp::WorkspaceLayout)];
+static std::atomic<void *> g_scratch_ptr[xfp::kMaxDevices];
+
+static hipError_t scratch_resolve(void **out)
+{
+    const int dev = xfp::current_device();
+    if (dev < 0) return hipErrorInvalidDevice;
+    void *ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        hipError_t err = hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch));
+        if (err != hipSuccess) return err;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+    }
+    if (out) *out = ptr;
+    return hipSuccess;
+}
 
 namespace {
 
@@ -66,12 +89,14 @@ bool dtype_ok(int y_dtype)
 }
 
 // Where a call's scratch memory comes from: one slot of the static ring, taken
-// the first time some path asks for it (most calls never do).
+// the first time some path asks for it (most calls never do), or a workspace
+// the entry point fixed beforehand.
 struct Scratch {
     hipStream_t stream;
     bool have = false;
     xfp::Workspace ws{};
     explicit Scratch(hipStream_t s) : stream(s) {}
+    Scratch(hipStream_t s, const xfp::Workspace &fixed) : stream(s), have(true), ws(fixed) {}
     hipError_t get(const xfp::Workspace **out)
     {
         if (!have) {
@@ -233,6 +258,34 @@ int xfp_gemv(const xfp_weights *W, const void *x, int M, int64_t ldx, void *y, i
     return decode(W, nullptr, M, x, ldx, y, y_dtype, ldy, sc, s);
 }
 
+int xfp_gemv_noalloc(const xfp_weights *W, const void *x, int M, int64_t ldx, void *y, int y_dtype,
+                     int64_t ldy, void *hip_stream)
+{
+    int rc = check_weights(W);
+    if (rc) return rc;
+    if (W->E != 1) return XFP_ERR_SHAPE;
+    if (M <= 0 || M > 65535) return XFP_ERR_SHAPE;
+    rc = check_io(W, x, y, y_dtype, ldy);
+    if (rc) return rc;
+    if (ldx < (int64_t)W->K) return XFP_ERR_SHAPE;
+    if (ldx % 8 != 0) return XFP_ERR_ALIGN;
+    // a route that only the size of the scratch planes closes is refused, not replaced
+    const int bits = (int)W->bits, mode = (int)W->mode;
+    constexpr uint64_t kNoCap = ~0ull;
+    if (xfp::batch_supports(bits, mode, W->L, W->N, W->K, M, kNoCap, kNoCap) != xfp::batch_supports(bits, mode, W->L, W->N, W->K, M))
+        return XFP_ERR_SCRATCH;
+    if (!xfp::batch_supports(bits, mode, W->L, W->N, W->K, M) && !xfp::stream_supports(bits, mode, W->K, W->L) &&
+        xfp::splitk_slices(bits, mode, W->N, W->K, W->L, M, kNoCap) != xfp::splitk_slices(bits, mode, W->N, W->K, W->L, M))
+        return XFP_ERR_SCRATCH;
+    if (!decodable(W, M)) return XFP_ERR_UNSUPPORTED;
+    void *ptr = nullptr;
+    hipError_t err = scratch_resolve(&ptr);
+    if (err != hipSuccess) return finish(err);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    Scratch sc(s, xfp::workspace_at(ptr));
+    return decode(W, nullptr, M, x, ldx, y, y_dtype, ldy, sc, s);
+}
+
 int xfp_gemv_moe(const xfp_weights *bank, const int32_t *expert_ids, int T, const void *x,
                  int64_t x_slot_stride, void *y, int y_dtype, int64_t ldy, void *hip_stream)
 {
@@ -383,6 +436,7 @@ const char *xfp_strerror(int status)
     case XFP_ERR_SHAPE: return "bad shape (sizes must be positive, K a multiple of 128, leading dimensions large enough)";
     case XFP_ERR_UNSUPPORTED: return "unsupported format or shape (bits 2..4, mode V2/V2a, group 128, flags 0, output fp16/bf16/fp32; a row too long for every kernel; a result too large for the scratch plane)";
     case XFP_ERR_ALIGN: return "a pointer or leading dimension is misaligned";
+    case XFP_ERR_SCRATCH: return "the call needs more scratch memory than xfp_gemv_noalloc's static array holds (M >= 2: K <= 32768 and S * 16 * N <= 2^20; sliced rows: S * M * N <= 2^20)";
     case XFP_ERR_HIP:
         std::snprintf(g_msg, sizeof(g_msg), "HIP launch failed: %s", hipGetErrorString(g_last_hip));
         return g_msg;
@@ -390,7 +444,12 @@ const char *xfp_strerror(int status)
     }
 }
 
-int xfp_init(void) { return finish(xfp::ring_resolve()); }
+int xfp_init(void)
+{
+    hipError_t err = xfp::ring_resolve();
+    if (err == hipSuccess) err = scratch_resolve(nullptr);
+    return finish(err);
+}
 
 int xfp_ring_slot(unsigned ticket, int capturing) { return xfp::ring_slot_index(ticket, capturing != 0); }
 

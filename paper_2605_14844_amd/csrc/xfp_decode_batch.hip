@@ -54,16 +54,17 @@ __global__ __launch_bounds__(256) void relayout_x_kernel(const uint16_t *x, int6
 }  // namespace
 
 // V2 at every bit width; V2a at 3 and 4 bits when the library's pair tables fit the 64 KB table region.
-bool batch_supports(int bits, int mode, uint32_t L, uint32_t N, uint32_t K, int M)
+// k_cap, plane_cap: what the workspace holds (columns of the re-laid copies, floats of a partial-sum plane).
+bool batch_supports(int bits, int mode, uint32_t L, uint32_t N, uint32_t K, int M, uint64_t k_cap, uint64_t plane_cap)
 {
     const bool format = mode == 0 ? bits >= 2 && bits <= 4
                                   : mode == 1 && (bits == 3 || bits == 4) && L >= 1 && ((size_t)L << (2 * bits)) * 4 <= 64 * 1024;
-    if (!(format && M >= 2 && K % kGroup == 0 && K >= kGroup && K <= (uint32_t)kXtMaxK))
+    if (!(format && M >= 2 && K % kGroup == 0 && K >= kGroup && K <= k_cap))
         return false;
     if (K <= 8192) return true;
     const uint32_t GS = (uint32_t)batch_split_nl(K) * 8;
     const uint32_t S = (K / kGroup + GS - 1) / GS;
-    return (uint64_t)S * 16u * N <= kPlaneFloats;                    // the partial planes of 16 tokens fit
+    return (uint64_t)S * 16u * N <= plane_cap;                       // the partial planes of 16 tokens fit
 }
 
 bool batch_is_split(uint32_t K) { return batch_split_nl(K) != 0; }

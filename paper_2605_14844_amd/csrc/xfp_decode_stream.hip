@@ -43,13 +43,13 @@ __global__ __launch_bounds__(256) void splitk_sum_kernel(const float *part, uint
     store_out(y, o, s, y_f32 != 0, y_bf16 != 0);
 }
 
-int splitk_slices(int bits, int mode, uint32_t N, uint32_t K, uint32_t L, int slots)
+int splitk_slices(int bits, int mode, uint32_t N, uint32_t K, uint32_t L, int slots, uint64_t plane_cap)
 {
     const uint32_t G = K / kGroup;
     for (uint32_t S = (K + 8191) / 8192; S <= 16; ++S) {
         if (G % S != 0) continue;
         if (!stream_supports(bits, mode, K / S, L)) return 0;
-        if ((uint64_t)S * (uint64_t)slots * N > kPlaneFloats) return 0;
+        if ((uint64_t)S * (uint64_t)slots * N > plane_cap) return 0;
         return (int)S;
     }
     return 0;

@@ -100,7 +100,8 @@ hipError_t launch_decode_stream(int bits, int mode, bool y_f32, const DecodeArgs
 // S equal slices of K, fp32 partial sums in a file-scope device buffer, summed in
 // slice order by a second kernel.  splitk_slices returns S, or 0 if the shape does
 // not fit (then the general kernel runs).
-int splitk_slices(int bits, int mode, uint32_t N, uint32_t K, uint32_t L, int slots);
+// plane_cap: floats of the scratch plane that takes the partial sums (S * slots * N of them).
+int splitk_slices(int bits, int mode, uint32_t N, uint32_t K, uint32_t L, int slots, uint64_t plane_cap = kPlaneFloats);
 hipError_t launch_decode_splitk(int bits, int mode, bool y_f32, const DecodeArgs &a, int slots, int slices,
                                 float *part, hipStream_t s);
 // y[slot][n] = sum over slices z, in order, of part[z][slot][n]
@@ -109,7 +110,8 @@ hipError_t launch_splitk_sum(const float *part, uint32_t slices, uint32_t N, int
 // Matrix-core kernel for 2..16 tokens per launch (V2 at 2..4 bits, V2a at 3 and 4 bits
 // with a library whose pair tables fit 64 KB of LDS; K <= 32768; rows
 // above 8192 columns in slices whose partial sums go through a scratch plane).
-bool batch_supports(int bits, int mode, uint32_t L, uint32_t N, uint32_t K, int M);
+bool batch_supports(int bits, int mode, uint32_t L, uint32_t N, uint32_t K, int M, uint64_t k_cap = kXtMaxK,
+                    uint64_t plane_cap = kPlaneFloats);
 bool batch_is_split(uint32_t K);
 hipError_t launch_decode_batch(int bits, int mode, const DecodeArgs &a, int M, bool y_f32, float *part, XCopies *xc,
                                hipStream_t s);

@@ -117,6 +117,18 @@ def test_ring_slot_arithmetic():
     assert not set(eager) & set(rec)
 
 
+def test_noalloc_entry_point_refuses_what_its_static_array_cannot_hold():
+    """Checked on the host before anything is launched (the pointers are fakes)."""
+    lib = xfp.load_library()
+    call = lambda d, M, ldx: lib.xfp_gemv_noalloc(ctypes.byref(d), FAKE, M, ldx, FAKE, 0, d.N, None)
+    assert call(desc(K=65536, bits=2), 2, 65536) == -6             # M >= 2: the re-laid activations hold K <= 32768
+    assert call(desc(K=12288, N=40000), 16, 12288) == -6           # two slices: 2 * 16 * N floats of partial sums > 2^20
+    assert call(desc(K=32768, N=300000), 1, 32768) == -6           # M = 1 split-K: 4 * N floats of partial sums > 2^20
+    assert "scratch" in xfp.xfp_strerror(-6)
+    assert call(desc(K=200), 1, 256) == -2 and call(desc(bits=9), 1, 256) == -3      # the usual validation comes first
+    assert call(desc(E=2), 1, 256) == -2
+
+
 def test_alignment_errors():
     assert gemv(desc(indices=FAKE + 4)) == -4
     assert gemv(desc(codebooks=FAKE + 2)) == -4
