@@ -3,14 +3,19 @@
 
 A step is one pass of the whole hot path over one batch: one xfp_gemv call
 (workloads 1, 2, 3, 5) or one gate_up + one down xfp_gemv_moe call (workload
-4).  Two more configurations measure what was added beyond the five: 6 (the
-expert layer of workload 4 with both epilogues fused) and 7 (split-K).  Weights are already resident in HBM; successive steps walk a ring of
-distinct device copies whose total size exceeds the last-level cache, so the
-weights of a step are never cache-resident.  The K timed steps are recorded
-into one HIP graph and replayed once between two events on the launch stream
-(the eager launch rate from Python is reported beside it).
+4).  More configurations measure what was added beyond the five: 6 (the
+expert layer of workload 4 with both epilogues fused), 7 (split-K), 8-10 (the
+batched kernel's other forms), 11 (2 bits).  Weights are already resident in
+HBM; successive steps walk a ring of distinct device copies whose total size
+exceeds the last-level cache, and 768 MB are streamed through the chip between
+the untimed and the timed replay, so the weights of a step are never
+cache-resident, whatever --steps is.  The K timed steps are recorded into one
+HIP graph and replayed once between two events on the launch stream (the eager
+launch rate from Python is reported beside it).
 
-Prints ONE JSON line.  value = algorithmic bytes per step / time per step.
+Prints ONE JSON line.  value = algorithmic bytes per step / time per step of
+the headline workload (2); the default run adds the same figures for workloads
+1, 3, 4, 5 and the 2-bit matrix under "configs".
 """
 from __future__ import annotations
 
@@ -35,8 +40,11 @@ def parse_args():
     p.add_argument("--config", type=int, default=2,
                    help="workload 1..5 (default 2, the headline); beyond the five: 6 = workload 4 as a whole expert "
                         "layer with both epilogues fused, 7 = a long-row matrix (8192x28672, 4-bit, M=1) through split-K, "
-                        "8 = the same matrix with 16 tokens, 9 = workload 5's shape at 3 bits, 10 = the same as V2a")
+                        "8 = the same matrix with 16 tokens, 9 = workload 5's shape at 3 bits, 10 = the same as V2a, "
+                        "11 = workload 2's shape at 2 bits")
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--single", action="store_true", help="time only --config (the default run of workload 2 also "
+                   "times workloads 1, 3, 4, 5 and a 2-bit matrix and reports them under \"configs\")")
     p.add_argument("--no-graph", action="store_true", help="time eager launches instead of a graph")
     p.add_argument("--no-plain-read", action="store_true", help="skip the read-only ceiling measurement")
     p.add_argument("--ring-bytes", type=int, default=RING_BYTES)
@@ -174,6 +182,27 @@ def build_workload(cfg: int, ring_bytes: int):
         return dict(name="V2 8192x28672 b4 M=1 (rows longer than 16384: split-K, two launches)", step=step,
                     bytes=nbytes, ring=R, oracle=oracle_once, launches=2, kernel_bytes=nbytes,
                     launch_bytes=[nbytes], keep=(ring, xd, y), M=1, N=W.N, K=W.K, bits=4, mode=0)
+    if cfg == 11:
+        W = xi.random_weights(xi.MODE_V2, 2, 8192, 4096, density=0.003, seed=xi.BASE_SEED + 11)
+        xb = xi.activations(np.random.default_rng(xi.BASE_SEED + 411), 1, W.K)
+        nbytes = W.algorithmic_bytes(M=1)
+        R = max(1, min(512, -(-ring_bytes // nbytes)))
+        ring = [xfp.upload(W)]
+        for _ in range(R - 1):
+            ring.append(clone_weights(ring[0]))
+        xd = dev_x(xb)
+        y = torch.empty((1, W.N), dtype=torch.float16, device="cuda")
+
+        def step(i):
+            xfp.xfp_gemv(ring[i % R], xd, y=y)
+
+        def oracle_once(threads=None):
+            import oracle
+            return oracle.gemv_weights(W, xb, threads)
+
+        return dict(name="V2 8192x4096 b2 M=1 (workload 2's shape at 2 bits)", step=step, bytes=nbytes, ring=R,
+                    oracle=oracle_once, launches=1, kernel_bytes=nbytes, launch_bytes=[nbytes], keep=(ring, xd, y),
+                    M=1, N=W.N, K=W.K, bits=2, mode=0)
     if cfg in (8, 9, 10):
         if cfg == 8:
             W = xi.random_weights(xi.MODE_V2, 4, 8192, 28672, density=0.003, seed=xi.BASE_SEED + 7)
@@ -207,20 +236,72 @@ def build_workload(cfg: int, ring_bytes: int):
 
 
 def read_traffic(cfg: int):
-    """HBM bytes per launch measured offline with rocprofv3 --pmc (see profiles/), or None."""
+    """HBM bytes per launch from an OFFLINE rocprofv3 --pmc run (see profiles/; not measured in this run),
+    and where the figure comes from; (None, None) when no such file exists."""
     path = os.path.join(ROOT, "profiles", f"pmc_traffic_workload{cfg}.txt")
     try:
+        val, stamp = None, ""
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":")[1].split()[0])
+                val = float(line.split(":")[1].split()[0])
+            if line.startswith("kernels_as_of:"):
+                stamp = ", kernels as of " + line.split(":", 1)[1].strip()
+        if val is not None:
+            return val, f"offline: profiles/{os.path.basename(path)} (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE{stamp})"
     except OSError:
         pass
-    return None
+    return None, None
 
 
-def time_plain_read(launch_bytes, K, ring_bytes):
+class CacheFlush:
+    """Streams a buffer three times the size of the 256 MB last-level cache through the chip (read-only kernel),
+    so that whatever the previous replay left in L2 / Infinity Cache is gone before a timed replay starts."""
+
+    def __init__(self, nbytes=768 << 20):
+        import torch
+        self.buf = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        self.buf.random_(0, 256)
+        self.sink = torch.zeros(4096, dtype=torch.int32, device="cuda")
+
+    def __call__(self):
+        import torch
+
+        import paper_2605_14844_amd as xfp
+        xfp.xfp_probe_read(self.buf, self.sink)
+        torch.cuda.synchronize()
+
+
+def timed_graph(step, K, first, flush):
+    """Records steps first .. first + K - 1 into one HIP graph, replays it once untimed (the first replay
+    uploads the graph), flushes the caches, then times ONE replay (exactly K steps) between two events on
+    the launch stream.  Returns (ms per step by the events, ms per step by the host clock)."""
+    import torch
+    stream = torch.cuda.current_stream()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            for i in range(K):
+                step(first + i)
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+    flush()
+    g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    w0 = time.perf_counter()
+    g0.record(stream)
+    graph.replay()
+    g1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - w0) * 1e3 / K
+    return g0.elapsed_time(g1) / K, wall_ms
+
+
+def time_plain_read(launch_bytes, K, ring_bytes, flush):
     """us per step of xfp_probe_read over the same byte counts, one launch per decode launch, walking a
-    buffer of ring_bytes so that no cache holds the data; same graph replay and events as the decode."""
+    buffer of ring_bytes so that no cache holds the data; same graph replay, flush and events as the decode."""
     import torch
 
     import paper_2605_14844_amd as xfp
@@ -229,7 +310,7 @@ def time_plain_read(launch_bytes, K, ring_bytes):
     sink = torch.zeros(4096, dtype=torch.int32, device="cuda")
     state = {"off": 0}
 
-    def step():
+    def step(_i):
         for nb in launch_bytes:
             nb16 = nb // 16 * 16
             if state["off"] + nb16 > ring_bytes:
@@ -237,25 +318,41 @@ def time_plain_read(launch_bytes, K, ring_bytes):
             xfp.xfp_probe_read(buf[state["off"]:], sink, nbytes=nb16)
             state["off"] += (nb16 + 4095) // 4096 * 4096
 
-    for _ in range(20):
-        step()
+    for i in range(20):
+        step(i)
+    return timed_graph(step, K, 0, flush)[0] * 1e3
+
+
+def measure(cfg, args, flush, want_eager=True):
+    """Builds workload cfg, runs warm-up, times K steps; returns (workload, dict of figures)."""
+    import torch
+    t0 = time.time()
+    wl = build_workload(cfg, args.ring_bytes)
+    setup_s = time.time() - t0
+    step, K, Wm = wl["step"], args.steps, args.warmup
     stream = torch.cuda.current_stream()
-    side = torch.cuda.Stream()
-    graph = torch.cuda.CUDAGraph()
-    with torch.cuda.stream(side):
+    for i in range(Wm):
+        step(i)
+    torch.cuda.synchronize()
+    eager_ms = None
+    if want_eager or args.no_graph:
+        # eager launch rate (reported, not the headline): Python + ctypes + hipLaunchKernel per call
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
-        with torch.cuda.graph(graph, stream=side):
-            for _ in range(K):
-                step()
-    torch.cuda.synchronize()
-    graph.replay()
-    torch.cuda.synchronize()
-    g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    g0.record(stream)
-    graph.replay()
-    g1.record(stream)
-    torch.cuda.synchronize()
-    return g0.elapsed_time(g1) / K * 1e3
+        e0.record(stream)
+        for i in range(K):
+            step(Wm + i)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        eager_ms = e0.elapsed_time(e1) / K
+    if args.no_graph:
+        ms_per_step, wall_ms = eager_ms, eager_ms
+    else:
+        ms_per_step, wall_ms = timed_graph(step, K, Wm, flush)
+    res = {"ms_per_step": ms_per_step, "wall_ms": wall_ms, "eager_ms": eager_ms, "setup_s": setup_s}
+    if not args.no_graph and not args.no_plain_read:
+        res["plain_read_us"] = time_plain_read(wl["launch_bytes"], K, args.ring_bytes, flush)
+    return wl, res
 
 
 def main():
@@ -270,6 +367,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     xfp.load_library()
+    xfp.xfp_init()
 
     if args.calibrate_copy:
         n = args.calibrate_copy << 20
@@ -281,53 +379,14 @@ def main():
         print(json.dumps({"calibrate_copy_bytes": n, "launches": 20, "kernel": "probe_copy_kernel"}))
         return
 
-    t0 = time.time()
-    wl = build_workload(args.config, args.ring_bytes)
-    setup_s = time.time() - t0
-    step, K, Wm = wl["step"], args.steps, args.warmup
-    stream = torch.cuda.current_stream()
-
-    for i in range(Wm):
-        step(i)
-    torch.cuda.synchronize()
-
-    # eager launch rate (reported, not the headline): Python + ctypes + hipLaunchKernel per call
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    e0.record(stream)
-    for i in range(K):
-        step(Wm + i)
-    e1.record(stream)
-    torch.cuda.synchronize()
-    eager_ms = e0.elapsed_time(e1) / K
-
-    if args.no_graph:
-        ms_per_step, wall_ms = eager_ms, eager_ms
-    else:
-        side = torch.cuda.Stream()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.stream(side):
-            torch.cuda.synchronize()
-            with torch.cuda.graph(graph, stream=side):
-                for i in range(K):
-                    step(Wm + i)
-        torch.cuda.synchronize()
-        graph.replay()                       # untimed: first replay uploads the graph
-        torch.cuda.synchronize()
-        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        w0 = time.perf_counter()
-        g0.record(stream)
-        graph.replay()                       # EXACTLY K steps
-        g1.record(stream)
-        torch.cuda.synchronize()
-        wall_ms = (time.perf_counter() - w0) * 1e3 / K
-        ms_per_step = g0.elapsed_time(g1) / K
-
+    flush = CacheFlush()
+    wl, res = measure(args.config, args, flush)
+    K, Wm = args.steps, args.warmup
+    ms_per_step = res["ms_per_step"]
     gbs = wl["bytes"] / (ms_per_step * 1e-3) / 1e9
     launch_ms = ms_per_step * wl["kernel_bytes"] / wl["bytes"] if wl["launches"] > 1 else ms_per_step
     achieved = wl["kernel_bytes"] / (launch_ms * 1e-3) / 1e9
-    traffic = read_traffic(args.config)
+    traffic, traffic_src = read_traffic(args.config)
 
     out = {
         "metric": "achieved HBM GB/s of the fused XFP decode GEMV (algorithmic bytes / time per call)",
@@ -337,19 +396,19 @@ def main():
         "config": {"workload": wl["name"], "M": wl["M"], "N": wl["N"], "K": wl["K"], "bits": wl["bits"],
                    "mode": "V2a" if wl["mode"] else "V2", "y_dtype": "f16",
                    "algorithmic_bytes_per_step": wl["bytes"], "ring_copies": wl["ring"],
-                   "launches_per_step": wl["launches"], "timed_with": "eager" if args.no_graph else "hip graph replay"},
+                   "launches_per_step": wl["launches"], "timed_with": "eager" if args.no_graph else "hip graph replay",
+                   "caches": "768 MB streamed through the chip between the untimed and the timed replay"},
         "us_per_call": round(ms_per_step * 1e3, 3),
         "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
-        "eager_us_per_step": round(eager_ms * 1e3, 3),
-        "wall_us_per_step": round(wall_ms * 1e3, 3),
-        "setup_s": round(setup_s, 1),
+        "eager_us_per_step": round(res["eager_ms"] * 1e3, 3),
+        "wall_us_per_step": round(res["wall_ms"] * 1e3, 3),
+        "setup_s": round(res["setup_s"], 1),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic},
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     "traffic_source": traffic_src},
     }
-
-    if not args.no_graph and not args.no_plain_read:
-        # practical ceiling: a read-only kernel over the same bytes per launch, in the same harness
-        pr_us = time_plain_read(wl["launch_bytes"], K, args.ring_bytes)
+    if "plain_read_us" in res:
+        pr_us = res["plain_read_us"]
         out["plain_read"] = {"us_per_step": round(pr_us, 3),
                              "GB/s": round(sum(b // 16 * 16 for b in wl["launch_bytes"]) / pr_us / 1e3, 2),
                              "decode_vs_plain_read": round(pr_us / (ms_per_step * 1e3), 4),
@@ -370,7 +429,28 @@ def main():
                                "cores": threads, "kind": "oracle",
                                "sample": f"{n} full calls of the same workload, {dt:.1f} s, "
                                          f"{dt / n * 1e3:.1f} ms per call"}
+
+    if args.config == 2 and not args.single:
+        # the other workloads of the target, same protocol, in the same line (the headline stays workload 2)
+        table = {"C2": row_of(wl, res)}
+        del wl
+        for cfg in (1, 3, 4, 5, 11):
+            torch.cuda.empty_cache()
+            w2, r2 = measure(cfg, args, flush, want_eager=False)
+            table[f"C{cfg}" if cfg <= 5 else "b2"] = row_of(w2, r2)
+            del w2
+        out["configs"] = table
     print(json.dumps(out))
+
+
+def row_of(wl, res):
+    us = res["ms_per_step"] * 1e3
+    row = {"workload": wl["name"], "us_per_step": round(us, 3), "GB/s": round(wl["bytes"] / us / 1e3, 1),
+           "frac": round(wl["bytes"] / us / 1e3 / HBM_PEAK_GBS, 4), "launches": wl["launches"],
+           "algorithmic_bytes": wl["bytes"]}
+    if "plain_read_us" in res:
+        row["plain_read_us"] = round(res["plain_read_us"], 3)
+    return row
 
 
 if __name__ == "__main__":

@@ -362,7 +362,13 @@ void decode_stream_kernel(DecodeArgs a, int y_f32)
 #pragma unroll
         for (int c = 0; c < NCH; ++c)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) xr[c][i] = bf16x2_to_f16x2(xr[c][i]);
+            for (int i = 0; i < 16; ++i) {
+                // one register at a time: left to itself the compiler converts all of them at once and
+                // pays for the temporaries with the occupancy of the fp16 path too
+                asm volatile("" : "+v"(xr[c][i]));
+                xr[c][i] = bf16x2_to_f16x2(xr[c][i]);
+                asm volatile("" : "+v"(xr[c][i]));
+            }
     }
 
     // One batch of rows.  FIRST: its index words were loaded in the prologue.

@@ -82,10 +82,15 @@ __device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t w)
     const _Float16 l16 = (_Float16)lo, h16 = (_Float16)hi;
     return (uint32_t)__builtin_bit_cast(uint16_t, l16) | ((uint32_t)__builtin_bit_cast(uint16_t, h16) << 16);
 }
-// one activation as fp32, from its fp16 or bf16 pattern
+// one activation as fp32, from its fp16 or bf16 pattern.  Both readings are
+// computed and one is picked bit-wise: as a branch, this handful of instructions
+// cost the streaming kernel 35 registers (and with them a wave per SIMD).
 __device__ __forceinline__ float x_bits_to_float(uint16_t h, bool bf16)
 {
-    return bf16 ? (float)bf16_bits_to_half(h) : (float)__builtin_bit_cast(_Float16, h);
+    const uint32_t a = __builtin_bit_cast(uint32_t, (float)__builtin_bit_cast(_Float16, h));
+    const uint32_t b = __builtin_bit_cast(uint32_t, (float)bf16_bits_to_half(h));
+    const uint32_t m = bf16 ? 0xFFFFFFFFu : 0u;
+    return __builtin_bit_cast(float, (b & m) | (a & ~m));
 }
 
 template <int CTRL>

@@ -1,0 +1,47 @@
+"""What the compiler made of the kernels (registers, spills, occupancy), read from the remarks the build keeps
+in kernel_resources.json.  A change in front of a kernel's loads can silently cost it a wave per SIMD or push it
+into scratch memory (a three-line branch once did: 35 registers, 98 spilled, a 2.4 times slower call), so the
+kernels that the five workloads launch are pinned here."""
+import json
+import os
+
+import pytest
+
+import paper_2605_14844_amd as xfp
+
+PATH = os.path.join(os.path.dirname(xfp.library_path()), "kernel_resources.json")
+
+
+def resources():
+    if not os.path.exists(PATH):
+        pytest.skip("kernel_resources.json is written by paper_2605_14844_amd.build.build()")
+    with open(PATH) as f:
+        return json.load(f)
+
+
+def find(res, *parts):
+    hits = [v for k, v in res.items() if all(p in k for p in parts)]
+    assert len(hits) == 1, (parts, len(hits))
+    return hits[0]
+
+
+def test_no_kernel_spills_more_than_a_few_registers():
+    res = resources()
+    assert len(res) > 500
+    worst = max(res.items(), key=lambda kv: kv[1]["vgpr_spills"])
+    assert worst[1]["vgpr_spills"] <= 16, worst
+    assert sum(1 for v in res.values() if v["vgpr_spills"] > 0) <= 10
+
+
+@pytest.mark.parametrize("parts,min_waves", [
+    (("decode_stream_kernelILi4ELi2ELi1ELb0ELi0ELi2ELi0E",), 4),      # workload 2: 4-bit, K = 4096, two rows per wave
+    (("decode_stream_kernelILi4ELi1ELi2ELb0ELi0ELi1ELi0E",), 4),      # workload 1: K = 1024
+    (("decode_stream_kernelILi3ELi2ELi1ELb0ELi1ELi2ELi0E",), 4),      # workload 3: V2a 3-bit
+    (("decode_stream_kernelILi3ELi2ELi1ELb0ELi0ELi4ELi0E",), 4),      # workload 4 gate_up
+    (("decode_stream_kernelILi3ELi1ELi2ELb0ELi0ELi4ELi0E",), 4),      # workload 4 down
+    (("decode_batch_kernelILi4ELi0ELi8ELi8ELb0ELb0E",), 1),           # workload 5: 8 waves, 8 groups each
+])
+def test_the_workloads_kernels_keep_their_registers(parts, min_waves):
+    k = find(resources(), *parts)
+    assert k["vgpr_spills"] == 0 and k["scratch_bytes_per_lane"] == 0, k
+    assert k["waves_per_simd"] >= min_waves, k
