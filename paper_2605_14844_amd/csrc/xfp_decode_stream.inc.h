@@ -290,12 +290,21 @@ void decode_stream_kernel(DecodeArgs a, int y_f32)
     // pair entries (lo, hi), lo = 0 .. ENT-1, which are contiguous in table l; it
     // needs codebook l (ENT / 2 dwords) and its entry hi.
     constexpr int CW = ENT / 2;
-    uint32_t libw[MODE == 1 ? CW : 1], libhi = 0u;
+    // The items of a library of up to 32 codebooks (j = tid, tid + threads, ...: PRE per thread) are
+    // loaded here, in front of everything that streams: a load inside the build loop is a full memory
+    // round trip in front of the barrier, for every wave of the workgroup (it cost workload 3 0.85 of
+    // its 5.5 us while the all-zero table's items still went through such a load).
+    constexpr int PRE = (32 * ENT + kStreamThreads - 1) / kStreamThreads < 4 ? (32 * ENT + kStreamThreads - 1) / kStreamThreads : 4;
+    uint32_t libw[MODE == 1 ? PRE : 1][MODE == 1 ? CW : 1], libhi[MODE == 1 ? PRE : 1];
     if constexpr (MODE == 1) {
-        const uint32_t l = min(threadIdx.x / ENT, a.L - 1), hi = threadIdx.x % ENT;
 #pragma unroll
-        for (int d = 0; d < CW; ++d) libw[d] = cbw[l * CW + d];
-        libhi = reinterpret_cast<const uint16_t *>(cbw)[l * ENT + hi];
+        for (int p = 0; p < PRE; ++p) {
+            const uint32_t j = threadIdx.x + p * kStreamThreads;
+            const uint32_t l = min(j / ENT, a.L - 1), hi = j % ENT;
+#pragma unroll
+            for (int d = 0; d < CW; ++d) libw[p][d] = cbw[l * CW + d];
+            libhi[p] = reinterpret_cast<const uint16_t *>(cbw)[l * ENT + hi];
+        }
     }
     __builtin_amdgcn_sched_barrier(0);
 
@@ -320,20 +329,9 @@ void decode_stream_kernel(DecodeArgs a, int y_f32)
         // loads are in flight.  Table l sits at l * kRowBytes; table L is all zero
         // (lanes past the end of a short row).  One barrier: nothing is staged.
         const uint32_t L = a.L, items = (L + 1) * ENT;
-        for (uint32_t j = threadIdx.x; j < items; j += kStreamThreads) {
+        auto build_item = [&](uint32_t j, const uint32_t (&w)[CW], uint32_t hv) {
             const uint32_t l = j / ENT, hi = j % ENT;
-            uint32_t w[CW], hv;
-            if (j == threadIdx.x) {
-#pragma unroll
-                for (int d = 0; d < CW; ++d) w[d] = libw[d];
-                hv = libhi;
-            } else {                                           // libraries of more than 256 / ENT codebooks
-                const uint32_t lc = min(l, L - 1);
-#pragma unroll
-                for (int d = 0; d < CW; ++d) w[d] = cbw[lc * CW + d];
-                hv = reinterpret_cast<const uint16_t *>(cbw)[lc * ENT + hi];
-            }
-            const uint32_t keep = l < L ? 0xFFFFFFFFu : 0u, hs = hv << 16;
+            const uint32_t keep = l < L ? 0xFFFFFFFFu : 0u, hs = hv << 16;       // table L: all zero
             const uint32_t dst = lds0 + l * Fmt::kRowBytes + hi * ENT * 4;
 #pragma unroll
             for (int c4 = 0; c4 < ENT / 4; ++c4) {
@@ -346,6 +344,22 @@ void decode_stream_kernel(DecodeArgs a, int y_f32)
                 typedef uint32_t u4 __attribute__((ext_vector_type(4)));
                 *(__attribute__((address_space(3))) u4 *)(uintptr_t)(dst + c4 * 16) = u4{v[0], v[1], v[2], v[3]};
             }
+        };
+#pragma unroll
+        for (int p = 0; p < PRE; ++p) {
+            const uint32_t j = threadIdx.x + p * kStreamThreads;
+            if (j < items) build_item(j, libw[p], libhi[p]);
+        }
+        for (uint32_t j = threadIdx.x + PRE * kStreamThreads; j < items; j += kStreamThreads) {
+            uint32_t w[CW], hv = 0u;                           // larger libraries: loaded here
+#pragma unroll
+            for (int d = 0; d < CW; ++d) w[d] = 0u;
+            if (j / ENT < L) {                                 // (the all-zero table needs no load)
+#pragma unroll
+                for (int d = 0; d < CW; ++d) w[d] = cbw[(j / ENT) * CW + d];
+                hv = reinterpret_cast<const uint16_t *>(cbw)[j];
+            }
+            build_item(j, w, hv);
         }
         __syncthreads();
     } else if constexpr (TAIL) {
