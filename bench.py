@@ -4,7 +4,7 @@
 A step is one pass of the whole hot path over one batch: one xfp_gemv call
 (workloads 1, 2, 3, 5) or one gate_up + one down xfp_gemv_moe call (workload
 4).  More configurations measure what was added beyond the five: 6 (the
-expert layer of workload 4 with both epilogues fused), 7 (split-K), 8-10 (the
+expert layer of workload 4 with both epilogues fused), 7 (long rows), 8-10 (the
 batched kernel's other forms), 11 (2 bits).  Weights are already resident in
 HBM; successive steps walk a ring of distinct device copies whose total size
 exceeds the last-level cache, and 768 MB are streamed through the chip between
@@ -39,7 +39,7 @@ def parse_args():
     p.add_argument("--warmup", type=int, default=200)
     p.add_argument("--config", type=int, default=2,
                    help="workload 1..5 (default 2, the headline); beyond the five: 6 = workload 4 as a whole expert "
-                        "layer with both epilogues fused, 7 = a long-row matrix (8192x28672, 4-bit, M=1) through split-K, "
+                        "layer with both epilogues fused, 7 = a long-row matrix (8192x28672, 4-bit, M=1) through the tile kernel, "
                         "8 = the same matrix with 16 tokens, 9 = workload 5's shape at 3 bits, 10 = the same as V2a, "
                         "11 = workload 2's shape at 2 bits")
     p.add_argument("--no-cpu-baseline", action="store_true")
@@ -179,8 +179,8 @@ def build_workload(cfg: int, ring_bytes: int):
             import oracle
             return oracle.gemv_weights(W, xb, threads)
 
-        return dict(name="V2 8192x28672 b4 M=1 (rows longer than 16384: split-K, two launches)", step=step,
-                    bytes=nbytes, ring=R, oracle=oracle_once, launches=2, kernel_bytes=nbytes,
+        return dict(name="V2 8192x28672 b4 M=1 (rows longer than 16384: the tile kernel, one launch)", step=step,
+                    bytes=nbytes, ring=R, oracle=oracle_once, launches=1, kernel_bytes=nbytes,
                     launch_bytes=[nbytes], keep=(ring, xd, y), M=1, N=W.N, K=W.K, bits=4, mode=0)
     if cfg == 11:
         W = xi.random_weights(xi.MODE_V2, 2, 8192, 4096, density=0.003, seed=xi.BASE_SEED + 11)

@@ -301,6 +301,17 @@ int xfp_probe_copy(const void *src, void *dst, uint64_t bytes, void *hip_stream)
 int xfp_init(void);
 
 /*
+ * Measurement and test aid (no paper counterpart): which kernel the M = 1 calls
+ * take where two can (V2, 4 bits: the streaming kernel, one wave per output row,
+ * or the tile kernel, 32 rows across the lanes with a pair table per lane).
+ * XFP_KERNEL_AUTO restores the library's own rule (the tile kernel for rows of
+ * more than 16384 columns).  Process-wide; results agree to rounding either way.
+ * XFP_ERR_UNSUPPORTED for any other value.
+ */
+typedef enum { XFP_KERNEL_AUTO = 0, XFP_KERNEL_STREAM = 1, XFP_KERNEL_TILE = 2 } xfp_kernel_choice;
+int xfp_select_kernel(int which);
+
+/*
  * Test hook for the ring's slot arithmetic (host only, touches no device): the
  * slot index in [0, 8) that the ticket-th scratch-using call of its kind takes;
  * capturing != 0: a call recorded into a HIP graph.  Eager calls get slots

@@ -69,10 +69,11 @@ def load_library():
     lib.xfp_dequant_bulk.argtypes = [wp, vp, vp]
     lib.xfp_probe_read.argtypes = [vp, u64, vp, vp]
     lib.xfp_probe_copy.argtypes = [vp, vp, u64, vp]
+    lib.xfp_select_kernel.argtypes = [i32]
     lib.xfp_strerror.argtypes = [i32]
     lib.xfp_strerror.restype = ctypes.c_char_p
     for name in ("xfp_gemv", "xfp_gemv_noalloc", "xfp_gemv_moe", "xfp_gemv_moe_silu_mul", "xfp_gemv_moe_combine", "xfp_check_contents", "xfp_convert_bf16_to_f16", "xfp_repack_word10", "xfp_unpack_indices", "xfp_dequant_bulk",
-                 "xfp_probe_read", "xfp_probe_copy", "xfp_version", "xfp_init"):
+                 "xfp_probe_read", "xfp_probe_copy", "xfp_version", "xfp_init", "xfp_select_kernel"):
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -84,6 +85,14 @@ def xfp_strerror(status: int) -> str:
 
 def xfp_version() -> int:
     return int(load_library().xfp_version())
+
+
+XFP_KERNEL_AUTO, XFP_KERNEL_STREAM, XFP_KERNEL_TILE = 0, 1, 2
+
+
+def xfp_select_kernel(which: int) -> None:
+    """Which kernel M = 1 calls take where two can (measurement and test aid); XFP_KERNEL_AUTO restores the rule."""
+    _check(load_library().xfp_select_kernel(int(which)))
 
 
 def xfp_init() -> None:

@@ -145,11 +145,28 @@ uint32_t rows_per_block(uint32_t N, int slots)
     return r;
 }
 
+// M = 1 per slot: the tile kernel or the streaming kernel?  Measured on MI355X (4-bit V2, one call per
+// matrix, graph replay over a ring of copies): rows of up to 8192 columns run within 5 % of each other on
+// both (8192 x 4096: 6.2 us streaming, 6.7 tile; 16384 x 4096: 10.0 / 9.5; 28672 x 8192: 30.6 / 29.8), so
+// they stay with the streaming kernel; rows beyond what that kernel holds in registers, which it can only
+// take as split-K slices plus a second launch, are the tile kernel's (8192 x 28672: 32.9 / 25.8 us).
+std::atomic<int> g_kernel_choice{XFP_KERNEL_AUTO};
+
+bool prefer_tile(const xfp_weights *W, int slots)
+{
+    if (!xfp::tile_supports((int)W->bits, (int)W->mode, W->N, W->K, slots)) return false;
+    const int choice = g_kernel_choice.load(std::memory_order_relaxed);
+    if (choice == XFP_KERNEL_TILE) return true;
+    if (choice == XFP_KERNEL_STREAM) return false;
+    return W->K > 16384;
+}
+
 // One token through the M = 1 kernels (the odd token left over after chunks of 16).
 int single_token(const xfp_weights *W, xfp::DecodeArgs c, int y_dtype, Scratch &sc, hipStream_t s)
 {
     const int bits = (int)W->bits, mode = (int)W->mode;
     const bool y_f32 = y_dtype == XFP_F32;
+    if (prefer_tile(W, 1)) return finish(xfp::launch_decode_tile(bits, y_f32, c, 1, s));
     if (xfp::stream_supports(bits, mode, W->K, W->L)) return finish(xfp::launch_decode_stream(bits, mode, y_f32, c, 1, s));
     if (const int S = xfp::splitk_slices(bits, mode, W->N, W->K, W->L, 1)) {
         const xfp::Workspace *ws = nullptr;
@@ -195,6 +212,7 @@ int decode(const xfp_weights *W, const int32_t *eids, int slots, const void *x, 
         }
         return XFP_OK;
     }
+    if (prefer_tile(W, slots)) return finish(xfp::launch_decode_tile(bits, y_dtype == XFP_F32, a, slots, s));
     if (xfp::stream_supports(bits, mode, W->K, W->L))
         return finish(xfp::launch_decode_stream(bits, mode, y_dtype == XFP_F32, a, slots, s));
     if (const int S = xfp::splitk_slices(bits, mode, W->N, W->K, W->L, slots)) {
@@ -449,6 +467,13 @@ int xfp_init(void)
     hipError_t err = xfp::ring_resolve();
     if (err == hipSuccess) err = scratch_resolve(nullptr);
     return finish(err);
+}
+
+int xfp_select_kernel(int which)
+{
+    if (which != XFP_KERNEL_AUTO && which != XFP_KERNEL_STREAM && which != XFP_KERNEL_TILE) return XFP_ERR_UNSUPPORTED;
+    g_kernel_choice.store(which, std::memory_order_relaxed);
+    return XFP_OK;
 }
 
 int xfp_ring_slot(unsigned ticket, int capturing) { return xfp::ring_slot_index(ticket, capturing != 0); }

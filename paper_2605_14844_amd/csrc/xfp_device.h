@@ -136,6 +136,40 @@ __device__ __forceinline__ float segment_sum(float v)
     return v;
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits
+// for every outstanding global load, which would drain the index prefetch.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// Exchange a register-index bit with lane-index bit 0 (HIGH = 0, quad_perm
+// [1,0,3,2]) or bit 1 (HIGH = 1, quad_perm [2,3,0,1]) for two register pairs
+// (x0, y0) and (x1, y1): afterwards x holds, in the lanes whose bit is set, what
+// y held in the partner lane, and y holds, in the lanes whose bit is clear, what
+// x held in the partner lane.  One v_cndmask_b32 with a DPP source per output;
+// the two scalar moves in front also cover the wait states a DPP read needs
+// after a vector write.
+#define XFP_EXCHANGE_ASM(QP, MASK)                                                                   \
+    asm volatile("s_nop 1\n\t"                                                                       \
+                 "s_mov_b32 vcc_lo, " MASK "\n\ts_mov_b32 vcc_hi, " MASK "\n\t"                        \
+                 "v_cndmask_b32_dpp %0, %5, %4, vcc quad_perm:" QP " row_mask:0xf bank_mask:0xf\n\t" \
+                 "v_cndmask_b32_dpp %2, %7, %6, vcc quad_perm:" QP " row_mask:0xf bank_mask:0xf\n\t" \
+                 "s_not_b64 vcc, vcc\n\t"                                                            \
+                 "v_cndmask_b32_dpp %1, %4, %5, vcc quad_perm:" QP " row_mask:0xf bank_mask:0xf\n\t" \
+                 "v_cndmask_b32_dpp %3, %6, %7, vcc quad_perm:" QP " row_mask:0xf bank_mask:0xf"      \
+                 : "=&v"(o0), "=&v"(o1), "=&v"(o2), "=&v"(o3)                                        \
+                 : "v"(x0), "v"(y0), "v"(x1), "v"(y1)                                                \
+                 : "vcc", "scc")
+template <int HIGH>
+__device__ __forceinline__ void lane_reg_exchange(uint32_t &x0, uint32_t &y0, uint32_t &x1, uint32_t &y1)
+{
+    uint32_t o0, o1, o2, o3;
+    if constexpr (HIGH) XFP_EXCHANGE_ASM("[2,3,0,1]", "0x33333333");    // vcc: lanes whose bit 1 is clear
+    else XFP_EXCHANGE_ASM("[1,0,3,2]", "0x55555555");                   // vcc: lanes whose bit 0 is clear
+    x0 = o0; y0 = o1; x1 = o2; y1 = o3;
+}
+
 // fp32 -> bf16 bit pattern, round to nearest even, NaN stays NaN
 __device__ __forceinline__ uint16_t float_to_bf16_bits(float v)
 {

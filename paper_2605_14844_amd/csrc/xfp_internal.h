@@ -96,6 +96,9 @@ hipError_t launch_decode_rows(int bits, int mode, bool y_f32, const DecodeArgs &
 // registers, pair tables in LDS.
 bool stream_supports(int bits, int mode, uint32_t K, uint32_t L);
 hipError_t launch_decode_stream(int bits, int mode, bool y_f32, const DecodeArgs &a, int slots, hipStream_t s);
+// Tile kernel (V2, 4-bit, M = 1 per slot): rows across lanes, one pair table per lane, conflict-free lookups.
+bool tile_supports(int bits, int mode, uint32_t N, uint32_t K, int slots);
+hipError_t launch_decode_tile(int bits, bool y_f32, const DecodeArgs &a, int slots, hipStream_t s);
 // Split-K form of the streaming kernel for rows longer than it holds in registers:
 // S equal slices of K, fp32 partial sums in a file-scope device buffer, summed in
 // slice order by a second kernel.  splitk_slices returns S, or 0 if the shape does

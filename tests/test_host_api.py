@@ -129,6 +129,12 @@ def test_noalloc_entry_point_refuses_what_its_static_array_cannot_hold():
     assert call(desc(E=2), 1, 256) == -2
 
 
+def test_kernel_selection_takes_only_its_three_values():
+    lib = xfp.load_library()
+    assert lib.xfp_select_kernel(2) == 0 and lib.xfp_select_kernel(1) == 0 and lib.xfp_select_kernel(0) == 0
+    assert lib.xfp_select_kernel(3) == -3 and lib.xfp_select_kernel(-1) == -3
+
+
 def test_alignment_errors():
     assert gemv(desc(indices=FAKE + 4)) == -4
     assert gemv(desc(codebooks=FAKE + 2)) == -4
