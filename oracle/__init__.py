@@ -90,21 +90,43 @@ def repack_word10(words: np.ndarray, K: int) -> np.ndarray:
     return pack(unpack_word10(words, K), 3)
 
 
-def dequant_bulk(mode, bits, N, K, words, codebooks, group_ids=None, want_double=True):
-    """Bulk term Codebook[Q] of one matrix: (fp16 bit patterns [N,K], doubles or None)."""
+def unpack_wordform(words: np.ndarray, K: int, bits: int) -> np.ndarray:
+    """Indices stored in the word forms of the paper's table 2 (2: 16 per uint32, 3: 10 per uint32, 4: 8 per
+    uint32, 5: 3 per uint16, 6: 5 per uint32; reserve bits ignored): words [..., ceil(K/per)] -> uint8 [..., K]."""
+    per = {2: 16, 3: 10, 4: 8, 5: 3, 6: 5}[bits]
+    wdt = np.uint16 if bits == 5 else np.uint32
+    words = _c(words, wdt)
+    wpr = (K + per - 1) // per
+    rows = words.size // wpr
+    q = np.empty((rows, K), dtype=np.uint8)
+    raw = np.ascontiguousarray(words).view(np.uint8)
+    got = _load().xfp_oracle_unpack_wordform(_p(raw), ctypes.c_int64(rows), ctypes.c_int64(K), ctypes.c_int(bits), _p(q))
+    assert got == per
+    return q.reshape(*words.shape[:-1], K)
+
+
+def repack_wordform(words: np.ndarray, K: int, bits: int) -> np.ndarray:
+    """The same indices as the dense stream: unpack every value, pack it again."""
+    return pack(unpack_wordform(words, K, bits), bits)
+
+
+def dequant_bulk(mode, bits, N, K, words, codebooks, group_ids=None, want_double=True, group_scale=None, group_mid=None):
+    """Bulk term of one matrix: (fp16 bit patterns of the selected entries [N,K], bulk values as doubles or None;
+    the doubles include the per-group scale and mid-point when given)."""
     words, codebooks = _c(words, np.uint32), _c(codebooks, np.uint16)
     group_ids = _c(group_ids, np.uint8)
+    group_scale, group_mid = _c(group_scale, np.uint16), _c(group_mid, np.uint16)
     wb = np.empty((N, K), dtype=np.uint16)
     wd = np.empty((N, K), dtype=np.float64) if want_double else None
     rc = _load().xfp_oracle_dequant_bulk(ctypes.c_int(mode), ctypes.c_int(bits), ctypes.c_int64(N),
                                          ctypes.c_int64(K), _p(words), _p(codebooks),
-                                         _p(group_ids), _p(wb), _p(wd))
+                                         _p(group_ids), _p(group_scale), _p(group_mid), _p(wb), _p(wd))
     if rc:
         raise ValueError(f"oracle dequant_bulk rejected arguments ({rc})")
     return wb, wd
 
 
-def gemv(mode, bits, N, K, words, codebooks, group_ids, row_ptr, col, val, x, threads=None):
+def gemv(mode, bits, N, K, words, codebooks, group_ids, row_ptr, col, val, x, threads=None, group_scale=None, group_mid=None):
     """y double [M,N] for one matrix; x is fp16 bits [M,K] (or [K])."""
     x = _c(x, np.uint16)
     x2 = x.reshape(-1, K)
@@ -113,9 +135,10 @@ def gemv(mode, bits, N, K, words, codebooks, group_ids, row_ptr, col, val, x, th
     words, codebooks = _c(words, np.uint32), _c(codebooks, np.uint16)
     group_ids = _c(group_ids, np.uint8)
     row_ptr, col, val = _c(row_ptr, np.int32), _c(col, np.int32), _c(val, np.uint16)
+    group_scale, group_mid = _c(group_scale, np.uint16), _c(group_mid, np.uint16)
     rc = _load().xfp_oracle_gemv(ctypes.c_int(mode), ctypes.c_int(bits), ctypes.c_int64(N),
                                  ctypes.c_int64(K), _p(words), _p(codebooks), _p(group_ids),
-                                 _p(row_ptr), _p(col), _p(val), _p(x2), ctypes.c_int64(M),
+                                 _p(group_scale), _p(group_mid), _p(row_ptr), _p(col), _p(val), _p(x2), ctypes.c_int64(M),
                                  ctypes.c_int64(K), _p(y), ctypes.c_int64(N),
                                  ctypes.c_int(threads or max_threads()))
     if rc:
@@ -128,7 +151,9 @@ def gemv_weights(W, x, threads=None):
     assert W.E == 1
     return gemv(W.mode, W.bits, W.N, W.K, W.indices[0], W.codebooks[0],
                 None if W.group_ids is None else W.group_ids[0],
-                W.out_row_ptr, W.out_col, W.out_val, x, threads)
+                W.out_row_ptr, W.out_col, W.out_val, x, threads,
+                None if getattr(W, "group_scale", None) is None else W.group_scale[0],
+                None if getattr(W, "group_mid", None) is None else W.group_mid[0])
 
 
 def gemv_moe(W, expert_ids, x, shared_x: bool, threads=None):
@@ -141,9 +166,10 @@ def gemv_moe(W, expert_ids, x, shared_x: bool, threads=None):
     y = np.empty((T, W.N), dtype=np.float64)
     words, codebooks = _c(W.indices, np.uint32), _c(W.codebooks, np.uint16)
     gids = _c(W.group_ids, np.uint8)
+    gs, gm = _c(getattr(W, "group_scale", None), np.uint16), _c(getattr(W, "group_mid", None), np.uint16)
     rc = _load().xfp_oracle_gemv_moe(
         ctypes.c_int(W.mode), ctypes.c_int(W.bits), ctypes.c_int64(W.N), ctypes.c_int64(W.K),
-        ctypes.c_int64(W.L), ctypes.c_int64(W.E), _p(words), _p(codebooks), _p(gids),
+        ctypes.c_int64(W.L), ctypes.c_int64(W.E), _p(words), _p(codebooks), _p(gids), _p(gs), _p(gm),
         _p(_c(W.out_row_ptr, np.int32)), _p(_c(W.out_col, np.int32)), _p(_c(W.out_val, np.uint16)),
         _p(ids), ctypes.c_int64(T), _p(x), ctypes.c_int64(stride), _p(y), ctypes.c_int64(W.N),
         ctypes.c_int(threads or max_threads()))

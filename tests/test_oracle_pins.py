@@ -350,3 +350,120 @@ def test_moe_combine_special_cases_and_matmul():
                        (w.astype(np.float64) + w2.astype(np.float64)) @ y, rtol=1e-13)
     assert np.allclose(oracle.moe_combine(y + 2.0 * y[::-1], w), oracle.moe_combine(y, w) + 2.0 * oracle.moe_combine(y[::-1], w),
                        rtol=1e-13)
+
+
+# ------------------------------------------------------------------ 5 and 6 bits; the word forms of the packing table
+def test_unpack_hand_vectors_5_and_6_bit_dense_stream():
+    # 5-bit: field 6 = 21 = 0b10101 occupies stream bits 30..34: bits 30, 31 of word 0 (1, 0) and bits 0..2 of
+    # word 1 (1, 0, 1); field 0 = 31
+    words = np.array([[0x4000001F, 0x00000005, 0, 0, 0]], dtype=np.uint32)
+    exp = np.zeros((1, 32), dtype=np.uint8)
+    exp[0, 0], exp[0, 6] = 31, 21
+    assert np.array_equal(oracle.unpack(words, 32, 5), exp)
+    assert np.array_equal(oracle.pack(exp, 5), words)
+    # 6-bit: field 5 = 0b110011 = 51 occupies stream bits 30..35: word 0 bits 30, 31 = (1, 1), word 1 bits 0..3 = (0, 0, 1, 1)
+    words = np.array([[0xC0000000, 0x0000000C, 0]], dtype=np.uint32)
+    exp = np.zeros((1, 16), dtype=np.uint8)
+    exp[0, 5] = 51
+    assert np.array_equal(oracle.unpack(words, 16, 6), exp)
+
+
+@pytest.mark.parametrize("bits", [5, 6])
+def test_pack_unpack_round_trip_5_and_6_bit(bits):
+    rng = np.random.default_rng(bits)
+    q = rng.integers(0, 1 << bits, size=(7, 384), dtype=np.uint8)
+    w = oracle.pack(q, bits)
+    assert w.shape == (7, 384 * bits // 32)
+    assert np.array_equal(oracle.unpack(w, 384, bits), q)
+    assert np.array_equal(np_unpack(w, 384, bits), q)                          # numpy bit expansion
+    assert all(np.array_equal(bigint_pack(q[r], bits), w[r]) for r in range(7))   # big-integer packer
+
+
+def test_word_forms_hand_written():
+    # 5 bits: three values per uint16, bit 15 reserved.  (31, 0, 21) -> 31 | 21 << 10 = 0x541F; with the reserve bit
+    # set the same three values must come out
+    for word in (0x541F, 0xD41F):
+        assert oracle.unpack_wordform(np.array([[word]], np.uint16), 3, 5).tolist() == [[31, 0, 21]]
+    # 6 bits: five per uint32, bits 30, 31 reserved.  (1, 2, 3, 4, 63) -> 1 | 2<<6 | 3<<12 | 4<<18 | 63<<24
+    w6 = 1 | 2 << 6 | 3 << 12 | 4 << 18 | 63 << 24
+    assert w6 == 0x3F103081
+    for word in (w6, w6 | 0xC0000000):
+        assert oracle.unpack_wordform(np.array([[word]], np.uint32), 5, 6).tolist() == [[1, 2, 3, 4, 63]]
+    # 3 bits through the general routine = the ten-per-word routine
+    w3 = np.array([[0o1234567012 | 0x80000000, 0o7]], np.uint32)
+    assert np.array_equal(oracle.unpack_wordform(w3, 11, 3), oracle.unpack_word10(w3, 11))
+    # a part-filled last word: K = 4 at 5 bits takes two uint16
+    assert oracle.unpack_wordform(np.array([[0x541F, 0x0007]], np.uint16), 4, 5).tolist() == [[31, 0, 21, 7]]
+
+
+def test_word_forms_match_the_packing_table_counts():
+    per_word = {}
+    for line in open(GOLDEN):
+        t = line.split("#")[0].split()
+        if t and t[0] == "pack":
+            n, per, wbits, used, reserve = map(int, t[1:])
+            assert per * n == used and used + reserve == wbits
+            per_word[n] = (per, wbits)
+    rng = np.random.default_rng(11)
+    for bits, (per, wbits) in per_word.items():
+        K = 256
+        q = rng.integers(0, 1 << bits, size=(3, K), dtype=np.uint8)
+        w = xi.pack_wordform(q, bits)                                          # the generator's own packer
+        assert w.dtype.itemsize * 8 == wbits and w.shape == (3, -(-K // per))
+        assert np.array_equal(oracle.unpack_wordform(w, K, bits), q)
+        assert np.array_equal(oracle.repack_wordform(w, K, bits), oracle.pack(q, bits))
+        if bits in (2, 4):                                                     # no reserve bits: the word form IS the dense stream
+            assert np.array_equal(w, oracle.pack(q, bits))
+
+
+# ------------------------------------------------------------------ V2a with a scale and a mid-point per group
+def test_affine_groups_identity_is_the_plain_library():
+    W = xi.random_weights(V2A, 4, 12, 512, density=0.004, seed=40, affine=True)
+    x = xi.activations(np.random.default_rng(41), 3, W.K)
+    plain = oracle.gemv(V2A, 4, W.N, W.K, W.indices[0], W.codebooks[0], W.group_ids[0], W.out_row_ptr, W.out_col, W.out_val, x)
+    one, zero = np.full_like(W.group_scale[0], 0x3C00), np.zeros_like(W.group_mid[0])
+    ident = oracle.gemv(V2A, 4, W.N, W.K, W.indices[0], W.codebooks[0], W.group_ids[0], W.out_row_ptr, W.out_col, W.out_val, x,
+                        group_scale=one, group_mid=zero)
+    assert np.array_equal(plain, ident)
+    assert not np.allclose(plain, oracle.gemv_weights(W, x))                   # the generated scales and mid-points do act
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_affine_groups_against_dense_numpy_and_exact_rationals(bits):
+    from fractions import Fraction
+    W = xi.random_weights(V2A, bits, 9, 384, L=7, density=0.01, seed=50 + bits, affine=True)
+    x = xi.activations(np.random.default_rng(51), 2, W.K)
+    # dense build with numpy fancy indexing (not the oracle's loop): C * scale + mid per group, plus the outliers
+    C, O = np_dense_weight(W)
+    s = np.repeat(W.group_scale[0].view(np.float16).astype(np.float64), 128, axis=1)
+    m = np.repeat(W.group_mid[0].view(np.float16).astype(np.float64), 128, axis=1)
+    dense = C * s + m + O
+    xf = x.view(np.float16).astype(np.float64)
+    got = oracle.gemv_weights(W, x)
+    assert gated_rel_err(got, xf @ dense.T) <= 1e-12
+    # the dequantised doubles themselves, and one output in exact rational arithmetic
+    _, wd = oracle.dequant_bulk(V2A, bits, W.N, W.K, W.indices[0], W.codebooks[0], W.group_ids[0],
+                                group_scale=W.group_scale[0], group_mid=W.group_mid[0])
+    assert np.array_equal(wd, C * s + m)
+    n = 4
+    exact = sum(Fraction(float(xf[1, k])) * (Fraction(float(C[n, k])) * Fraction(float(s[n, k])) + Fraction(float(m[n, k])) + Fraction(float(O[n, k])))
+                for k in range(W.K))
+    assert abs(got[1, n] - float(exact)) <= 1e-12 * max(1.0, abs(float(exact)))
+    # the mid-point alone: zero codebooks, unit scale -> y[n] = sum_g mid[n, g] * (sum of x over group g)
+    Z = xi.random_weights(V2A, bits, 9, 384, L=7, density=0.0, seed=60, affine=True)
+    Z.codebooks[:] = 0
+    yz = oracle.gemv_weights(Z, x)
+    xs = xf.reshape(2, 3, 128).sum(axis=2)
+    assert gated_rel_err(yz, xs @ Z.group_mid[0].view(np.float16).astype(np.float64).T) <= 1e-12
+
+
+def test_affine_groups_expert_indexed_slices_scale_and_mid_by_expert():
+    W = xi.random_weights(V2A, 3, 6, 256, E=3, density=0.01, seed=70, affine=True)
+    x = xi.activations(np.random.default_rng(71), 1, W.K)
+    ids = np.array([2, 0, 2], np.int32)
+    y = oracle.gemv_moe(W, ids, x, shared_x=True)
+    for t, e in enumerate(ids):
+        rp = W.out_row_ptr[e * W.N:(e + 1) * W.N + 1]
+        single = oracle.gemv(V2A, 3, W.N, W.K, W.indices[e], W.codebooks[e], W.group_ids[e], rp, W.out_col, W.out_val, x,
+                             group_scale=W.group_scale[e], group_mid=W.group_mid[e])
+        assert np.array_equal(y[t], single[0])

@@ -36,6 +36,8 @@ class XfpHostWeights:
     indices    uint32 [E, N, K*bits/32]  row-major little-endian bitstream
     codebooks  uint16 (fp16 bits)  V2: [E, N, 2**bits]   V2a: [E, L, 2**bits]
     group_ids  uint8  [E, N, K/128] (V2a) or None
+    group_scale, group_mid  uint16 (fp16 bits) [E, N, K/128] or None: the per-group scale and
+               mid-point of a V2a matrix (paper section 3.4), both or neither
     out_row_ptr int32 [E*N + 1], out_col int32 [nnz], out_val uint16 [nnz]
     """
     mode: int
@@ -52,6 +54,8 @@ class XfpHostWeights:
     out_val: np.ndarray
     group: int = GROUP
     meta: dict = field(default_factory=dict)
+    group_scale: Optional[np.ndarray] = None
+    group_mid: Optional[np.ndarray] = None
 
     @property
     def nnz(self) -> int:
@@ -69,7 +73,7 @@ class XfpHostWeights:
         if self.mode == MODE_V2:
             per += self.N * (1 << self.bits) * 2
         else:
-            per += self.L * (1 << self.bits) * 2 + self.N * (self.K // self.group)
+            per += self.L * (1 << self.bits) * 2 + self.N * (self.K // self.group) * (5 if self.group_scale is not None else 1)
         nnz_per = self.nnz // self.E
         per += 6 * nnz_per + 4 * (self.N + 1)
         xb = M * self.K * 2
@@ -118,6 +122,23 @@ def pack_word10(q: np.ndarray) -> np.ndarray:
     for j in range(10):
         w |= q2[:, j::10] << np.uint32(3 * j)
     return w.reshape(*q.shape[:-1], wpr)
+
+
+def pack_wordform(q: np.ndarray, bits: int) -> np.ndarray:
+    """Encode indices q [..., K] in the word forms of the paper's table 2: 16 / 10 / 8 / 5 values per uint32 at
+    2 / 3 / 4 / 6 bits, 3 per uint16 at 5 bits; value k in word k // per at bit bits * (k % per), reserve bits and
+    the unused tail of a row's last word zero."""
+    per = {2: 16, 3: 10, 4: 8, 5: 3, 6: 5}[bits]
+    wdt = np.uint16 if bits == 5 else np.uint32
+    q = np.ascontiguousarray(q, dtype=np.uint8)
+    K = q.shape[-1]
+    wpr = (K + per - 1) // per
+    q2 = np.zeros((q.size // K, wpr * per), dtype=np.uint32)
+    q2[:, :K] = q.reshape(-1, K)
+    w = np.zeros((q2.shape[0], wpr), dtype=np.uint32)
+    for j in range(per):
+        w |= q2[:, j::per] << np.uint32(bits * j)
+    return w.astype(wdt).reshape(*q.shape[:-1], wpr)
 
 
 def random_words(rng: np.random.Generator, shape) -> np.ndarray:
@@ -172,9 +193,10 @@ def _streams(seed: int):
 
 def random_weights(mode: int, bits: int, N: int, K: int, *, E: int = 1, L: int = 32,
                    density: float = 0.003, seed: int = 0, cb_sigma: float = 0.02,
-                   val_sigma: float = 0.5, nnz_per_expert: int | None = None) -> XfpHostWeights:
-    """Uniform-random indices, sorted-normal codebooks, uniform-random outliers."""
-    assert K % GROUP == 0 and bits in (2, 3, 4)
+                   val_sigma: float = 0.5, nnz_per_expert: int | None = None, affine: bool = False) -> XfpHostWeights:
+    """Uniform-random indices, sorted-normal codebooks, uniform-random outliers.
+    affine (V2a): every group also gets a scale (uniform in [0.5, 2)) and a mid-point (N(0, cb_sigma / 2))."""
+    assert K % GROUP == 0 and bits in (2, 3, 4, 5, 6) and not (affine and mode != MODE_V2A)
     r_idx, r_cb, r_id, r_pos, r_val, _, _ = _streams(seed)
     indices = random_words(r_idx, (E, N, K * bits // 32))
     if mode == MODE_V2:
@@ -196,11 +218,16 @@ def random_weights(mode: int, bits: int, N: int, K: int, *, E: int = 1, L: int =
         cols.append(c)
         vals.append(v)
     row_ptr = np.concatenate(ptrs + [np.array([base], dtype=np.int64)]).astype(np.int32)
+    gscale = gmid = None
+    if affine:
+        r_aff = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, 7])))    # a stream of its own
+        gscale = _f16_bits(r_aff.uniform(0.5, 2.0, size=(E, N, K // GROUP)))
+        gmid = _f16_bits(r_aff.normal(0.0, cb_sigma / 2, size=(E, N, K // GROUP)))
     return XfpHostWeights(mode=mode, bits=bits, N=N, K=K, E=E, L=Lx, indices=indices,
                           codebooks=codebooks, group_ids=ids, out_row_ptr=row_ptr,
                           out_col=np.concatenate(cols) if cols else np.zeros(0, np.int32),
                           out_val=np.concatenate(vals) if vals else np.zeros(0, np.uint16),
-                          meta={"recipe": "uniform-random", "seed": seed})
+                          meta={"recipe": "uniform-random", "seed": seed}, group_scale=gscale, group_mid=gmid)
 
 
 def _lloyd_rows(bulk: np.ndarray, levels: int, iters: int) -> np.ndarray:
