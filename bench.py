@@ -70,7 +70,8 @@ def build_workload(cfg: int, ring_bytes: int):
         d = dW.desc
         return xfp.binding.make_descriptor(d.mode, d.bits, d.N, d.K, d.L, d.E, t["indices"],
                                            t["codebooks"], t["group_ids"], t["out_row_ptr"],
-                                           t["out_col"], t["out_val"])
+                                           t["out_col"], t["out_val"], group_scale=t.get("group_scale"),
+                                           group_mid=t.get("group_mid"))
 
     if cfg in (1, 2, 3, 5):
         M = 16 if cfg == 5 else 1

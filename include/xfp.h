@@ -56,9 +56,10 @@
  *    Field k of a row is bits [k*bits, (k+1)*bits) of the row's bit stream,
  *    least significant bit first; the stream fills word 0 from bit 0 upward,
  *    then word 1, ...  For bits = 2 and 4 this is the paper's table 2 (16 and
- *    8 values per uint32, no reserve bits).  For bits = 3 the stream is dense
- *    (3.0 bit per weight, fields cross word boundaries), which is NOT the
- *    paper's 10-values-per-word form.
+ *    8 values per uint32, no reserve bits).  For bits = 3, 5 and 6 the stream is
+ *    dense (3.0, 5.0, 6.0 bit per weight, fields cross word boundaries), which
+ *    is NOT the table's word forms with reserve bits (10 per uint32, 3 per
+ *    uint16, 5 per uint32); xfp_repack_words converts those once at load.
  *  - group: 128 consecutive k of one output row (K % 128 == 0).
  *  - outliers: CSR over the stacked E*N rows: int32 row_ptr [E*N + 1] holding
  *    absolute offsets (row_ptr[0] == 0), int32 col [nnz] ascending within a
@@ -80,7 +81,7 @@ typedef enum {
     XFP_OK = 0,
     XFP_ERR_NULL = -1,        /* a required pointer is NULL                         */
     XFP_ERR_SHAPE = -2,       /* N, K, M, E <= 0, T < 0, K % group != 0, ld too small */
-    XFP_ERR_UNSUPPORTED = -3, /* bits, mode, L, group, dtype, flags, struct_size     */
+    XFP_ERR_UNSUPPORTED = -3, /* bits, mode, L, group, dtype, flags, struct_size; a row no kernel takes */
     XFP_ERR_ALIGN = -4,       /* a base pointer or a leading dimension is misaligned */
     XFP_ERR_HIP = -5,         /* the HIP runtime refused the launch                  */
     XFP_ERR_SCRATCH = -6      /* xfp_gemv_noalloc: the call needs more scratch than the static array holds */
@@ -95,6 +96,16 @@ typedef enum { XFP_F16 = 0, XFP_F32 = 1, XFP_BF16 = 2 } xfp_dtype;   /* type of 
  * same call on the converted activations. */
 #define XFP_X_BF16 0x100
 
+/* xfp_weights.flags, bit 0: a V2a matrix whose groups carry a scale and a
+ * mid-point next to their library id (paper section 3.4; with the one-byte id a
+ * 40-bit record per group, the 0.31 bit per weight of section 3.2).  The paper
+ * gives no formula; reading taken: the affine map
+ *     C[n][k] = library[id][q] * scale[n][k/128] + mid[n][k/128],
+ * evaluated in fp32 on a group's partial sums (scale * sum(x * entry) + mid *
+ * sum(x), which is the same thing by linearity).  Scale 1 and mid-point 0 give
+ * the plain library.  Such matrices run the general kernel (one wave per row). */
+#define XFP_FLAG_GROUP_AFFINE 1u
+
 #define XFP_GROUP 128
 #define XFP_MAX_LIBRARY 256          /* V2a ids are one byte each */
 
@@ -102,12 +113,12 @@ typedef enum { XFP_F16 = 0, XFP_F32 = 1, XFP_BF16 = 2 } xfp_dtype;   /* type of 
 typedef struct xfp_weights {
     uint32_t struct_size;       /* sizeof(xfp_weights), checked                              */
     uint32_t mode;              /* xfp_mode                                                  */
-    uint32_t bits;              /* 2, 3 or 4                                                 */
+    uint32_t bits;              /* 2 .. 6 (paper section 3.1); 5 and 6 run the general kernel only */
     uint32_t group;             /* must be 128                                               */
     uint32_t N, K;              /* output channels, input channels; K % 128 == 0             */
     uint32_t L;                 /* V2a: library size, 1..256 (paper default 32); V2: 0       */
     uint32_t E;                 /* matrices stacked in this bank                             */
-    uint32_t flags;             /* must be 0                                                 */
+    uint32_t flags;             /* 0 or XFP_FLAG_GROUP_AFFINE                                */
     uint32_t reserved;          /* must be 0                                                 */
     const uint32_t *indices;    /* [E][N][K*bits/32]                                         */
     const uint16_t *codebooks;  /* fp16: V2 [E][N][1<<bits], V2a [E][L][1<<bits]             */
@@ -115,6 +126,8 @@ typedef struct xfp_weights {
     const int32_t *out_row_ptr; /* [E*N + 1]                                                 */
     const int32_t *out_col;     /* [nnz] (may be NULL when nnz == 0)                         */
     const uint16_t *out_val;    /* fp16 [nnz] (may be NULL when nnz == 0)                    */
+    const uint16_t *group_scale;/* fp16 [E][N][K/128] with XFP_FLAG_GROUP_AFFINE, else NULL  */
+    const uint16_t *group_mid;  /* fp16 [E][N][K/128] with XFP_FLAG_GROUP_AFFINE, else NULL  */
 } xfp_weights;
 
 /*
@@ -153,7 +166,8 @@ int xfp_gemv(const xfp_weights *W, const void *x, int M, int64_t ldx,
  * scratch plane is too small, this one returns XFP_ERR_SCRATCH and launches
  * nothing: M >= 2 with K > 32768; M >= 2, K > 8192 with S * 16 * N > 2^20
  * (S = ceil(K / 8192) slices); rows above 16384 columns that the M = 1 path
- * cuts into S equal slices with S * M * N > 2^20.
+ * cuts into S equal slices with S * M * N > 2^20 (4-bit V2 rows of that length
+ * take the tile kernel, which needs no scratch).
  * Every call on a GPU uses that GPU's one array, which keeps the last call's
  * contents (nothing in it has to start at zero: every plane is written before it
  * is read): calls that overlap in time on one GPU (two streams, two threads)
@@ -248,11 +262,23 @@ int xfp_convert_bf16_to_f16(const void *src, int64_t ld_src, void *dst, int rows
 int xfp_repack_word10(const uint32_t *src, int64_t rows, int K, uint32_t *dst, void *hip_stream);
 
 /*
+ * The same conversion for every width of the packing table (section 3.3, table
+ * 2): bits = 2, 3, 4, 6 are 16, 10, 8, 5 values per uint32, bits = 5 is 3 values
+ * per uint16 (one reserve bit).  Same reading: value k in word k / per at bit
+ * bits * (k % per), reserve bits on top and ignored, a row takes ceil(K / per)
+ * words, rows back to back.  src: DEVICE pointer to the words (2-byte aligned for
+ * bits = 5, else 4-byte); dst [rows][K*bits/32] as for xfp_repack_word10.
+ * For bits = 2 and 4 the word form is the dense stream and this is a copy.
+ */
+int xfp_repack_words(const void *src, int64_t rows, int K, int bits, uint32_t *dst, void *hip_stream);
+
+/*
  * Parity hooks: the first two fused steps on their own (paper section 5,
  * steps 1 and 2), so that they can be compared bit for bit.
  * xfp_unpack_indices writes every index as one byte, idx_out [E*N][K].
  * xfp_dequant_bulk writes the selected codebook entry's fp16 bit pattern,
- * w_out [E*N][K]; the outlier term is not included.
+ * w_out [E*N][K]; the outlier term is not included, nor is the scale and
+ * mid-point of XFP_FLAG_GROUP_AFFINE (both are applied in the decode).
  */
 int xfp_unpack_indices(const xfp_weights *W, uint8_t *idx_out, void *hip_stream);
 int xfp_dequant_bulk(const xfp_weights *W, uint16_t *w_out, void *hip_stream);

@@ -38,6 +38,7 @@ class xfp_weights(ctypes.Structure):
         ("reserved", ctypes.c_uint32),
         ("indices", ctypes.c_void_p), ("codebooks", ctypes.c_void_p), ("group_ids", ctypes.c_void_p),
         ("out_row_ptr", ctypes.c_void_p), ("out_col", ctypes.c_void_p), ("out_val", ctypes.c_void_p),
+        ("group_scale", ctypes.c_void_p), ("group_mid", ctypes.c_void_p),
     ]
 
 
@@ -65,6 +66,7 @@ def load_library():
     lib.xfp_gemv_moe_combine.argtypes = [wp, vp, i32, vp, i64, vp, vp, i32, vp]
     lib.xfp_convert_bf16_to_f16.argtypes = [vp, i64, vp, i32, i32, vp]
     lib.xfp_repack_word10.argtypes = [vp, i64, i32, vp, vp]
+    lib.xfp_repack_words.argtypes = [vp, i64, i32, i32, vp, vp]
     lib.xfp_check_contents.argtypes = [wp, i64, vp, i32, vp, vp]
     lib.xfp_dequant_bulk.argtypes = [wp, vp, vp]
     lib.xfp_probe_read.argtypes = [vp, u64, vp, vp]
@@ -72,7 +74,7 @@ def load_library():
     lib.xfp_select_kernel.argtypes = [i32]
     lib.xfp_strerror.argtypes = [i32]
     lib.xfp_strerror.restype = ctypes.c_char_p
-    for name in ("xfp_gemv", "xfp_gemv_noalloc", "xfp_gemv_moe", "xfp_gemv_moe_silu_mul", "xfp_gemv_moe_combine", "xfp_check_contents", "xfp_convert_bf16_to_f16", "xfp_repack_word10", "xfp_unpack_indices", "xfp_dequant_bulk",
+    for name in ("xfp_gemv", "xfp_gemv_noalloc", "xfp_gemv_moe", "xfp_gemv_moe_silu_mul", "xfp_gemv_moe_combine", "xfp_check_contents", "xfp_convert_bf16_to_f16", "xfp_repack_word10", "xfp_repack_words", "xfp_unpack_indices", "xfp_dequant_bulk",
                  "xfp_probe_read", "xfp_probe_copy", "xfp_version", "xfp_init", "xfp_select_kernel"):
         getattr(lib, name).restype = i32
     _lib = lib
@@ -137,17 +139,23 @@ class DeviceWeights:
     def mode(self): return int(self.desc.mode)
 
 
+XFP_FLAG_GROUP_AFFINE = 1
+
+
 def make_descriptor(mode, bits, N, K, L, E, indices, codebooks, group_ids, out_row_ptr, out_col,
-                    out_val, group=128) -> DeviceWeights:
+                    out_val, group=128, group_scale=None, group_mid=None) -> DeviceWeights:
     """Wrap device tensors (already laid out as include/xfp.h states) in a descriptor."""
     d = xfp_weights()
     d.struct_size = ctypes.sizeof(xfp_weights)
     d.mode, d.bits, d.group, d.N, d.K, d.L, d.E = mode, bits, group, N, K, L, E
-    d.flags = d.reserved = 0
+    d.flags = XFP_FLAG_GROUP_AFFINE if group_scale is not None else 0
+    d.reserved = 0
     d.indices, d.codebooks, d.group_ids = _ptr(indices), _ptr(codebooks), _ptr(group_ids)
     d.out_row_ptr, d.out_col, d.out_val = _ptr(out_row_ptr), _ptr(out_col), _ptr(out_val)
+    d.group_scale, d.group_mid = _ptr(group_scale), _ptr(group_mid)
     return DeviceWeights(d, dict(indices=indices, codebooks=codebooks, group_ids=group_ids,
-                                 out_row_ptr=out_row_ptr, out_col=out_col, out_val=out_val))
+                                 out_row_ptr=out_row_ptr, out_col=out_col, out_val=out_val,
+                                 group_scale=group_scale, group_mid=group_mid))
 
 
 def _to_dev(a: Optional[np.ndarray], device, view=None):
@@ -165,7 +173,9 @@ def upload(W, device="cuda") -> DeviceWeights:
         W.mode, W.bits, W.N, W.K, W.L, W.E,
         _to_dev(W.indices, device, np.int32), _to_dev(W.codebooks, device, np.int16),
         _to_dev(W.group_ids, device), _to_dev(W.out_row_ptr, device),
-        _to_dev(W.out_col, device), _to_dev(W.out_val, device, np.int16), group=W.group)
+        _to_dev(W.out_col, device), _to_dev(W.out_val, device, np.int16), group=W.group,
+        group_scale=_to_dev(getattr(W, "group_scale", None), device, np.int16),
+        group_mid=_to_dev(getattr(W, "group_mid", None), device, np.int16))
 
 
 def _y_code(dtype, x: Optional[torch.Tensor] = None) -> int:
@@ -291,6 +301,19 @@ def xfp_repack_word10(words: torch.Tensor, K: int, stream=None) -> torch.Tensor:
     dst = torch.empty((rows, K * 3 // 32), dtype=torch.int32, device=words.device)
     _check(load_library().xfp_repack_word10(_ptr(w2), rows, int(K), _ptr(dst), _stream(stream)))
     return dst.reshape(*words.shape[:-1], K * 3 // 32)
+
+
+def xfp_repack_words(words: torch.Tensor, K: int, bits: int, stream=None) -> torch.Tensor:
+    """Dense stream [rows, K*bits/32] (int32 tensor) of indices stored in a word form of the paper's table 2
+    (16 / 10 / 8 / 5 per 32-bit word at 2 / 3 / 4 / 6 bits, 3 per 16-bit word at 5 bits); once at load."""
+    per = {2: 16, 3: 10, 4: 8, 5: 3, 6: 5}[bits]
+    w2 = words.reshape(-1, words.shape[-1]).contiguous()
+    rows = int(w2.shape[0])
+    if w2.element_size() != (2 if bits == 5 else 4) or int(w2.shape[1]) != (K + per - 1) // per:
+        raise XfpError(-2, "words must be 16-bit (5 bits) or 32-bit, [rows, ceil(K/per)]")
+    dst = torch.empty((rows, K * bits // 32), dtype=torch.int32, device=words.device)
+    _check(load_library().xfp_repack_words(_ptr(w2), rows, int(K), int(bits), _ptr(dst), _stream(stream)))
+    return dst.reshape(*words.shape[:-1], K * bits // 32)
 
 
 def xfp_unpack_indices(W: DeviceWeights, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:

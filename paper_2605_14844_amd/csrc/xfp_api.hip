@@ -41,8 +41,9 @@ int check_weights(const xfp_weights *W)
     if (!W) return XFP_ERR_NULL;
     if (W->struct_size != sizeof(xfp_weights)) return XFP_ERR_UNSUPPORTED;
     if (W->mode != XFP_MODE_V2 && W->mode != XFP_MODE_V2A) return XFP_ERR_UNSUPPORTED;
-    if (W->bits < 2 || W->bits > 4) return XFP_ERR_UNSUPPORTED;
-    if (W->group != XFP_GROUP || W->flags != 0 || W->reserved != 0) return XFP_ERR_UNSUPPORTED;
+    if (W->bits < 2 || W->bits > 6) return XFP_ERR_UNSUPPORTED;
+    if (W->group != XFP_GROUP || (W->flags & ~XFP_FLAG_GROUP_AFFINE) != 0 || W->reserved != 0) return XFP_ERR_UNSUPPORTED;
+    if ((W->flags & XFP_FLAG_GROUP_AFFINE) && W->mode != XFP_MODE_V2A) return XFP_ERR_UNSUPPORTED;
     if (W->N == 0 || W->K == 0 || W->E == 0) return XFP_ERR_SHAPE;
     if (W->K % XFP_GROUP != 0) return XFP_ERR_SHAPE;
     if ((uint64_t)W->E * W->N > 0x7fffffffull) return XFP_ERR_SHAPE;
@@ -51,6 +52,12 @@ int check_weights(const xfp_weights *W)
         if (!W->group_ids) return XFP_ERR_NULL;
     } else if (W->L != 0) {
         return XFP_ERR_UNSUPPORTED;
+    }
+    if (W->flags & XFP_FLAG_GROUP_AFFINE) {
+        if (!W->group_scale || !W->group_mid) return XFP_ERR_NULL;
+        if (misaligned(W->group_scale, 2) || misaligned(W->group_mid, 2)) return XFP_ERR_ALIGN;
+    } else if (W->group_scale || W->group_mid) {
+        return XFP_ERR_UNSUPPORTED;                            // arrays given but not announced in flags
     }
     if (!W->indices || !W->codebooks || !W->out_row_ptr) return XFP_ERR_NULL;
     if (misaligned(W->indices, 16) || misaligned(W->codebooks, 16) || misaligned(W->out_row_ptr, 4) ||
@@ -72,6 +79,8 @@ xfp::DecodeArgs base_args(const xfp_weights *W)
     a.N = W->N;
     a.K = W->K;
     a.L = W->L;
+    a.gscale = W->group_scale;
+    a.gmid = W->group_mid;
     return a;
 }
 
@@ -109,6 +118,9 @@ struct Scratch {
     }
 };
 
+// Formats only the general kernel takes: 5- and 6-bit indices, a scale and a mid-point per group.
+bool general_only(const xfp_weights *W) { return W->bits > 4 || (W->flags & XFP_FLAG_GROUP_AFFINE) != 0; }
+
 // Longest row the general kernel can stage: x (2 K bytes) and its tables share the
 // 160 KB of LDS of a compute unit.
 bool rows_fits(const xfp_weights *W)
@@ -122,6 +134,7 @@ bool rows_fits(const xfp_weights *W)
 bool decodable(const xfp_weights *W, int slots)
 {
     const int bits = (int)W->bits, mode = (int)W->mode;
+    if (general_only(W)) return rows_fits(W);
     return xfp::stream_supports(bits, mode, W->K, W->L) || xfp::splitk_slices(bits, mode, W->N, W->K, W->L, slots) ||
            rows_fits(W);
 }
@@ -154,7 +167,7 @@ std::atomic<int> g_kernel_choice{XFP_KERNEL_AUTO};
 
 bool prefer_tile(const xfp_weights *W, int slots)
 {
-    if (!xfp::tile_supports((int)W->bits, (int)W->mode, W->N, W->K, slots)) return false;
+    if (general_only(W) || !xfp::tile_supports((int)W->bits, (int)W->mode, W->N, W->K, slots)) return false;
     const int choice = g_kernel_choice.load(std::memory_order_relaxed);
     if (choice == XFP_KERNEL_TILE) return true;
     if (choice == XFP_KERNEL_STREAM) return false;
@@ -166,9 +179,10 @@ int single_token(const xfp_weights *W, xfp::DecodeArgs c, int y_dtype, Scratch &
 {
     const int bits = (int)W->bits, mode = (int)W->mode;
     const bool y_f32 = y_dtype == XFP_F32;
+    const bool gen = general_only(W);
     if (prefer_tile(W, 1)) return finish(xfp::launch_decode_tile(bits, y_f32, c, 1, s));
-    if (xfp::stream_supports(bits, mode, W->K, W->L)) return finish(xfp::launch_decode_stream(bits, mode, y_f32, c, 1, s));
-    if (const int S = xfp::splitk_slices(bits, mode, W->N, W->K, W->L, 1)) {
+    if (!gen && xfp::stream_supports(bits, mode, W->K, W->L)) return finish(xfp::launch_decode_stream(bits, mode, y_f32, c, 1, s));
+    if (const int S = gen ? 0 : xfp::splitk_slices(bits, mode, W->N, W->K, W->L, 1)) {
         const xfp::Workspace *ws = nullptr;
         hipError_t err = sc.get(&ws);
         if (err != hipSuccess) return finish(err);
@@ -194,7 +208,8 @@ int decode(const xfp_weights *W, const int32_t *eids, int slots, const void *x, 
     a.y_stride = ldy;
     a.y_bf16 = y_dtype == XFP_BF16;
     a.x_bf16 = x_bf16;
-    if (!eids && xfp::batch_supports(bits, mode, W->L, W->N, W->K, slots)) {
+    const bool gen = general_only(W);
+    if (!gen && !eids && xfp::batch_supports(bits, mode, W->L, W->N, W->K, slots)) {
         // batched tokens: the weights are read once per 16 tokens; the chunks run in
         // stream order, so they share the workspace
         const size_t ysz = y_dtype == XFP_F32 ? 4 : 2;
@@ -213,9 +228,9 @@ int decode(const xfp_weights *W, const int32_t *eids, int slots, const void *x, 
         return XFP_OK;
     }
     if (prefer_tile(W, slots)) return finish(xfp::launch_decode_tile(bits, y_dtype == XFP_F32, a, slots, s));
-    if (xfp::stream_supports(bits, mode, W->K, W->L))
+    if (!gen && xfp::stream_supports(bits, mode, W->K, W->L))
         return finish(xfp::launch_decode_stream(bits, mode, y_dtype == XFP_F32, a, slots, s));
-    if (const int S = xfp::splitk_slices(bits, mode, W->N, W->K, W->L, slots)) {
+    if (const int S = gen ? 0 : xfp::splitk_slices(bits, mode, W->N, W->K, W->L, slots)) {
         const xfp::Workspace *ws = nullptr;
         hipError_t err = sc.get(&ws);
         if (err != hipSuccess) return finish(err);
@@ -233,7 +248,7 @@ int decode_silu_mul(const xfp_weights *W, const int32_t *eids, int slots, const 
 {
     const int x_flag = h_dtype & XFP_X_BF16;
     h_dtype &= 0xFF;
-    if (xfp::stream_supports((int)W->bits, (int)W->mode, W->K, W->L)) {
+    if (!general_only(W) && xfp::stream_supports((int)W->bits, (int)W->mode, W->K, W->L)) {
         xfp::DecodeArgs a = base_args(W);
         a.y_bf16 = h_dtype == XFP_BF16;
         a.x_bf16 = x_flag != 0;
@@ -290,9 +305,11 @@ int xfp_gemv_noalloc(const xfp_weights *W, const void *x, int M, int64_t ldx, vo
     // a route that only the size of the scratch planes closes is refused, not replaced
     const int bits = (int)W->bits, mode = (int)W->mode;
     constexpr uint64_t kNoCap = ~0ull;
-    if (xfp::batch_supports(bits, mode, W->L, W->N, W->K, M, kNoCap, kNoCap) != xfp::batch_supports(bits, mode, W->L, W->N, W->K, M))
+    if (!general_only(W) &&
+        xfp::batch_supports(bits, mode, W->L, W->N, W->K, M, kNoCap, kNoCap) != xfp::batch_supports(bits, mode, W->L, W->N, W->K, M))
         return XFP_ERR_SCRATCH;
-    if (!xfp::batch_supports(bits, mode, W->L, W->N, W->K, M) && !xfp::stream_supports(bits, mode, W->K, W->L) &&
+    if (!general_only(W) && !prefer_tile(W, M) &&
+        !xfp::batch_supports(bits, mode, W->L, W->N, W->K, M) && !xfp::stream_supports(bits, mode, W->K, W->L) &&
         xfp::splitk_slices(bits, mode, W->N, W->K, W->L, M, kNoCap) != xfp::splitk_slices(bits, mode, W->N, W->K, W->L, M))
         return XFP_ERR_SCRATCH;
     if (!decodable(W, M)) return XFP_ERR_UNSUPPORTED;
@@ -355,7 +372,7 @@ int xfp_gemv_moe_combine(const xfp_weights *bank, const int32_t *expert_ids, int
     if (x_slot_stride % 8 != 0 || misaligned(expert_ids, 4) || misaligned(slot_weights, 4)) return XFP_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const int yd = y_dtype & 0xFF;
-    if (xfp::combine_supports((int)bank->bits, (int)bank->mode, bank->K, T)) {
+    if (!general_only(bank) && xfp::combine_supports((int)bank->bits, (int)bank->mode, bank->K, T)) {
         xfp::DecodeArgs a = base_args(bank);
         a.x = static_cast<const uint16_t *>(x);
         a.y = y;
@@ -375,14 +392,20 @@ int xfp_gemv_moe_combine(const xfp_weights *bank, const int32_t *expert_ids, int
     return finish(xfp::launch_moe_combine(ws->epi, slot_weights, bank->N, T, y, yd == XFP_F32, yd == XFP_BF16, s));
 }
 
-int xfp_repack_word10(const uint32_t *src, int64_t rows, int K, uint32_t *dst, void *hip_stream)
+int xfp_repack_words(const void *src, int64_t rows, int K, int bits, uint32_t *dst, void *hip_stream)
 {
     if (!src || !dst) return XFP_ERR_NULL;
+    if (bits < 2 || bits > 6) return XFP_ERR_UNSUPPORTED;
     if (rows < 0 || K <= 0 || K % xfp::kGroup != 0) return XFP_ERR_SHAPE;
-    if ((uint64_t)rows * (uint64_t)(K / 32 * 3) >= (1ull << 40)) return XFP_ERR_SHAPE;
-    if (misaligned(src, 4) || misaligned(dst, 4)) return XFP_ERR_ALIGN;
+    if ((uint64_t)rows * (uint64_t)(K / 32 * bits) >= (1ull << 40)) return XFP_ERR_SHAPE;
+    if (misaligned(src, bits == 5 ? 2 : 4) || misaligned(dst, 4)) return XFP_ERR_ALIGN;
     if (rows == 0) return XFP_OK;
-    return finish(xfp::launch_repack_word10(src, (uint64_t)rows, (uint32_t)K, dst, static_cast<hipStream_t>(hip_stream)));
+    return finish(xfp::launch_repack_words(src, (uint64_t)rows, (uint32_t)K, bits, dst, static_cast<hipStream_t>(hip_stream)));
+}
+
+int xfp_repack_word10(const uint32_t *src, int64_t rows, int K, uint32_t *dst, void *hip_stream)
+{
+    return xfp_repack_words(src, rows, K, 3, dst, hip_stream);
 }
 
 int xfp_convert_bf16_to_f16(const void *src, int64_t ld_src, void *dst, int rows, int cols, void *hip_stream)
@@ -452,7 +475,7 @@ const char *xfp_strerror(int status)
     case XFP_OK: return "ok";
     case XFP_ERR_NULL: return "a required pointer is NULL";
     case XFP_ERR_SHAPE: return "bad shape (sizes must be positive, K a multiple of 128, leading dimensions large enough)";
-    case XFP_ERR_UNSUPPORTED: return "unsupported format or shape (bits 2..4, mode V2/V2a, group 128, flags 0, output fp16/bf16/fp32; a row too long for every kernel; a result too large for the scratch plane)";
+    case XFP_ERR_UNSUPPORTED: return "unsupported format or shape (bits 2..6, mode V2/V2a, group 128, flags 0 or 1 (V2a only), output fp16/bf16/fp32; a row too long for every kernel; a result too large for the scratch plane)";
     case XFP_ERR_ALIGN: return "a pointer or leading dimension is misaligned";
     case XFP_ERR_SCRATCH: return "the call needs more scratch memory than xfp_gemv_noalloc's static array holds (M >= 2: K <= 32768 and S * 16 * N <= 2^20; sliced rows: S * M * N <= 2^20)";
     case XFP_ERR_HIP:

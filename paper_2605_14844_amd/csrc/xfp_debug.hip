@@ -65,6 +65,8 @@ hipError_t launch_unpack(int bits, const uint32_t *idx, uint64_t rows, uint32_t 
     switch (bits) {
     case 2: hipLaunchKernelGGL(unpack_kernel<2>, grid, dim3(256), 0, s, idx, units, out); break;
     case 3: hipLaunchKernelGGL(unpack_kernel<3>, grid, dim3(256), 0, s, idx, units, out); break;
+    case 5: hipLaunchKernelGGL(unpack_kernel<5>, grid, dim3(256), 0, s, idx, units, out); break;
+    case 6: hipLaunchKernelGGL(unpack_kernel<6>, grid, dim3(256), 0, s, idx, units, out); break;
     default: hipLaunchKernelGGL(unpack_kernel<4>, grid, dim3(256), 0, s, idx, units, out); break;
     }
     return hipGetLastError();
@@ -89,6 +91,8 @@ hipError_t launch_dequant(int bits, int mode, const DecodeArgs &a, uint32_t E, u
     switch (bits) {
     case 2: launch_dequant_b<2>(mode, a, units, out, grid, s); break;
     case 3: launch_dequant_b<3>(mode, a, units, out, grid, s); break;
+    case 5: launch_dequant_b<5>(mode, a, units, out, grid, s); break;
+    case 6: launch_dequant_b<6>(mode, a, units, out, grid, s); break;
     default: launch_dequant_b<4>(mode, a, units, out, grid, s); break;
     }
     return hipGetLastError();

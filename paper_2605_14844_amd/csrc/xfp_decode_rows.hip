@@ -1,4 +1,5 @@
-// General fused decode kernel: any K that is a multiple of 128, any N.
+// General fused decode kernel: any K that is a multiple of 128, any N, every bit width of the paper's
+// packing table (2 .. 6), and the only kernel for V2a matrices with a scale and a mid-point per group.
 //
 // One wave owns one output row at a time (no atomics, a fixed summation
 // order).  The activation row is staged once per workgroup in LDS (paper
@@ -26,7 +27,10 @@ __device__ __forceinline__ void accumulate_pairs(const LaneWords<BITS> &lw, cons
     }
 }
 
-template <int BITS, int MODE, bool YF32>
+// AFF (V2a only): every group carries a scale and a mid-point (paper section 3.4; no formula given, reading
+// taken: entry * scale + mid).  By linearity a unit of 32 weights inside one group contributes
+// scale * sum(x * entry) + mid * sum(x), both sums in fp32, one fused multiply-add on top.
+template <int BITS, int MODE, bool YF32, bool AFF>
 __global__ __launch_bounds__(kRowsThreads) void decode_rows_kernel(DecodeArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -85,7 +89,18 @@ __global__ __launch_bounds__(kRowsThreads) void decode_rows_kernel(DecodeArgs a)
                 uint4 v = reinterpret_cast<const uint4 *>(xs)[u * 4 + i];
                 xw[4 * i] = v.x; xw[4 * i + 1] = v.y; xw[4 * i + 2] = v.z; xw[4 * i + 3] = v.w;
             }
-            accumulate_pairs<BITS, 0>(lw, tbl, xw, acc);
+            if constexpr (AFF) {
+                const size_t g = ((size_t)e * N + row) * (K / kGroup) + u / (kGroup / kLaneWeights);
+                const float sc = half_bits_to_float(a.gscale[g]), md = half_bits_to_float(a.gmid[g]);
+                float au = 0.f, xs = 0.f;
+                accumulate_pairs<BITS, 0>(lw, tbl, xw, au);
+                const half2_t ones = {(_Float16)1.0f, (_Float16)1.0f};
+#pragma unroll
+                for (int i = 0; i < 16; ++i) xs = dot2(ones, as_half2(xw[i]), xs);
+                acc += fmaf(sc, au, md * xs);
+            } else {
+                accumulate_pairs<BITS, 0>(lw, tbl, xw, acc);
+            }
         }
         // a7: outlier fold, CSR row owned by this wave.
         const int32_t j1 = rp[row + 1];
@@ -100,13 +115,13 @@ __global__ __launch_bounds__(kRowsThreads) void decode_rows_kernel(DecodeArgs a)
     }
 }
 
-template <int BITS, int MODE, bool YF32>
+template <int BITS, int MODE, bool YF32, bool AFF = false>
 static hipError_t launch_rows_t(const DecodeArgs &a, int slots, hipStream_t s)
 {
     size_t table_halves = MODE == 1 ? (size_t)a.L << BITS : (size_t)kRowsWaves << BITS;
     size_t smem = (size_t)a.K * 2 + table_halves * 2;
     dim3 grid((a.N + a.rows_per_block - 1) / a.rows_per_block, slots);
-    auto kern = decode_rows_kernel<BITS, MODE, YF32>;
+    auto kern = decode_rows_kernel<BITS, MODE, YF32, AFF>;
     if (smem > 48 * 1024) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -121,6 +136,8 @@ static hipError_t launch_rows_b(int mode, bool y_f32, const DecodeArgs &a, int s
 {
     if (mode == 0)
         return y_f32 ? launch_rows_t<BITS, 0, true>(a, slots, s) : launch_rows_t<BITS, 0, false>(a, slots, s);
+    if (a.gscale)
+        return y_f32 ? launch_rows_t<BITS, 1, true, true>(a, slots, s) : launch_rows_t<BITS, 1, false, true>(a, slots, s);
     return y_f32 ? launch_rows_t<BITS, 1, true>(a, slots, s) : launch_rows_t<BITS, 1, false>(a, slots, s);
 }
 
@@ -130,6 +147,8 @@ hipError_t launch_decode_rows(int bits, int mode, bool y_f32, const DecodeArgs &
     switch (bits) {
     case 2: return launch_rows_b<2>(mode, y_f32, a, slots, s);
     case 3: return launch_rows_b<3>(mode, y_f32, a, slots, s);
+    case 5: return launch_rows_b<5>(mode, y_f32, a, slots, s);
+    case 6: return launch_rows_b<6>(mode, y_f32, a, slots, s);
     default: return launch_rows_b<4>(mode, y_f32, a, slots, s);
     }
 }

@@ -37,6 +37,8 @@ struct DecodeArgs {
     uint32_t fuse_half;
     uint32_t y_bf16;       // the 16-bit output type is bf16 instead of fp16
     uint32_t x_bf16;       // x holds bf16 values; every kernel converts them to fp16 as it loads them
+    const uint16_t *gscale;   // V2a with a scale and a mid-point per group (general kernel only): fp16 [E][N][K/128]
+    const uint16_t *gmid;
 };
 
 // Device memory a call may need beyond its inputs and outputs.  One call gets ONE
@@ -129,8 +131,8 @@ hipError_t launch_moe_combine(const float *part, const float *w, uint32_t N, int
 // bf16 [rows][ld] -> fp16 [rows][K] (exact inside fp16's normal range, saturating beyond it);
 // the stand-alone form of the conversion every decode kernel applies when x_bf16 is set
 hipError_t launch_bf16_to_f16(const void *src, int64_t ld, void *dst, uint32_t rows, uint32_t K, hipStream_t s);
-// 3-bit indices, ten per uint32 [rows][ceil(K/10)] -> dense stream [rows][K*3/32]
-hipError_t launch_repack_word10(const uint32_t *src, uint64_t rows, uint32_t K, uint32_t *dst, hipStream_t s);
+// indices in a word form of the packing table [rows][ceil(K/per)] -> dense stream [rows][K*bits/32]
+hipError_t launch_repack_words(const void *src, uint64_t rows, uint32_t K, int bits, uint32_t *dst, hipStream_t s);
 hipError_t launch_unpack(int bits, const uint32_t *idx, uint64_t rows, uint32_t K, uint8_t *out,
                          hipStream_t s);
 hipError_t launch_dequant(int bits, int mode, const DecodeArgs &a, uint32_t E, uint16_t *out,

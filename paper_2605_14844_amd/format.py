@@ -23,7 +23,7 @@ import numpy as np
 MAGIC = b"XFPMI355"
 VERSION = 1
 ALIGN = 256
-_SECTIONS = ("indices", "codebooks", "group_ids", "out_row_ptr", "out_col", "out_val")
+_SECTIONS = ("indices", "codebooks", "group_ids", "out_row_ptr", "out_col", "out_val", "group_scale", "group_mid")
 
 
 def save_xfp(path: str, W) -> None:
@@ -31,7 +31,7 @@ def save_xfp(path: str, W) -> None:
                 L=int(W.L), E=int(W.E), sections=[])
     arrays = []
     for name in _SECTIONS:
-        a = getattr(W, name)
+        a = getattr(W, name, None)
         if a is None:
             continue
         a = np.ascontiguousarray(a)

@@ -19,16 +19,17 @@ def facts():
     return out
 
 
-@pytest.mark.parametrize("mode,bits,E", [(xi.MODE_V2, 4, 1), (xi.MODE_V2A, 3, 1), (xi.MODE_V2, 3, 5),
-                                         (xi.MODE_V2, 2, 1)])
-def test_save_load_bit_identical(tmp_path, mode, bits, E):
-    W = xi.random_weights(mode, bits, 48, 384, E=E, density=0.004, seed=3)
+@pytest.mark.parametrize("mode,bits,E,affine", [(xi.MODE_V2, 4, 1, False), (xi.MODE_V2A, 3, 1, False), (xi.MODE_V2, 3, 5, False),
+                                                (xi.MODE_V2, 2, 1, False), (xi.MODE_V2, 5, 2, False), (xi.MODE_V2A, 6, 1, False),
+                                                (xi.MODE_V2A, 4, 3, True)])
+def test_save_load_bit_identical(tmp_path, mode, bits, E, affine):
+    W = xi.random_weights(mode, bits, 48, 384, E=E, density=0.004, seed=3, affine=affine)
     p = str(tmp_path / "w.xfp")
     save_xfp(p, W)
     for mmap in (True, False):
         R = load_xfp(p, mmap=mmap)
         assert (R.mode, R.bits, R.N, R.K, R.L, R.E, R.group) == (W.mode, W.bits, W.N, W.K, W.L, W.E, 128)
-        for name in ("indices", "codebooks", "group_ids", "out_row_ptr", "out_col", "out_val"):
+        for name in ("indices", "codebooks", "group_ids", "out_row_ptr", "out_col", "out_val", "group_scale", "group_mid"):
             a, b = getattr(W, name), getattr(R, name)
             if a is None:
                 assert b is None

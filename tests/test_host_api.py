@@ -45,7 +45,7 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert hasattr(lib, n), n
     assert xfp.xfp_version() >= 0x100
-    assert ctypes.sizeof(xfp_weights) == 88
+    assert ctypes.sizeof(xfp_weights) == 104
 
 
 def test_strerror_texts():
@@ -83,11 +83,16 @@ def test_shape_errors():
 
 
 def test_unsupported_format():
-    for bits in (0, 1, 5, 6, 7, 8):
+    for bits in (0, 1, 7, 8):
         assert gemv(desc(bits=bits)) == -3
     assert gemv(desc(mode=2)) == -3
     assert gemv(desc(group=64)) == -3
-    assert gemv(desc(flags=1)) == -3
+    assert gemv(desc(flags=1)) == -3                           # a scale and mid-point per group: V2a only
+    assert gemv(desc(flags=2)) == -3 and gemv(desc(mode=1, L=32, group_ids=FAKE, flags=3, group_scale=FAKE, group_mid=FAKE)) == -3
+    assert gemv(desc(mode=1, L=32, group_ids=FAKE, flags=1)) == -1                      # announced but not given
+    assert gemv(desc(mode=1, L=32, group_ids=FAKE, flags=1, group_scale=FAKE)) == -1
+    assert gemv(desc(mode=1, L=32, group_ids=FAKE, group_scale=FAKE, group_mid=FAKE)) == -3   # given but not announced
+    assert gemv(desc(mode=1, L=32, group_ids=FAKE, flags=1, group_scale=FAKE + 1, group_mid=FAKE)) == -4
     assert gemv(desc(struct_size=80)) == -3
     assert gemv(desc(mode=1, L=0, group_ids=FAKE)) == -3
     assert gemv(desc(mode=1, L=300, group_ids=FAKE)) == -3
@@ -123,7 +128,7 @@ def test_noalloc_entry_point_refuses_what_its_static_array_cannot_hold():
     call = lambda d, M, ldx: lib.xfp_gemv_noalloc(ctypes.byref(d), FAKE, M, ldx, FAKE, 0, d.N, None)
     assert call(desc(K=65536, bits=2), 2, 65536) == -6             # M >= 2: the re-laid activations hold K <= 32768
     assert call(desc(K=12288, N=40000), 16, 12288) == -6           # two slices: 2 * 16 * N floats of partial sums > 2^20
-    assert call(desc(K=32768, N=300000), 1, 32768) == -6           # M = 1 split-K: 4 * N floats of partial sums > 2^20
+    assert call(desc(K=32768, N=300000, bits=3), 1, 32768) == -6   # M = 1 split-K (3 bits): 4 * N floats of partial sums > 2^20
     assert "scratch" in xfp.xfp_strerror(-6)
     assert call(desc(K=200), 1, 256) == -2 and call(desc(bits=9), 1, 256) == -3      # the usual validation comes first
     assert call(desc(E=2), 1, 256) == -2
@@ -181,6 +186,9 @@ def test_new_entry_points_reject_bad_arguments():
     assert cvt(cols=100) == -2 and cvt(ld=128) == -2 and cvt(rows=-1) == -2
     assert cvt(src=FAKE + 2) == -4 and cvt(ld=260) == -4
     assert cvt(rows=0) == 0
+    rpw = lambda src=FAKE, rows=4, K=256, bits=5, dst=FAKE: lib.xfp_repack_words(src, rows, K, bits, dst, None)
+    assert rpw(bits=7) == -3 and rpw(bits=1) == -3 and rpw(src=None) == -1 and rpw(K=100) == -2 and rpw(rows=0) == 0
+    assert rpw(src=FAKE + 2, bits=6) == -4 and rpw(src=FAKE + 1, bits=5) == -4
     rpk = lambda src=FAKE, rows=4, K=256, dst=FAKE: lib.xfp_repack_word10(src, rows, K, dst, None)
     assert rpk(src=None) == -1 and rpk(dst=None) == -1
     assert rpk(K=100) == -2 and rpk(K=0) == -2 and rpk(rows=-1) == -2 and rpk(rows=1 << 40) == -2
