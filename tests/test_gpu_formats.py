@@ -143,3 +143,23 @@ def test_affine_groups_expert_indexed():
     ref = oracle.gemv_moe(W, ids, xb, shared_x=False)
     y = host(xfp.xfp_gemv_moe(xfp.upload(W), torch.from_numpy(ids).cuda(), dev_x(xb), y_dtype=torch.float32))
     assert gated_rel_err(y, ref) <= 1e-4
+
+
+# ------------------------------------------------------------------ matrices written by the reference encoder
+@pytest.mark.parametrize("mode,bits,N,K", [(V2, 4, 300, 4096), (V2, 3, 130, 1024), (V2, 2, 64, 2048), (V2, 4, 40, 20480),
+                                           (V2A, 4, 96, 1024), (V2A, 2, 70, 512)])
+def test_decode_of_what_the_reference_encoder_writes(mode, bits, N, K):
+    """Heavy-tailed weights through outlier extraction, Lloyd codebooks (V2) or LibFit with a scale and a mid-point
+    per group (V2a): non-uniform index histograms, residual outliers.  The decoded product must match the oracle
+    AND the exact product with the original weights to the encoder's own cosine."""
+    import xfp_encoder as enc
+    Wf = 0.02 * np.random.default_rng(N + K).standard_t(4.0, size=(N, K))
+    e = (enc.encode_v2 if mode == V2 else enc.encode_v2a)(Wf, bits)
+    x = xi.activations(np.random.default_rng(K), 1, K)
+    dW, xd, ref = xfp.upload(e.weights), dev_x(x), oracle.gemv_weights(e.weights, x)
+    y = host(xfp.xfp_gemv(dW, xd, y_dtype=torch.float32))
+    assert gated_rel_err(y, ref) <= 1e-4
+    assert gated_rel_err(host(xfp.xfp_gemv(dW, xd, y_dtype=torch.float16)), ref) <= 1e-3
+    exact = x.view(np.float16).astype(np.float64) @ Wf.T
+    cos = float((y * exact).sum() / np.sqrt((y * y).sum() * (exact * exact).sum()))
+    assert cos > {2: 0.9, 3: 0.97, 4: 0.99}[bits]
