@@ -331,7 +331,7 @@ int xfp_init(void);
  * take where two can (V2, 4 bits: the streaming kernel, one wave per output row,
  * or the tile kernel, 32 rows across the lanes with a pair table per lane).
  * XFP_KERNEL_AUTO restores the library's own rule (the tile kernel for rows of
- * more than 16384 columns).  Process-wide; results agree to rounding either way.
+ * more than 16384 columns and for calls of 2^26 weights or more).  Process-wide; results agree to rounding either way.
  * XFP_ERR_UNSUPPORTED for any other value.
  */
 typedef enum { XFP_KERNEL_AUTO = 0, XFP_KERNEL_STREAM = 1, XFP_KERNEL_TILE = 2 } xfp_kernel_choice;

@@ -159,10 +159,14 @@ uint32_t rows_per_block(uint32_t N, int slots)
 }
 
 // M = 1 per slot: the tile kernel or the streaming kernel?  Measured on MI355X (4-bit V2, one call per
-// matrix, graph replay over a ring of copies): rows of up to 8192 columns run within 5 % of each other on
-// both (8192 x 4096: 6.2 us streaming, 6.7 tile; 16384 x 4096: 10.0 / 9.5; 28672 x 8192: 30.6 / 29.8), so
-// they stay with the streaming kernel; rows beyond what that kernel holds in registers, which it can only
-// take as split-K slices plus a second launch, are the tile kernel's (8192 x 28672: 32.9 / 25.8 us).
+// matrix, graph replay over a ring of copies, us streaming / tile): 8192 x 4096 6.2 / 6.7; 16384 x 4096
+// 10.0 / 9.2; 8192 x 8192 10.9 / 10.7; 4096 x 16384 14.8 / 14.5; 28672 x 4096 17.4 / 15.7; 32768 x 4096
+// 19.5 / 16.7; 16384 x 8192 20.0 / 17.7; 8192 x 16384 22.2 / 18.2; 28672 x 8192 31.0 / 30.2.  The streaming
+// kernel wins while a call is a few waves per SIMD (nothing to build per tile, no barrier); from 2^26
+// weights per call on the tile kernel's conflict-free lookups win or tie everywhere.  Rows beyond what
+// the streaming kernel holds in registers, which it can only take as split-K slices plus a second launch,
+// are the tile kernel's at any size (8192 x 28672: 32.9 / 25.2 us).
+constexpr uint64_t kTileFromWeights = 1ull << 26;
 std::atomic<int> g_kernel_choice{XFP_KERNEL_AUTO};
 
 bool prefer_tile(const xfp_weights *W, int slots)
@@ -171,7 +175,7 @@ bool prefer_tile(const xfp_weights *W, int slots)
     const int choice = g_kernel_choice.load(std::memory_order_relaxed);
     if (choice == XFP_KERNEL_TILE) return true;
     if (choice == XFP_KERNEL_STREAM) return false;
-    return W->K > 16384;
+    return W->K > 16384 || (uint64_t)W->N * W->K * (uint64_t)slots >= kTileFromWeights;
 }
 
 // One token through the M = 1 kernels (the odd token left over after chunks of 16).

@@ -1,7 +1,7 @@
 """The tile kernel (M = 1 per slot, V2, 4 bits: 32 rows across the lanes, one pair table per lane): parity with
 the oracle, bit-exact depack + gather through one-hot activations, and agreement with the streaming kernel.
-The library picks it by itself for rows of more than 16384 columns; shorter rows are put through it with
-xfp_select_kernel."""
+The library picks it by itself for rows of more than 16384 columns and for calls of 2^26 weights or more; smaller
+calls are put through it with xfp_select_kernel."""
 import numpy as np
 import pytest
 import torch
@@ -124,3 +124,32 @@ def test_tile_kernel_is_bitwise_repeatable(tile_kernel):
     first = xfp.xfp_gemv(dW, xd, y_dtype=torch.float32).clone()
     for _ in range(20):
         assert torch.equal(xfp.xfp_gemv(dW, xd, y_dtype=torch.float32), first)
+
+
+def test_large_matrices_take_the_tile_kernel_by_weight_count():
+    """No selection: from 2^26 weights per call on (here 16384 x 4096, every output against the oracle) the library
+    picks the tile kernel whatever the row length; the streaming kernel's result on the same call agrees to rounding
+    and differs in bits (another summation order), which is how the test knows that two kernels ran."""
+    W = xi.random_weights(V2, 4, 16384, 4096, density=0.003, seed=21)
+    x = xi.activations(np.random.default_rng(22), 1, W.K)
+    dW, xd, ref = xfp.upload(W), dev_x(x), oracle.gemv_weights(W, x)
+    y_auto = host(xfp.xfp_gemv(dW, xd, y_dtype=torch.float32))
+    xfp.xfp_select_kernel(xfp.XFP_KERNEL_TILE)
+    try:
+        y_tile = host(xfp.xfp_gemv(dW, xd, y_dtype=torch.float32))
+        xfp.xfp_select_kernel(xfp.XFP_KERNEL_STREAM)
+        y_stream = host(xfp.xfp_gemv(dW, xd, y_dtype=torch.float32))
+    finally:
+        xfp.xfp_select_kernel(xfp.XFP_KERNEL_AUTO)
+    assert gated_rel_err(y_auto, ref) <= 1e-4 and gated_rel_err(y_stream, ref) <= 1e-4
+    assert np.array_equal(y_auto, y_tile)
+    assert not np.array_equal(y_auto, y_stream)
+
+
+def test_bench_configuration_7_full_size():
+    """8192 x 28672, 4 bits, one token: the shape, inputs and launch bench.py --config 7 times (the tile kernel's
+    sixteen-wave form, one tile per compute unit)."""
+    W = xi.random_weights(V2, 4, 8192, 28672, density=0.003, seed=xi.BASE_SEED + 7)
+    x = xi.activations(np.random.default_rng(xi.BASE_SEED + 407), 1, W.K)
+    y = host(xfp.xfp_gemv(xfp.upload(W), dev_x(x), y_dtype=torch.float32))
+    assert gated_rel_err(y, oracle.gemv_weights(W, x)) <= 1e-4
