@@ -214,17 +214,27 @@ int decode(const xfp_weights *W, const int32_t *eids, int slots, const void *x, 
     a.x_bf16 = x_bf16;
     const bool gen = general_only(W);
     if (!gen && !eids && xfp::batch_supports(bits, mode, W->L, W->N, W->K, slots)) {
-        // batched tokens: the weights are read once per 16 tokens; the chunks run in
-        // stream order, so they share the workspace
+        // batched tokens: the weights are read once per 16 tokens (once per up to 64 where the wide kernel
+        // takes the format); the chunks run in stream order, so they share the workspace
         const size_t ysz = y_dtype == XFP_F32 ? 4 : 2;
         const xfp::Workspace *ws = nullptr;
         hipError_t werr = sc.get(&ws);
         if (werr != hipSuccess) return finish(werr);
-        for (int m0 = 0; m0 < slots; m0 += 16) {
+        for (int m0 = 0; m0 < slots;) {
             xfp::DecodeArgs c = a;
             c.x = a.x + (int64_t)m0 * x_stride;
             c.y = static_cast<char *>(y) + (size_t)m0 * (size_t)ldy * ysz;
+            // more than 16 tokens left: as many as the wide kernel takes in one pass over the weights
+            int wide = slots - m0 < 64 ? slots - m0 : 64;
+            while (wide > 16 && !xfp::wide_supports(bits, mode, W->N, W->K, wide)) wide -= 16;
+            if (wide > 16) {
+                const int rc = finish(xfp::launch_decode_wide(bits, c, wide, y_dtype == XFP_F32, ws->xc, s));
+                if (rc) return rc;
+                m0 += wide;
+                continue;
+            }
             const int mc = slots - m0 < 16 ? slots - m0 : 16;
+            m0 += 16;
             const int rc = mc >= 2 ? finish(xfp::launch_decode_batch(bits, mode, c, mc, y_dtype == XFP_F32, ws->part, ws->xc, s))
                                    : single_token(W, c, y_dtype, sc, s);
             if (rc) return rc;

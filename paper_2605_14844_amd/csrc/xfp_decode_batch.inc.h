@@ -95,22 +95,6 @@ struct BatchLds {
     static constexpr int kTotal = kProd + 2 * kProdOne;               // 140 KB at 4 bits, 92 KB at 3, 80 KB at 2 (W = 8)
 };
 
-// Lane l = 4a + b holds pieces d = 0..3 (v[d]) of chunk b of tile row a.
-// Afterwards lane (i, q) = i + 16 q holds, in v[b], piece q of chunk b of tile
-// row 4 (i % 4) + i / 4.
-__device__ __forceinline__ void to_operand_layout(uint32_t (&v)[4])
-{
-    // lane bit 5 <-> register bit 1, lane bit 4 <-> register bit 0
-    auto s02 = __builtin_amdgcn_permlane32_swap(v[0], v[2], false, false);
-    auto s13 = __builtin_amdgcn_permlane32_swap(v[1], v[3], false, false);
-    auto s01 = __builtin_amdgcn_permlane16_swap(s02[0], s13[0], false, false);
-    auto s23 = __builtin_amdgcn_permlane16_swap(s02[1], s13[1], false, false);
-    v[0] = s01[0]; v[1] = s01[1]; v[2] = s23[0]; v[3] = s23[1];
-    // lane bit 1 <-> register bit 1, lane bit 0 <-> register bit 0
-    lane_reg_exchange<1>(v[0], v[2], v[1], v[3]);
-    lane_reg_exchange<0>(v[0], v[1], v[2], v[3]);
-}
-
 struct BatchArgs {
     DecodeArgs a;
     const uint4 *xt;      // [K][16 tokens] fp16

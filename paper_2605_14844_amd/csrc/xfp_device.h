@@ -170,6 +170,23 @@ __device__ __forceinline__ void lane_reg_exchange(uint32_t &x0, uint32_t &y0, ui
     x0 = o0; y0 = o1; x1 = o2; y1 = o3;
 }
 
+// Index words from the coalesced load layout to the MFMA A-operand layout (matrix-core kernels).
+// Before: lane l = 4a + b holds pieces d = 0..3 (v[d], 8 weights each) of chunk b of tile row a (a tile
+// is 16 rows, a chunk 32 weights).  Afterwards lane (i, q) = i + 16 q holds, in v[b], piece q of chunk b
+// of tile row 4 (i % 4) + i / 4.
+__device__ __forceinline__ void to_operand_layout(uint32_t (&v)[4])
+{
+    // lane bit 5 <-> register bit 1, lane bit 4 <-> register bit 0
+    auto s02 = __builtin_amdgcn_permlane32_swap(v[0], v[2], false, false);
+    auto s13 = __builtin_amdgcn_permlane32_swap(v[1], v[3], false, false);
+    auto s01 = __builtin_amdgcn_permlane16_swap(s02[0], s13[0], false, false);
+    auto s23 = __builtin_amdgcn_permlane16_swap(s02[1], s13[1], false, false);
+    v[0] = s01[0]; v[1] = s01[1]; v[2] = s23[0]; v[3] = s23[1];
+    // lane bit 1 <-> register bit 1, lane bit 0 <-> register bit 0
+    lane_reg_exchange<1>(v[0], v[2], v[1], v[3]);
+    lane_reg_exchange<0>(v[0], v[1], v[2], v[3]);
+}
+
 // fp32 -> bf16 bit pattern, round to nearest even, NaN stays NaN
 __device__ __forceinline__ uint16_t float_to_bf16_bits(float v)
 {

@@ -48,7 +48,8 @@ struct DecodeArgs {
 constexpr uint32_t kPlaneFloats = 1u << 20;        // floats of an fp32 scratch plane (4 MB)
 constexpr int kXtMaxK = 32768;                     // longest row the batched kernel takes
 constexpr int kXtTokens = 16;                      // tokens per launch of the batched kernel
-// Two re-laid copies of the 16 x K activations of a batched launch:
+// Two re-laid copies of the activations of a batched launch (16 tokens x K <= 32768, or up to 64 tokens with
+// 16 ceil(M / 16) K <= 16 * 32768 for the wide kernel, whose copies are [k][16 T tokens] and [T][k / 8][16][8]):
 //   xt [k][16 tokens]           the outlier products read the 16 tokens of one column as 32 bytes;
 //   xb [k / 8][16 tokens][8 k]  the B operand of lane (m, q) for a k block is 16 contiguous bytes and
 //                               the 64 lanes of a wave read 1 KB contiguous (from the row-major x the
@@ -120,6 +121,10 @@ bool batch_supports(int bits, int mode, uint32_t L, uint32_t N, uint32_t K, int 
 bool batch_is_split(uint32_t K);
 hipError_t launch_decode_batch(int bits, int mode, const DecodeArgs &a, int M, bool y_f32, float *part, XCopies *xc,
                                hipStream_t s);
+// Wide matrix-core kernel: up to 64 tokens in ONE pass over the weights (V2, 4 bits; the re-laid copies of
+// 16 ceil(M / 16) x K activations must fit copy_cap halves each).
+bool wide_supports(int bits, int mode, uint32_t N, uint32_t K, int M, uint64_t copy_cap = (uint64_t)kXtMaxK * kXtTokens);
+hipError_t launch_decode_wide(int bits, const DecodeArgs &a, int M, bool y_f32, XCopies *xc, hipStream_t s);
 hipError_t launch_silu_mul(const float *y, uint32_t half, int slots, void *h, int64_t h_stride, bool h_f32,
                            bool h_bf16, hipStream_t s);
 // Down projection with the router's weighted sum over the slots in one launch (V2, T <= 8, T * K <= 16384)

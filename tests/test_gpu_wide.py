@@ -1,0 +1,122 @@
+"""The wide matrix-core kernel (V2, 4 bits, 17 .. 64 tokens in one pass over the weights): parity with the oracle,
+bit-exact depack + gather through one-hot activations, agreement with the single-token calls, the token counts and
+row lengths at which the call falls back to chunks of 16."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2605_14844_amd as xfp
+import xfp_inputs as xi
+from helpers import gated_rel_err
+
+pytestmark = pytest.mark.gpu
+V2 = xi.MODE_V2
+
+
+def dev_x(x_bits):
+    return torch.from_numpy(np.ascontiguousarray(x_bits).view(np.int16)).cuda().view(torch.float16)
+
+
+def host(y):
+    torch.cuda.synchronize()
+    return y.float().cpu().numpy().astype(np.float64)
+
+
+def check(W, x, tol32=1e-4, tol16=1e-3):
+    dW, xd, ref = xfp.upload(W), dev_x(x), oracle.gemv_weights(W, x)
+    y32 = host(xfp.xfp_gemv(dW, xd, y_dtype=torch.float32))
+    y16 = host(xfp.xfp_gemv(dW, xd, y_dtype=torch.float16))
+    e32, e16 = gated_rel_err(y32, ref), gated_rel_err(y16, ref)
+    print(f"  N={W.N} K={W.K} M={x.shape[0]}: err f32 {e32:.2e} f16 {e16:.2e}", flush=True)
+    assert e32 <= tol32 and e16 <= tol16
+    return dW, xd, ref, y32
+
+
+# N: one tile, a ragged last tile, rows that leave the second row block empty, many tiles; K: fewer groups than
+# waves, a group count that is no multiple of 8, the longest row 64 tokens go with (8192), longer rows with fewer
+# tokens; M: every chunk count, full and ragged last chunks; outliers: none, the benchmark's density, dense
+@pytest.mark.parametrize("N,K,M,dens", [(32, 1024, 64, 0.003), (77, 4096, 17, 0.003), (200, 8192, 64, 0.003),
+                                        (10, 384, 33, 0.01), (45, 2176, 48, 0.0), (129, 5120, 32, 0.003),
+                                        (64, 16384, 32, 0.003), (40, 10880, 47, 0.003), (33, 128, 20, 0.05),
+                                        (300, 7296, 49, 0.02), (4500, 256, 64, 0.003)])
+def test_wide_kernel_matches_oracle(N, K, M, dens):
+    W = xi.random_weights(V2, 4, N, K, density=dens, seed=N + K + M)
+    check(W, xi.activations(np.random.default_rng(M + N), M, K))
+
+
+def test_wide_kernel_agrees_with_single_token_calls_and_is_repeatable():
+    W = xi.random_weights(V2, 4, 150, 4096, density=0.003, seed=3)
+    x = xi.activations(np.random.default_rng(4), 40, W.K)
+    dW, xd, ref, y = check(W, x)
+    for m in (0, 15, 16, 39):
+        y1 = host(xfp.xfp_gemv(dW, xd[m:m + 1].contiguous(), y_dtype=torch.float32))
+        assert gated_rel_err(y[m], y1[0]) <= 1e-4
+    first = xfp.xfp_gemv(dW, xd, y_dtype=torch.float32).clone()
+    for _ in range(10):
+        assert torch.equal(xfp.xfp_gemv(dW, xd, y_dtype=torch.float32), first)
+
+
+def test_wide_kernel_one_row_holds_every_outlier():
+    """All entries in one row (more than two 64-entry chunks of a wave's run), none elsewhere."""
+    W = xi.random_weights(V2, 4, 70, 2048, density=0.0, seed=9)
+    cols = np.sort(np.random.default_rng(1).choice(W.K, size=700, replace=False)).astype(np.int32)
+    W.out_row_ptr = np.concatenate([np.zeros(38, np.int32), np.full(70 - 37, 700, np.int32)])
+    W.out_col = cols
+    W.out_val = xi.activations(np.random.default_rng(2), 1, 700).ravel()
+    check(W, xi.activations(np.random.default_rng(3), 24, W.K))
+
+
+@pytest.mark.parametrize("N,K,M", [(48, 1024, 64), (37, 640, 19)])
+def test_wide_kernel_one_hot_sweep(N, K, M):
+    """Token m carries a single 1.0 at column (k0 + m) of a sweep over all columns: y[m][n] must then be EXACTLY the
+    dequantized weight Codebook[n][q[n, k]] (+ the outlier at that position), bit for bit: the kernel's own depack
+    and gather, not the stand-alone hooks', are what is checked."""
+    W = xi.random_weights(V2, 4, N, K, density=0.01, seed=N + K)
+    dW = xfp.upload(W)
+    q = oracle.unpack(W.indices[0], K, 4)
+    cb = W.codebooks[0].view(np.float16).astype(np.float32)                     # [N][16]
+    dense = np.take_along_axis(cb, q.astype(np.int64), axis=1)                  # [N][K]
+    rp, col, val = W.out_row_ptr, W.out_col, W.out_val.view(np.float16).astype(np.float32)
+    for n in range(N):
+        for j in range(rp[n], rp[n + 1]):
+            dense[n, col[j]] = np.float32(dense[n, col[j]]) + np.float32(val[j])   # both exact in fp16, the sum in fp32
+    for k0 in range(0, K, M):
+        Mc = min(M, K - k0)
+        if Mc <= 16:
+            break                                                               # the last chunk would take another kernel
+        x = np.zeros((Mc, K), np.float16)
+        x[np.arange(Mc), k0 + np.arange(Mc)] = 1.0
+        y = xfp.xfp_gemv(dW, dev_x(x.view(np.uint16)), y_dtype=torch.float32)
+        torch.cuda.synchronize()
+        got = y.cpu().numpy()                                                   # [Mc][N]
+        assert np.array_equal(got, dense[:, k0:k0 + Mc].T), (k0, np.argwhere(got != dense[:, k0:k0 + Mc].T)[:4])
+
+
+def test_wide_kernel_bf16_activations_equal_the_converted_call():
+    W = xi.random_weights(V2, 4, 64, 2048, density=0.003, seed=12)
+    x = torch.randn(50, W.K, device="cuda")
+    dW = xfp.upload(W)
+    y_bf = xfp.xfp_gemv(dW, x.bfloat16(), y_dtype=torch.float32)
+    y_h = xfp.xfp_gemv(dW, xfp.xfp_convert_bf16_to_f16(x.bfloat16()), y_dtype=torch.float32)
+    assert torch.equal(y_bf, y_h)
+
+
+def test_strided_tokens_and_outputs():
+    W = xi.random_weights(V2, 4, 100, 1024, density=0.003, seed=5)
+    xb = xi.activations(np.random.default_rng(6), 30, 2 * W.K)                  # token rows of 2 K halves: stride 2 K
+    xd = dev_x(xb)[:, :W.K]
+    ybuf = torch.full((30, 128), 7.0, dtype=torch.float32, device="cuda")
+    dW = xfp.upload(W)
+    xfp.xfp_gemv(dW, xd, y=ybuf[:, :100])
+    got = host(ybuf)
+    ref = oracle.gemv_weights(W, np.ascontiguousarray(xb[:, :W.K]))
+    assert gated_rel_err(got[:, :100], ref) <= 1e-4
+    assert np.all(got[:, 100:] == 7.0)                                          # nothing written past N
+
+
+def test_workload_5_matrix_with_64_tokens_full_size():
+    """28672 x 8192, 4 bits, 64 tokens in one pass: the size the timing in the design notes is quoted on."""
+    W = xi.config_weights(5)
+    x = xi.config_x(5, 64, W.K)
+    check(W, x)
