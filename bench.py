@@ -41,7 +41,7 @@ def parse_args():
                    help="workload 1..5 (default 2, the headline); beyond the five: 6 = workload 4 as a whole expert "
                         "layer with both epilogues fused, 7 = a long-row matrix (8192x28672, 4-bit, M=1) through the tile kernel, "
                         "8 = the same matrix with 16 tokens, 9 = workload 5's shape at 3 bits, 10 = the same as V2a, "
-                        "11 = workload 2's shape at 2 bits")
+                        "11 = workload 2's shape at 2 bits, 12 = workload 5's matrix with 64 tokens (wide matrix-core kernel)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--single", action="store_true", help="time only --config (the default run of workload 2 also "
                    "times workloads 1, 3, 4, 5 and a 2-bit matrix and reports them under \"configs\")")
@@ -233,6 +233,28 @@ def build_workload(cfg: int, ring_bytes: int):
         return dict(name=name, step=step, bytes=nbytes, ring=R, oracle=oracle_once, launches=3 if cfg == 8 else 2,
                     kernel_bytes=nbytes, launch_bytes=[nbytes], keep=(ring, xd, y), M=16, N=W.N, K=W.K, bits=W.bits,
                     mode=W.mode)
+    if cfg == 12:
+        # workload 5's matrix with 64 tokens: one pass of the wide matrix-core kernel
+        W = xi.config_weights(5)
+        xb = xi.config_x(5, 64, W.K)
+        nbytes = W.algorithmic_bytes(M=64)
+        R = max(1, min(512, -(-ring_bytes // nbytes)))
+        ring = [xfp.upload(W)]
+        for _ in range(R - 1):
+            ring.append(clone_weights(ring[0]))
+        xd = dev_x(xb)
+        y = torch.empty((64, W.N), dtype=torch.float16, device="cuda")
+
+        def step(i):
+            xfp.xfp_gemv(ring[i % R], xd, y=y)
+
+        def oracle_once(threads=None):
+            import oracle
+            return oracle.gemv_weights(W, xb, threads)
+
+        return dict(name="V2 28672x8192 b4 M=64 (workload 5's matrix, 64 tokens in one pass: wide matrix-core kernel, two launches)",
+                    step=step, bytes=nbytes, ring=R, oracle=oracle_once, launches=2, kernel_bytes=nbytes,
+                    launch_bytes=[nbytes], keep=(ring, xd, y), M=64, N=W.N, K=W.K, bits=W.bits, mode=W.mode)
     raise SystemExit(f"no workload {cfg}")
 
 
