@@ -1,5 +1,5 @@
 // Wide form of the batched decode on the matrix cores: up to 64 tokens per pass
-// over the weights (V2 codebooks, 4-bit indices).
+// over the weights (V2 codebooks, 2-, 3- or 4-bit indices).
 //
 // Why: the 16-token kernel keeps its tokens' activations in registers as B
 // operands (128 of a wave's 256 registers), so more than 16 tokens mean another
@@ -50,6 +50,8 @@ namespace {
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x3_t __attribute__((ext_vector_type(3)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(3))) uint32_t lds_u32_t;
 typedef __attribute__((address_space(3))) const uint32_t lds_cu32_t;
 typedef __attribute__((address_space(3))) float lds_f32_t;
@@ -60,12 +62,12 @@ constexpr int kWideWaves = 8;
 constexpr int kWideThreads = kWideWaves * kWave;
 constexpr int kTokStride = 33;             // floats between two tokens of a plane (32 rows + 1: spreads the banks)
 
-template <int T>
+template <int BITS, int T>
 struct WideLds {
-    static constexpr int kTab = 256 * 256;                             // pair tables: [256 entries][64 slots] dwords
+    static constexpr int kTab = (1 << (2 * BITS)) * 256;               // pair tables: [4^BITS entries][64 slots] dwords
     static constexpr int kPlane = 16 * T * kTokStride * 4;             // [16 T tokens][33] floats
     static constexpr int kOut = kWideWaves * kPlane > kTab ? kWideWaves * kPlane : kTab;   // the outlier plane: behind both
-    static constexpr int kTotal = kOut + kPlane;                       // 76 032 bytes at T = 4, 67 648 at T = 1
+    static constexpr int kTotal = kOut + kPlane;                       // 76 032 bytes at T = 4; 4 bits, T = 1: 67 648
 };
 
 struct WideArgs {
@@ -76,11 +78,14 @@ struct WideArgs {
     int y_f32;
 };
 
-template <int T>
+template <int BITS, int T>
 __global__ __launch_bounds__(kWideThreads) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void decode_wide_kernel(WideArgs ta)
 {
-    using L = WideLds<T>;
+    static_assert(BITS >= 2 && BITS <= 4, "pair tables of 16, 64 or 256 entries");
+    using L = WideLds<BITS, T>;
+    constexpr int CW = BITS;                               // dwords of a lane's chunk of 32 weights
+    constexpr uint32_t ENT = 1u << (2 * BITS);             // entries of a pair table
     constexpr int NSLOT = T <= 2 ? 4 : 2;                  // steps of B operands in flight
     constexpr int D = T == 4 ? 2 : T == 3 ? 4 : T == 2 ? 5 : 6;         // groups of index words in flight (what the registers allow)
     constexpr uint32_t MP = 16 * T;                        // tokens of the re-laid copies
@@ -94,19 +99,32 @@ void decode_wide_kernel(WideArgs ta)
     const uint32_t i = lane & 15, q = lane >> 4;           // operand layout: A row / token, k block
     const uint32_t la = lane >> 2, lb = lane & 3;          // load layout: row of a row block, chunk of a group
     const uint32_t N = a.N, K = a.K;
-    const uint32_t G = K / kGroup, wpr = K / 8;            // groups, dwords of a row
+    const uint32_t G = K / kGroup, wpr = K / 32 * CW;      // groups, dwords of a row
     const uint32_t n0 = blockIdx.x * kWideRows;
     const uint32_t rows_here = min((uint32_t)kWideRows, N - n0);
     const_i32_t *rp = (const_i32_t *)(uintptr_t)a.rp;
 
     // ---------------------------------------------------------------- loads, oldest consumer first
-    // table builder role: slot tid % 64 (row block, copy, operand row), part tid / 64 builds the 32 entries
-    // whose second index is 2 part or 2 part + 1
+    // table builder role: slot tid % 64 (row block, copy, operand row), part tid / 64 (0..7) builds ENT / 8 entries:
+    //   4 bits: the 32 entries whose second index is 2 part or 2 part + 1 (16 + 2 codebook values);
+    //   3 bits: the 8 entries whose second index is part (8 + 1 values);
+    //   2 bits: the 2 entries (first index 2 (part & 1) + {0, 1}, second index part / 2).
     const uint32_t slot = tid & 63, part = tid >> 6;
     const uint32_t trow = (slot >> 5) * 16 + 4 * (slot & 3) + ((slot & 15) >> 2);
-    const uint16_t *cbr = a.cb + (size_t)min(n0 + trow, N - 1) * 16;
-    const uint4 c0 = *reinterpret_cast<const uint4 *>(cbr), c1 = *reinterpret_cast<const uint4 *>(cbr + 8);
-    const uint32_t chi = reinterpret_cast<const uint32_t *>(cbr)[part];
+    const uint16_t *cbr = a.cb + (size_t)min(n0 + trow, N - 1) * (1u << BITS);
+    uint4 c0 = make_uint4(0u, 0u, 0u, 0u), c1 = c0;
+    uint32_t chi;
+    if constexpr (BITS == 4) {
+        c0 = *reinterpret_cast<const uint4 *>(cbr);
+        c1 = *reinterpret_cast<const uint4 *>(cbr + 8);
+        chi = reinterpret_cast<const uint32_t *>(cbr)[part];
+    } else if constexpr (BITS == 3) {
+        c0 = *reinterpret_cast<const uint4 *>(cbr);
+        chi = cbr[part];
+    } else {
+        c0.x = reinterpret_cast<const uint32_t *>(cbr)[part & 1];
+        chi = cbr[part >> 1];
+    }
     // the wave's outlier run: tile rows 4 wave .. 4 wave + 3
     int32_t oe[5];
 #pragma unroll
@@ -114,15 +132,29 @@ void decode_wide_kernel(WideArgs ta)
 
     __amdgpu_buffer_rsrc_t ri = __builtin_amdgcn_make_buffer_rsrc((void *)(a.idx + (size_t)n0 * wpr), 0, rows_here * wpr * 4, 0x00020000);
     __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void *)ta.xb, 0, T * K * 32, 0x00020000);
-    const uint32_t ioff0 = la * (wpr * 4) + lb * 16, ioff1 = ioff0 + 16 * (wpr * 4);
-    // Index words: a ring of D groups per wave, i.e. D x 2 KB in flight: a CU needs about 64 KB on the way to
-    // keep HBM busy, and a group is consumed faster the fewer tokens there are.
-    uint32_t iw[D][2][4];
-    auto load_group = [&](uint32_t (&w)[2][4], uint32_t g) {   // rows past the end of the matrix read zeros
-        const u32x4_t v0 = __builtin_amdgcn_raw_buffer_load_b128(ri, ioff0, g * 64, 2);   // read once: non-temporal
-        const u32x4_t v1 = __builtin_amdgcn_raw_buffer_load_b128(ri, ioff1, g * 64, 2);
-        w[0][0] = v0.x; w[0][1] = v0.y; w[0][2] = v0.z; w[0][3] = v0.w;
-        w[1][0] = v1.x; w[1][1] = v1.y; w[1][2] = v1.z; w[1][3] = v1.w;
+    const uint32_t ioff0 = la * (wpr * 4) + lb * (4 * CW), ioff1 = ioff0 + 16 * (wpr * 4);
+    // Index words: a ring of D groups per wave, i.e. D x 2 KB (4 bits) in flight: a CU needs about 64 KB on the
+    // way to keep HBM busy, and a group is consumed faster the fewer tokens there are.  A lane's chunk of 32
+    // weights is 16, 12 or 8 bytes; the quad reads 64, 48 or 32 contiguous bytes.
+    uint32_t iw[D][2][CW];
+    auto load_group = [&](uint32_t (&w)[2][CW], uint32_t g) {  // rows past the end of the matrix read zeros
+        const uint32_t so = g * (16 * CW);                 // read once: non-temporal
+        if constexpr (BITS == 4) {
+            const u32x4_t v0 = __builtin_amdgcn_raw_buffer_load_b128(ri, ioff0, so, 2);
+            const u32x4_t v1 = __builtin_amdgcn_raw_buffer_load_b128(ri, ioff1, so, 2);
+            w[0][0] = v0.x; w[0][1] = v0.y; w[0][2] = v0.z; w[0][3] = v0.w;
+            w[1][0] = v1.x; w[1][1] = v1.y; w[1][2] = v1.z; w[1][3] = v1.w;
+        } else if constexpr (BITS == 3) {
+            const u32x3_t v0 = __builtin_amdgcn_raw_buffer_load_b96(ri, ioff0, so, 2);
+            const u32x3_t v1 = __builtin_amdgcn_raw_buffer_load_b96(ri, ioff1, so, 2);
+            w[0][0] = v0.x; w[0][1] = v0.y; w[0][2] = v0.z;
+            w[1][0] = v1.x; w[1][1] = v1.y; w[1][2] = v1.z;
+        } else {
+            const u32x2_t v0 = __builtin_amdgcn_raw_buffer_load_b64(ri, ioff0, so, 2);
+            const u32x2_t v1 = __builtin_amdgcn_raw_buffer_load_b64(ri, ioff1, so, 2);
+            w[0][0] = v0.x; w[0][1] = v0.y;
+            w[1][0] = v1.x; w[1][1] = v1.y;
+        }
     };
     // B operands of step b of group g, all chunks: lane (token i, k block q) reads 16 bytes, the wave 1 KB
     uint32_t xr[NSLOT][T][4];
@@ -162,13 +194,14 @@ void decode_wide_kernel(WideArgs ta)
     // ---------------------------------------------------------------- a2: the tile's pair tables
     {
         const uint32_t clo[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
-        const uint32_t base = lds0 + part * (32 * 256) + slot * 4;
+        constexpr int EPT = (int)ENT / 8;                  // entries per thread: 32, 8, 2
+        const uint32_t base = lds0 + part * (EPT * 256) + slot * 4;
 #pragma unroll
-        for (int j = 0; j < 32; ++j) {
-            const int lo = j % 16;
+        for (int j = 0; j < EPT; ++j) {                    // entry part * EPT + j = first index + 2^BITS * second index
+            const int lo = BITS == 2 ? j : j % (1 << BITS);                // within this thread's codebook words
             const uint32_t lw = clo[lo / 2];
             const uint32_t lov = (lo & 1) ? lw >> 16 : lw & 0xFFFFu;
-            const uint32_t hiv = j < 16 ? chi << 16 : chi & 0xFFFF0000u;
+            const uint32_t hiv = (BITS == 4 && j >= 16) ? chi & 0xFFFF0000u : chi << 16;
             *(lds_u32_t *)(uintptr_t)(base + j * 256) = lov | hiv;
         }
     }
@@ -266,26 +299,53 @@ void decode_wide_kernel(WideArgs ta)
     // lookup address has been formed from it
     auto group_body = [&](auto dtag, uint32_t g) {
         constexpr int d = decltype(dtag)::value;
-        uint32_t (&pw)[2][4] = iw[d];
-        to_operand_layout(pw[0]);
-        to_operand_layout(pw[1]);
+        // four pieces of 8 weights per row block (a dword at 4 bits, 24 bits at 3, 16 at 2; bits above a piece
+        // are ignored), then the transposition to the operand layout.  At 4 bits the pieces ARE the index words:
+        // they are transposed in place and the slot is refilled once its last lookup address is formed; at 3 and
+        // 2 bits the pieces are registers of their own and the slot is refilled at once.
+        uint32_t pw_own[BITS == 4 ? 1 : 2][4];
+        uint32_t (&pw)[2][4] = *[&]() -> uint32_t (*)[2][4] {
+            if constexpr (BITS == 4) return &iw[d];
+            else return &pw_own;
+        }();
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+            if constexpr (BITS == 3) {
+                const uint32_t (&w)[CW] = iw[d][rb];
+                pw[rb][0] = w[0];
+                pw[rb][1] = __builtin_amdgcn_alignbit(w[1], w[0], 24);
+                pw[rb][2] = __builtin_amdgcn_alignbit(w[2], w[1], 16);
+                pw[rb][3] = w[2] >> 8;
+            } else if constexpr (BITS == 2) {
+                const uint32_t (&w)[CW] = iw[d][rb];
+                pw[rb][0] = w[0]; pw[rb][1] = w[0] >> 16; pw[rb][2] = w[1]; pw[rb][3] = w[1] >> 16;
+            }
+            to_operand_layout(pw[rb]);
+        }
+        constexpr int REFILL_STEP = BITS == 4 ? 2 : 0;
         const bool more = g + kWideWaves < G;
         uint32_t av[2][2][4];
         auto lookup = [&](int b, uint32_t (&v)[2][4]) {
 #pragma unroll
             for (int rb = 0; rb < 2; ++rb) {
                 const uint32_t w = pw[rb][b];
-                v[rb][0] = *(lds_cu32_t *)(uintptr_t)(__builtin_amdgcn_perm(w, sel, 0x0c0c0400u) + rb * 128);
-                v[rb][1] = *(lds_cu32_t *)(uintptr_t)(__builtin_amdgcn_perm(w, sel, 0x0c0c0500u) + rb * 128);
-                v[rb][2] = *(lds_cu32_t *)(uintptr_t)(__builtin_amdgcn_perm(w, sel, 0x0c0c0600u) + rb * 128);
-                v[rb][3] = *(lds_cu32_t *)(uintptr_t)(__builtin_amdgcn_perm(w, sel, 0x0c0c0700u) + rb * 128);
+                if constexpr (BITS == 4) {
+                    v[rb][0] = *(lds_cu32_t *)(uintptr_t)(__builtin_amdgcn_perm(w, sel, 0x0c0c0400u) + rb * 128);
+                    v[rb][1] = *(lds_cu32_t *)(uintptr_t)(__builtin_amdgcn_perm(w, sel, 0x0c0c0500u) + rb * 128);
+                    v[rb][2] = *(lds_cu32_t *)(uintptr_t)(__builtin_amdgcn_perm(w, sel, 0x0c0c0600u) + rb * 128);
+                    v[rb][3] = *(lds_cu32_t *)(uintptr_t)(__builtin_amdgcn_perm(w, sel, 0x0c0c0700u) + rb * 128);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        v[rb][j] = *(lds_cu32_t *)(uintptr_t)(((((w >> (2 * BITS * j)) & (ENT - 1u)) << 8) | sel) + rb * 128);
+                }
             }
         };
         lookup(0, av[0]);
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
             if (b < 3) lookup(b + 1, av[(b + 1) & 1]);
-            if (b == 2 && g + D * kWideWaves < G) load_group(pw, g + D * kWideWaves);
+            if (b == REFILL_STEP && g + D * kWideWaves < G) load_group(iw[d], g + D * kWideWaves);
             __builtin_amdgcn_sched_barrier(0);
             const uint32_t (&cur)[2][4] = av[b & 1];
 #pragma unroll
@@ -380,11 +440,11 @@ __global__ __launch_bounds__(256) void relayout_x_wide_kernel(const uint16_t *x,
     }
 }
 
-template <int T>
+template <int BITS, int T>
 hipError_t launch_wide_t(const WideArgs &ta, hipStream_t s)
 {
-    constexpr int kLds = WideLds<T>::kTotal;
-    auto kern = decode_wide_kernel<T>;
+    constexpr int kLds = WideLds<BITS, T>::kTotal;
+    auto kern = decode_wide_kernel<BITS, T>;
     static std::atomic<int> configured[kMaxDevices];       // per device; idempotent attribute, benign race
     const int dev = current_device();
     if (dev < 0) return hipErrorInvalidDevice;
@@ -397,12 +457,23 @@ hipError_t launch_wide_t(const WideArgs &ta, hipStream_t s)
     return hipGetLastError();
 }
 
+template <int BITS>
+hipError_t launch_wide_b(const WideArgs &ta, int T, hipStream_t s)
+{
+    switch (T) {
+    case 1: return launch_wide_t<BITS, 1>(ta, s);
+    case 2: return launch_wide_t<BITS, 2>(ta, s);
+    case 3: return launch_wide_t<BITS, 3>(ta, s);
+    default: return launch_wide_t<BITS, 4>(ta, s);
+    }
+}
+
 }  // namespace
 
-// V2, 4 bits, up to 64 tokens whose re-laid copies fit the workspace (16 ceil(M / 16) K halves each).
+// V2, 2 to 4 bits, up to 64 tokens whose re-laid copies fit the workspace (16 ceil(M / 16) K halves each).
 bool wide_supports(int bits, int mode, uint32_t N, uint32_t K, int M, uint64_t copy_cap)
 {
-    if (!(mode == 0 && bits == 4 && M >= 1 && M <= 64 && K % kGroup == 0 && K >= kGroup && N >= 1)) return false;
+    if (!(mode == 0 && bits >= 2 && bits <= 4 && M >= 1 && M <= 64 && K % kGroup == 0 && K >= kGroup && N >= 1)) return false;
     return (uint64_t)K * 16u * (uint64_t)((M + 15) / 16) <= copy_cap && (uint64_t)K * 32u * 4u <= 0xFFFFFFFFull;
 }
 
@@ -410,7 +481,7 @@ bool wide_supports(int bits, int mode, uint32_t N, uint32_t K, int M, uint64_t c
 // small kernel in front of the decode kernel (launches on one stream may share them).
 hipError_t launch_decode_wide(int bits, const DecodeArgs &a, int M, bool y_f32, XCopies *xc, hipStream_t s)
 {
-    if (!xc || bits != 4 || M < 1 || M > 64) return hipErrorInvalidValue;
+    if (!xc || bits < 2 || bits > 4 || M < 1 || M > 64) return hipErrorInvalidValue;
     const int T = (M + 15) / 16;
     const uint32_t nb = (a.K * 2 * (uint32_t)T + 255) / 256 + (a.K / 8 * 16 * (uint32_t)T + 255) / 256;
     hipLaunchKernelGGL(relayout_x_wide_kernel, dim3(nb), dim3(256), 0, s, a.x, a.x_stride, M, a.K, T, (int)a.x_bf16, xc->xt, xc->xb);
@@ -422,12 +493,7 @@ hipError_t launch_decode_wide(int bits, const DecodeArgs &a, int M, bool y_f32, 
     ta.xb = xc->xb;
     ta.M = M;
     ta.y_f32 = (int)y_f32;
-    switch (T) {
-    case 1: return launch_wide_t<1>(ta, s);
-    case 2: return launch_wide_t<2>(ta, s);
-    case 3: return launch_wide_t<3>(ta, s);
-    default: return launch_wide_t<4>(ta, s);
-    }
+    return bits == 4 ? launch_wide_b<4>(ta, T, s) : bits == 3 ? launch_wide_b<3>(ta, T, s) : launch_wide_b<2>(ta, T, s);
 }
 
 }  // namespace xfp

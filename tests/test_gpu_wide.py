@@ -1,4 +1,4 @@
-"""The wide matrix-core kernel (V2, 4 bits, 17 .. 64 tokens in one pass over the weights): parity with the oracle,
+"""The wide matrix-core kernel (V2, 2 to 4 bits, 17 .. 64 tokens in one pass over the weights): parity with the oracle,
 bit-exact depack + gather through one-hot activations, agreement with the single-token calls, the token counts and
 row lengths at which the call falls back to chunks of 16."""
 import numpy as np
@@ -40,8 +40,9 @@ def check(W, x, tol32=1e-4, tol16=1e-3):
                                         (10, 384, 33, 0.01), (45, 2176, 48, 0.0), (129, 5120, 32, 0.003),
                                         (64, 16384, 32, 0.003), (40, 10880, 47, 0.003), (33, 128, 20, 0.05),
                                         (300, 7296, 49, 0.02), (4500, 256, 64, 0.003)])
-def test_wide_kernel_matches_oracle(N, K, M, dens):
-    W = xi.random_weights(V2, 4, N, K, density=dens, seed=N + K + M)
+@pytest.mark.parametrize("bits", [4, 3, 2])
+def test_wide_kernel_matches_oracle(bits, N, K, M, dens):
+    W = xi.random_weights(V2, bits, N, K, density=dens, seed=N + K + M)
     check(W, xi.activations(np.random.default_rng(M + N), M, K))
 
 
@@ -67,15 +68,15 @@ def test_wide_kernel_one_row_holds_every_outlier():
     check(W, xi.activations(np.random.default_rng(3), 24, W.K))
 
 
-@pytest.mark.parametrize("N,K,M", [(48, 1024, 64), (37, 640, 19)])
-def test_wide_kernel_one_hot_sweep(N, K, M):
+@pytest.mark.parametrize("bits,N,K,M", [(4, 48, 1024, 64), (4, 37, 640, 19), (3, 48, 1024, 64), (3, 37, 640, 35), (2, 40, 768, 64)])
+def test_wide_kernel_one_hot_sweep(bits, N, K, M):
     """Token m carries a single 1.0 at column (k0 + m) of a sweep over all columns: y[m][n] must then be EXACTLY the
     dequantized weight Codebook[n][q[n, k]] (+ the outlier at that position), bit for bit: the kernel's own depack
     and gather, not the stand-alone hooks', are what is checked."""
-    W = xi.random_weights(V2, 4, N, K, density=0.01, seed=N + K)
+    W = xi.random_weights(V2, bits, N, K, density=0.01, seed=N + K)
     dW = xfp.upload(W)
-    q = oracle.unpack(W.indices[0], K, 4)
-    cb = W.codebooks[0].view(np.float16).astype(np.float32)                     # [N][16]
+    q = oracle.unpack(W.indices[0], K, bits)
+    cb = W.codebooks[0].view(np.float16).astype(np.float32)                     # [N][2^bits]
     dense = np.take_along_axis(cb, q.astype(np.int64), axis=1)                  # [N][K]
     rp, col, val = W.out_row_ptr, W.out_col, W.out_val.view(np.float16).astype(np.float32)
     for n in range(N):
@@ -113,6 +114,12 @@ def test_strided_tokens_and_outputs():
     ref = oracle.gemv_weights(W, np.ascontiguousarray(xb[:, :W.K]))
     assert gated_rel_err(got[:, :100], ref) <= 1e-4
     assert np.all(got[:, 100:] == 7.0)                                          # nothing written past N
+
+
+def test_workload_5_shape_at_3_bits_with_48_tokens_full_size():
+    """28672 x 8192, 3 bits (the matrix of bench.py --config 9), 48 tokens in one pass."""
+    W = xi.random_weights(V2, 3, 28672, 8192, density=0.003, seed=xi.BASE_SEED + 9)
+    check(W, xi.activations(np.random.default_rng(xi.BASE_SEED + 448), 48, W.K))
 
 
 def test_workload_5_matrix_with_64_tokens_full_size():
