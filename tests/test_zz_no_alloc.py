@@ -44,6 +44,9 @@ def one_call(mode, bits, N, K, M, seed, dtype):
     # V2a batched, several chunks of 16 and an odd token; then M = 1 with no scratch at all
     ((V2A, 3, 70, 10240, 35), (V2A, 3, 33, 4096, 1)),
     ((V2, 2, 128, 32768, 4), (V2, 2, 16, 128, 2)),
+    # more than 16 tokens in one pass over the weights (wider re-laid copies in the same array), then 16 tokens
+    ((V2, 4, 100, 8192, 64), (V2, 4, 50, 4096, 16)),
+    ((V2, 3, 77, 16384, 40), (V2, 3, 33, 1024, 20)),
 ])
 def test_two_calls_in_a_row_match_xfp_gemv(first, second):
     for dtype in (torch.float32, torch.float16):
