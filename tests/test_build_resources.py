@@ -50,3 +50,17 @@ def test_the_workloads_kernels_keep_their_registers(parts, min_waves):
     k = find(resources(), *parts)
     assert k["vgpr_spills"] == 0 and k["scratch_bytes_per_lane"] == 0, k
     assert k["waves_per_simd"] >= min_waves, k
+
+
+def test_kernels_that_address_lds_from_zero_have_no_static_lds():
+    """The matrix-core kernels, the tile kernel and the V2a streaming kernels form lookup addresses that assume
+    their tables at LDS offset 0 (one v_perm_b32 writes the whole address).  That holds because they declare
+    dynamic LDS only; a static __shared__ array added to one of them would move the tables and the kernel would
+    return without writing (its guard).  This pins the guarantee at build time."""
+    res = resources()
+    names = [k for k in res if any(p in k for p in ("decode_batch_kernel", "decode_tile_kernel", "decode_wide_kernel"))]
+    # the streaming kernel's V2a instantiations: template argument 5 (MODE) is 1
+    names += [k for k in res if "decode_stream_kernelILi" in k and k.split("decode_stream_kernelI")[1].split("E")[4] == "Li1"]
+    assert len(names) >= 100
+    for k in names:
+        assert res[k]["lds_bytes"] == 0, (k, res[k])
