@@ -103,6 +103,16 @@ def test_wide_kernel_bf16_activations_equal_the_converted_call():
     assert torch.equal(y_bf, y_h)
 
 
+def test_wide_kernel_bf16_output_is_one_rounding_of_the_fp32_result():
+    W = xi.random_weights(V2, 4, 90, 2048, density=0.003, seed=15)
+    dW = xfp.upload(W)
+    xd = dev_x(xi.activations(np.random.default_rng(16), 37, W.K))
+    y32 = xfp.xfp_gemv(dW, xd, y_dtype=torch.float32)
+    ybf = xfp.xfp_gemv(dW, xd, y_dtype=torch.bfloat16)
+    y16 = xfp.xfp_gemv(dW, xd, y_dtype=torch.float16)
+    assert torch.equal(ybf, y32.bfloat16()) and torch.equal(y16, y32.half())
+
+
 def test_strided_tokens_and_outputs():
     W = xi.random_weights(V2, 4, 100, 1024, density=0.003, seed=5)
     xb = xi.activations(np.random.default_rng(6), 30, 2 * W.K)                  # token rows of 2 K halves: stride 2 K
