@@ -147,10 +147,11 @@ typedef struct xfp_weights {
  *        of 16 as 16 * ceil(m / 16) * K <= 2^19 allows: 64 tokens up to
  *        K = 8192, 32 up to 16384); any other shape runs the
  *        M = 1 path once per token.  Same results either way, to rounding.
- * XFP_ERR_UNSUPPORTED for a row no kernel takes: longer than 16384 columns with
- * no split into equal slices of at most 8192 (or partial sums beyond the
- * scratch plane) AND too long for the general kernel to stage on chip
- * (2 K bytes plus its tables within 160 KB).
+ * XFP_ERR_UNSUPPORTED for a row no kernel takes: longer than 16384 columns, not
+ * 4-bit V2 (whose rows of any length the tile kernel takes), with no split into
+ * equal slices of at most 8192 (or partial sums beyond the scratch plane) AND
+ * too long for the general kernel to stage on chip (2 K bytes plus its tables
+ * within 160 KB).  xfp_route tells on the host which kernel a call takes.
  */
 int xfp_gemv(const xfp_weights *W, const void *x, int M, int64_t ldx,
              void *y, int y_dtype, int64_t ldy, void *hip_stream);
@@ -339,6 +340,25 @@ int xfp_init(void);
  */
 typedef enum { XFP_KERNEL_AUTO = 0, XFP_KERNEL_STREAM = 1, XFP_KERNEL_TILE = 2 } xfp_kernel_choice;
 int xfp_select_kernel(int which);
+
+/*
+ * The dispatch rule, queryable on the host (no paper counterpart; touches no device): which kernel family the
+ * FIRST launch of xfp_gemv(W, x, M, ...) (expert_indexed == 0) or of xfp_gemv_moe(bank, ids, T = M, ...)
+ * (expert_indexed != 0) would be, and in *tokens (may be NULL) how many of the M tokens / slots that launch
+ * covers; a call with tokens left over continues with the rule applied to the rest.  The descriptor is validated
+ * as by the decode calls (its pointers are not dereferenced).  Returns an xfp_route_id, or a negative xfp_status
+ * (XFP_ERR_UNSUPPORTED for a row no kernel takes).  xfp_select_kernel changes what it reports, as it changes
+ * what runs.
+ */
+typedef enum {
+    XFP_ROUTE_GENERAL = 0,   /* one wave per row, x and tables in LDS: widths 5 and 6, scale + mid-point, odd shapes */
+    XFP_ROUTE_STREAM = 1,    /* M = 1 per slot, a wave per row (run of rows), x in registers                        */
+    XFP_ROUTE_SPLIT_K = 2,   /* the streaming kernel over slices of K plus the fixed-order sum                      */
+    XFP_ROUTE_TILE = 3,      /* M = 1 per slot, 32 rows across the lanes                                             */
+    XFP_ROUTE_BATCH = 4,     /* 2 .. 16 tokens on the matrix cores, activations in registers                         */
+    XFP_ROUTE_WIDE = 5       /* 17 .. 64 tokens on the matrix cores in one pass over the weights                     */
+} xfp_route_id;
+int xfp_route(const xfp_weights *W, int M, int expert_indexed, int *tokens);
 
 /*
  * Test hook for the ring's slot arithmetic (host only, touches no device): the

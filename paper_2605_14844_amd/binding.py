@@ -72,10 +72,11 @@ def load_library():
     lib.xfp_probe_read.argtypes = [vp, u64, vp, vp]
     lib.xfp_probe_copy.argtypes = [vp, vp, u64, vp]
     lib.xfp_select_kernel.argtypes = [i32]
+    lib.xfp_route.argtypes = [wp, i32, i32, ctypes.POINTER(ctypes.c_int)]
     lib.xfp_strerror.argtypes = [i32]
     lib.xfp_strerror.restype = ctypes.c_char_p
     for name in ("xfp_gemv", "xfp_gemv_noalloc", "xfp_gemv_moe", "xfp_gemv_moe_silu_mul", "xfp_gemv_moe_combine", "xfp_check_contents", "xfp_convert_bf16_to_f16", "xfp_repack_word10", "xfp_repack_words", "xfp_unpack_indices", "xfp_dequant_bulk",
-                 "xfp_probe_read", "xfp_probe_copy", "xfp_version", "xfp_init", "xfp_select_kernel"):
+                 "xfp_probe_read", "xfp_probe_copy", "xfp_version", "xfp_init", "xfp_select_kernel", "xfp_route"):
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -95,6 +96,20 @@ XFP_KERNEL_AUTO, XFP_KERNEL_STREAM, XFP_KERNEL_TILE = 0, 1, 2
 def xfp_select_kernel(which: int) -> None:
     """Which kernel M = 1 calls take where two can (measurement and test aid); XFP_KERNEL_AUTO restores the rule."""
     _check(load_library().xfp_select_kernel(int(which)))
+
+
+XFP_ROUTE_GENERAL, XFP_ROUTE_STREAM, XFP_ROUTE_SPLIT_K, XFP_ROUTE_TILE, XFP_ROUTE_BATCH, XFP_ROUTE_WIDE = range(6)
+
+
+def xfp_route(W, M: int, expert_indexed: bool = False):
+    """(route id, tokens) of the first launch xfp_gemv / xfp_gemv_moe would make for M tokens / slots (host only).
+    W: a DeviceWeights or an xfp_weights descriptor."""
+    desc = W.desc if hasattr(W, "desc") else W
+    n = ctypes.c_int(0)
+    r = load_library().xfp_route(ctypes.byref(desc), int(M), int(bool(expert_indexed)), ctypes.byref(n))
+    if r < 0:
+        _check(r)
+    return r, n.value
 
 
 def xfp_init() -> None:

@@ -131,12 +131,14 @@ bool rows_fits(const xfp_weights *W)
 
 // Shapes no kernel takes (checked before anything is launched): rows beyond the
 // streaming and split-K kernels that the general kernel cannot stage either.
+bool prefer_tile(const xfp_weights *W, int slots);
+
 bool decodable(const xfp_weights *W, int slots)
 {
     const int bits = (int)W->bits, mode = (int)W->mode;
     if (general_only(W)) return rows_fits(W);
-    return xfp::stream_supports(bits, mode, W->K, W->L) || xfp::splitk_slices(bits, mode, W->N, W->K, W->L, slots) ||
-           rows_fits(W);
+    return prefer_tile(W, slots) || xfp::stream_supports(bits, mode, W->K, W->L) ||
+           xfp::splitk_slices(bits, mode, W->N, W->K, W->L, slots) || rows_fits(W);
 }
 
 int check_io(const xfp_weights *W, const void *x, const void *y, int y_dtype, int64_t ldy)
@@ -178,23 +180,33 @@ bool prefer_tile(const xfp_weights *W, int slots)
     return W->K > 16384 || (uint64_t)W->N * W->K * (uint64_t)slots >= kTileFromWeights;
 }
 
-// One token through the M = 1 kernels (the odd token left over after chunks of 16).
-int single_token(const xfp_weights *W, xfp::DecodeArgs c, int y_dtype, Scratch &sc, hipStream_t s)
+// What the next launch of a plain decode call is: the kernel family and how many of the remaining slots it
+// takes.  The one place the dispatch rule lives: decode() executes it, xfp_route() reports it.
+struct Plan {
+    int route;      // an xfp_route_id, or a negative status
+    int take;       // slots (tokens) the launch covers
+    int slices;     // split-K: slices of K
+};
+
+Plan plan(const xfp_weights *W, bool expert_indexed, int slots)
 {
     const int bits = (int)W->bits, mode = (int)W->mode;
-    const bool y_f32 = y_dtype == XFP_F32;
     const bool gen = general_only(W);
-    if (prefer_tile(W, 1)) return finish(xfp::launch_decode_tile(bits, y_f32, c, 1, s));
-    if (!gen && xfp::stream_supports(bits, mode, W->K, W->L)) return finish(xfp::launch_decode_stream(bits, mode, y_f32, c, 1, s));
-    if (const int S = gen ? 0 : xfp::splitk_slices(bits, mode, W->N, W->K, W->L, 1)) {
-        const xfp::Workspace *ws = nullptr;
-        hipError_t err = sc.get(&ws);
-        if (err != hipSuccess) return finish(err);
-        return finish(xfp::launch_decode_splitk(bits, mode, y_f32, c, 1, S, ws->part, s));
+    if (!gen && !expert_indexed && xfp::batch_supports(bits, mode, W->L, W->N, W->K, slots)) {
+        // batched tokens: the weights are read once per 16 tokens, once per up to 64 where the wide kernel takes
+        // the format and its re-laid copies fit the workspace
+        int wide = slots < 64 ? slots : 64;
+        while (wide > 16 && !xfp::wide_supports(bits, mode, W->N, W->K, wide)) wide -= 16;
+        if (wide > 16) return Plan{XFP_ROUTE_WIDE, wide, 0};
+        if (slots >= 2) return Plan{XFP_ROUTE_BATCH, slots < 16 ? slots : 16, 0};
     }
-    if (!rows_fits(W)) return XFP_ERR_UNSUPPORTED;
-    c.rows_per_block = rows_per_block(W->N, 1);
-    return finish(xfp::launch_decode_rows(bits, mode, y_f32, c, 1, s));
+    // M = 1 per slot: every remaining slot in one launch (also the odd token left over after chunks of 16)
+    const int take = slots;
+    if (prefer_tile(W, take)) return Plan{XFP_ROUTE_TILE, take, 0};
+    if (!gen && xfp::stream_supports(bits, mode, W->K, W->L)) return Plan{XFP_ROUTE_STREAM, take, 0};
+    if (const int S = gen ? 0 : xfp::splitk_slices(bits, mode, W->N, W->K, W->L, take)) return Plan{XFP_ROUTE_SPLIT_K, take, S};
+    if (!rows_fits(W)) return Plan{XFP_ERR_UNSUPPORTED, 0, 0};
+    return Plan{XFP_ROUTE_GENERAL, take, 0};
 }
 
 // y_dtype: an xfp_dtype, optionally OR-ed with XFP_X_BF16
@@ -204,6 +216,7 @@ int decode(const xfp_weights *W, const int32_t *eids, int slots, const void *x, 
     const bool x_bf16 = (y_dtype & XFP_X_BF16) != 0;
     y_dtype &= 0xFF;
     const int bits = (int)W->bits, mode = (int)W->mode;
+    const bool y_f32 = y_dtype == XFP_F32;
     xfp::DecodeArgs a = base_args(W);
     a.x = static_cast<const uint16_t *>(x);
     a.y = y;
@@ -212,47 +225,36 @@ int decode(const xfp_weights *W, const int32_t *eids, int slots, const void *x, 
     a.y_stride = ldy;
     a.y_bf16 = y_dtype == XFP_BF16;
     a.x_bf16 = x_bf16;
-    const bool gen = general_only(W);
-    if (!gen && !eids && xfp::batch_supports(bits, mode, W->L, W->N, W->K, slots)) {
-        // batched tokens: the weights are read once per 16 tokens (once per up to 64 where the wide kernel
-        // takes the format); the chunks run in stream order, so they share the workspace
-        const size_t ysz = y_dtype == XFP_F32 ? 4 : 2;
+    const size_t ysz = y_f32 ? 4 : 2;
+    // the launches of a call run in stream order, so they share the call's workspace
+    for (int m0 = 0; m0 < slots;) {
+        const Plan p = plan(W, eids != nullptr, slots - m0);
+        if (p.route < 0) return p.route;
+        xfp::DecodeArgs c = a;
+        c.x = a.x + (int64_t)m0 * x_stride;
+        c.y = static_cast<char *>(y) + (size_t)m0 * (size_t)ldy * ysz;
+        if (eids) c.eids = eids + m0;
         const xfp::Workspace *ws = nullptr;
-        hipError_t werr = sc.get(&ws);
-        if (werr != hipSuccess) return finish(werr);
-        for (int m0 = 0; m0 < slots;) {
-            xfp::DecodeArgs c = a;
-            c.x = a.x + (int64_t)m0 * x_stride;
-            c.y = static_cast<char *>(y) + (size_t)m0 * (size_t)ldy * ysz;
-            // more than 16 tokens left: as many as the wide kernel takes in one pass over the weights
-            int wide = slots - m0 < 64 ? slots - m0 : 64;
-            while (wide > 16 && !xfp::wide_supports(bits, mode, W->N, W->K, wide)) wide -= 16;
-            if (wide > 16) {
-                const int rc = finish(xfp::launch_decode_wide(bits, c, wide, y_dtype == XFP_F32, ws->xc, s));
-                if (rc) return rc;
-                m0 += wide;
-                continue;
-            }
-            const int mc = slots - m0 < 16 ? slots - m0 : 16;
-            m0 += 16;
-            const int rc = mc >= 2 ? finish(xfp::launch_decode_batch(bits, mode, c, mc, y_dtype == XFP_F32, ws->part, ws->xc, s))
-                                   : single_token(W, c, y_dtype, sc, s);
-            if (rc) return rc;
+        if (p.route == XFP_ROUTE_WIDE || p.route == XFP_ROUTE_BATCH || p.route == XFP_ROUTE_SPLIT_K) {
+            hipError_t werr = sc.get(&ws);
+            if (werr != hipSuccess) return finish(werr);
         }
-        return XFP_OK;
-    }
-    if (prefer_tile(W, slots)) return finish(xfp::launch_decode_tile(bits, y_dtype == XFP_F32, a, slots, s));
-    if (!gen && xfp::stream_supports(bits, mode, W->K, W->L))
-        return finish(xfp::launch_decode_stream(bits, mode, y_dtype == XFP_F32, a, slots, s));
-    if (const int S = gen ? 0 : xfp::splitk_slices(bits, mode, W->N, W->K, W->L, slots)) {
-        const xfp::Workspace *ws = nullptr;
-        hipError_t err = sc.get(&ws);
+        hipError_t err = hipSuccess;
+        switch (p.route) {
+        case XFP_ROUTE_WIDE: err = xfp::launch_decode_wide(bits, c, p.take, y_f32, ws->xc, s); break;
+        case XFP_ROUTE_BATCH: err = xfp::launch_decode_batch(bits, mode, c, p.take, y_f32, ws->part, ws->xc, s); break;
+        case XFP_ROUTE_TILE: err = xfp::launch_decode_tile(bits, y_f32, c, p.take, s); break;
+        case XFP_ROUTE_STREAM: err = xfp::launch_decode_stream(bits, mode, y_f32, c, p.take, s); break;
+        case XFP_ROUTE_SPLIT_K: err = xfp::launch_decode_splitk(bits, mode, y_f32, c, p.take, p.slices, ws->part, s); break;
+        default:
+            c.rows_per_block = rows_per_block(W->N, p.take);
+            err = xfp::launch_decode_rows(bits, mode, y_f32, c, p.take, s);
+            break;
+        }
         if (err != hipSuccess) return finish(err);
-        return finish(xfp::launch_decode_splitk(bits, mode, y_dtype == XFP_F32, a, slots, S, ws->part, s));
+        m0 += p.take;
     }
-    if (!rows_fits(W)) return XFP_ERR_UNSUPPORTED;
-    a.rows_per_block = rows_per_block(W->N, slots);
-    return finish(xfp::launch_decode_rows(bits, mode, y_dtype == XFP_F32, a, slots, s));
+    return XFP_OK;
 }
 
 // h[t][j] = SiLU(y[t][j]) * y[t][N/2 + j]: in the streaming kernel's store when it
@@ -511,6 +513,17 @@ int xfp_select_kernel(int which)
     if (which != XFP_KERNEL_AUTO && which != XFP_KERNEL_STREAM && which != XFP_KERNEL_TILE) return XFP_ERR_UNSUPPORTED;
     g_kernel_choice.store(which, std::memory_order_relaxed);
     return XFP_OK;
+}
+
+int xfp_route(const xfp_weights *W, int M, int expert_indexed, int *tokens)
+{
+    int rc = check_weights(W);
+    if (rc) return rc;
+    if (M < 1 || M > 65535) return XFP_ERR_SHAPE;
+    if (!expert_indexed && W->E != 1) return XFP_ERR_SHAPE;
+    const Plan p = plan(W, expert_indexed != 0, M);
+    if (tokens) *tokens = p.take;
+    return p.route;
 }
 
 int xfp_ring_slot(unsigned ticket, int capturing) { return xfp::ring_slot_index(ticket, capturing != 0); }

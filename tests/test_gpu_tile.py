@@ -153,3 +153,13 @@ def test_bench_configuration_7_full_size():
     x = xi.activations(np.random.default_rng(xi.BASE_SEED + 407), 1, W.K)
     y = host(xfp.xfp_gemv(xfp.upload(W), dev_x(x), y_dtype=torch.float32))
     assert gated_rel_err(y, oracle.gemv_weights(W, x)) <= 1e-4
+
+
+def test_a_row_no_other_kernel_takes_goes_to_the_tile_kernel():
+    """1009 groups (a prime: no equal slices for split-K) and too long for the general kernel to stage: at 4 bits
+    V2 the call is the tile kernel's, which takes any number of groups."""
+    W = xi.random_weights(V2, 4, 40, 128 * 1009, density=0.001, seed=31)
+    assert xfp.xfp_route(xfp.upload(W), 1) == (xfp.XFP_ROUTE_TILE, 1)
+    x = xi.activations(np.random.default_rng(32), 1, W.K)
+    y = host(xfp.xfp_gemv(xfp.upload(W), dev_x(x), y_dtype=torch.float32))
+    assert gated_rel_err(y, oracle.gemv_weights(W, x)) <= 1e-4

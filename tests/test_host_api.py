@@ -104,9 +104,11 @@ def test_unsupported_format():
 def test_rows_no_kernel_can_take_are_rejected_up_front():
     """Longer than the streaming kernel holds, no split into equal slices (a prime number of groups),
     and too long for the general kernel to stage in LDS: refused before anything is launched."""
-    assert gemv(desc(K=128 * 1009), ldx=128 * 1009) == -3
     assert gemv(desc(K=128 * 1009, bits=3), ldx=128 * 1009) == -3
-    assert moe(desc(E=4, K=128 * 1009), xs=128 * 1009) == -3
+    assert gemv(desc(K=128 * 1009, bits=2), ldx=128 * 1009) == -3
+    assert moe(desc(E=4, K=128 * 1009, bits=3), xs=128 * 1009) == -3
+    # the same row at 4 bits (V2) is the tile kernel's, which takes any number of groups
+    assert xfp.xfp_route(desc(K=128 * 1009), 1) == (xfp.XFP_ROUTE_TILE, 1)
     assert "too long" in xfp.xfp_strerror(-3) and "bf16" in xfp.xfp_strerror(-3)
 
 
@@ -197,3 +199,54 @@ def test_new_entry_points_reject_bad_arguments():
     chk = lambda dd=d, cap=10, ids=None, T=0, rep=FAKE: lib.xfp_check_contents(ctypes.byref(dd), cap, ids, T, rep, None)
     assert chk(rep=None) == -1 and chk(cap=-1) == -2 and chk(rep=FAKE + 4) == -4
     assert chk(dd=desc(out_col=None)) == -1                   # entries claimed but no column array
+
+
+def route(d, M, moe=False):
+    return xfp.xfp_route(d, M, moe)
+
+
+def test_dispatch_rule_on_the_host():
+    """xfp_route reports the rule the decode calls execute (one function in the library serves both): the five
+    workloads and the configurations bench.py times land on the kernels the design notes name, and the size
+    limits sit where the header says."""
+    R = xfp
+    v2a = dict(mode=1, L=32, group_ids=FAKE)
+    # the five workloads
+    assert route(desc(N=512, K=1024), 1) == (R.XFP_ROUTE_STREAM, 1)                       # C1
+    assert route(desc(N=8192, K=4096), 1) == (R.XFP_ROUTE_STREAM, 1)                      # C2: 2^25 weights
+    assert route(desc(N=4096, K=4096, bits=3, **v2a), 1) == (R.XFP_ROUTE_STREAM, 1)       # C3
+    assert route(desc(N=2048, K=4096, bits=3, E=256), 8, moe=True) == (R.XFP_ROUTE_STREAM, 8)   # C4 gate_up
+    assert route(desc(N=28672, K=8192), 16) == (R.XFP_ROUTE_BATCH, 16)                    # C5
+    # M = 1: the tile kernel from 2^26 weights per call on and for rows beyond 16384 columns (4-bit V2 only)
+    assert route(desc(N=16384, K=4096), 1) == (R.XFP_ROUTE_TILE, 1)
+    assert route(desc(N=8192, K=28672), 1) == (R.XFP_ROUTE_TILE, 1)
+    assert route(desc(N=64, K=16384 + 128), 1) == (R.XFP_ROUTE_TILE, 1)
+    assert route(desc(N=16384, K=4096, bits=3), 1) == (R.XFP_ROUTE_STREAM, 1)
+    assert route(desc(N=8192, K=28672, bits=3), 1) == (R.XFP_ROUTE_SPLIT_K, 1)
+    assert route(desc(N=2048, K=4096, E=16), 8, moe=True) == (R.XFP_ROUTE_TILE, 8)        # 8 slots x 2^23 weights
+    # tokens: 2 .. 16 the batched kernel; more: as many as the wide kernel's copies hold, then the rest
+    assert route(desc(N=64, K=8192), 2) == (R.XFP_ROUTE_BATCH, 2)
+    assert route(desc(N=64, K=8192), 17) == (R.XFP_ROUTE_WIDE, 17)
+    assert route(desc(N=64, K=8192), 64) == (R.XFP_ROUTE_WIDE, 64)
+    assert route(desc(N=64, K=8192), 200) == (R.XFP_ROUTE_WIDE, 64)
+    assert route(desc(N=64, K=8192 + 128), 64) == (R.XFP_ROUTE_WIDE, 48)                  # 16 * 3 * K <= 2^19 < 16 * 4 * K
+    assert route(desc(N=64, K=16384), 64) == (R.XFP_ROUTE_WIDE, 32)
+    assert route(desc(N=64, K=16384 + 128), 64) == (R.XFP_ROUTE_BATCH, 16)                # one chunk only: chunks of 16
+    assert route(desc(N=64, K=8192, bits=3), 40) == (R.XFP_ROUTE_WIDE, 40)
+    assert route(desc(N=64, K=8192, bits=3, **v2a), 40) == (R.XFP_ROUTE_BATCH, 16)        # the wide kernel is V2 only
+    assert route(desc(N=64, K=8192, bits=2, **v2a), 40) == (R.XFP_ROUTE_STREAM, 40)       # no batched kernel: 40 slots, M = 1 each
+    # widths 5 and 6 and tensors with a scale and a mid-point per group: the general kernel, token by token
+    assert route(desc(N=64, K=4096, bits=5), 3) == (R.XFP_ROUTE_GENERAL, 3)
+    assert route(desc(N=64, K=4096, flags=1, group_scale=FAKE, group_mid=FAKE, **v2a), 1) == (R.XFP_ROUTE_GENERAL, 1)
+    # what xfp_select_kernel changes, xfp_route reports
+    xfp.xfp_select_kernel(xfp.XFP_KERNEL_TILE)
+    try:
+        assert route(desc(N=512, K=1024), 1) == (R.XFP_ROUTE_TILE, 1)
+    finally:
+        xfp.xfp_select_kernel(xfp.XFP_KERNEL_AUTO)
+    # errors come back as the decode calls would raise them
+    with pytest.raises(xfp.XfpError) as ei:
+        route(desc(K=128 * 1009, bits=3), 1)
+    assert ei.value.status == -3
+    with pytest.raises(xfp.XfpError):
+        route(desc(K=200), 1)
