@@ -1,5 +1,6 @@
 // Wide form of the batched decode on the matrix cores: up to 64 tokens per pass
-// over the weights (V2 codebooks, 2-, 3- or 4-bit indices).
+// over the weights (V2 codebooks, 2-, 3- or 4-bit indices): the batched variant
+// of the fused kernel for M >= 16 (paper section 5), same four fused steps.
 //
 // Why: the 16-token kernel keeps its tokens' activations in registers as B
 // operands (128 of a wave's 256 registers), so more than 16 tokens mean another
@@ -16,8 +17,10 @@
 //     B (32 k x 16 tokens) activations of one chunk: one 16-byte load per lane from the
 //                          operand-ordered copy of x (1 KB contiguous per wave, L2 hits);
 //     D (16 x 16 fp32)     one accumulator per (row block, chunk): 2 T of them.
-// 2 T v_mfma_f32_16x16x32_f16 per 8 lookups: at T = 4 the matrix cores, not the
-// lookups, set the pace.  A 32-row tile halves the B traffic of a 16-row one
+// 2 T v_mfma_f32_16x16x32_f16 per 8 lookups: by instruction count the matrix
+// cores, not the lookups, set the pace at T = 4 (measured, the kernel mostly
+// waits: a wave's loads complete in issue order, so its B operands, L2 hits,
+// queue behind its index words, HBM misses).  A 32-row tile halves the B traffic of a 16-row one
 // (every B operand meets two A operands); the B operands live in a ring of a few
 // steps, requested that many steps ahead.
 //
@@ -69,6 +72,12 @@ struct WideLds {
     static constexpr int kOut = kWideWaves * kPlane > kTab ? kWideWaves * kPlane : kTab;   // the outlier plane: behind both
     static constexpr int kTotal = kOut + kPlane;                       // 76 032 bytes at T = 4; 4 bits, T = 1: 67 648
 };
+
+// Where a group's four pieces per row block live: at 4 bits they are the index words themselves (in place), else
+// registers of their own.
+__device__ __forceinline__ uint32_t (&pieces_of(uint32_t (&words)[2][4], uint32_t (&)[1][4]))[2][4] { return words; }
+template <int CW>
+__device__ __forceinline__ uint32_t (&pieces_of(uint32_t (&)[2][CW], uint32_t (&own)[2][4]))[2][4] { return own; }
 
 struct WideArgs {
     DecodeArgs a;
@@ -304,10 +313,7 @@ void decode_wide_kernel(WideArgs ta)
         // they are transposed in place and the slot is refilled once its last lookup address is formed; at 3 and
         // 2 bits the pieces are registers of their own and the slot is refilled at once.
         uint32_t pw_own[BITS == 4 ? 1 : 2][4];
-        uint32_t (&pw)[2][4] = *[&]() -> uint32_t (*)[2][4] {
-            if constexpr (BITS == 4) return &iw[d];
-            else return &pw_own;
-        }();
+        uint32_t (&pw)[2][4] = pieces_of(iw[d], pw_own);
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) {
             if constexpr (BITS == 3) {
