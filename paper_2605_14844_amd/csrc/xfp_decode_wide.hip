@@ -147,20 +147,22 @@ void decode_wide_kernel(WideArgs ta)
     // weights is 16, 12 or 8 bytes; the quad reads 64, 48 or 32 contiguous bytes.
     uint32_t iw[D][2][CW];
     auto load_group = [&](uint32_t (&w)[2][CW], uint32_t g) {  // rows past the end of the matrix read zeros
-        const uint32_t so = g * (16 * CW);                 // read once: non-temporal
+        // plain loads: two neighbouring groups of a row share a 128-byte line and are fetched by different waves at
+        // different times; with the non-temporal hint the line often left L2 in between (4 % slower)
+        const uint32_t so = g * (16 * CW);
         if constexpr (BITS == 4) {
-            const u32x4_t v0 = __builtin_amdgcn_raw_buffer_load_b128(ri, ioff0, so, 2);
-            const u32x4_t v1 = __builtin_amdgcn_raw_buffer_load_b128(ri, ioff1, so, 2);
+            const u32x4_t v0 = __builtin_amdgcn_raw_buffer_load_b128(ri, ioff0, so, 0);
+            const u32x4_t v1 = __builtin_amdgcn_raw_buffer_load_b128(ri, ioff1, so, 0);
             w[0][0] = v0.x; w[0][1] = v0.y; w[0][2] = v0.z; w[0][3] = v0.w;
             w[1][0] = v1.x; w[1][1] = v1.y; w[1][2] = v1.z; w[1][3] = v1.w;
         } else if constexpr (BITS == 3) {
-            const u32x3_t v0 = __builtin_amdgcn_raw_buffer_load_b96(ri, ioff0, so, 2);
-            const u32x3_t v1 = __builtin_amdgcn_raw_buffer_load_b96(ri, ioff1, so, 2);
+            const u32x3_t v0 = __builtin_amdgcn_raw_buffer_load_b96(ri, ioff0, so, 0);
+            const u32x3_t v1 = __builtin_amdgcn_raw_buffer_load_b96(ri, ioff1, so, 0);
             w[0][0] = v0.x; w[0][1] = v0.y; w[0][2] = v0.z;
             w[1][0] = v1.x; w[1][1] = v1.y; w[1][2] = v1.z;
         } else {
-            const u32x2_t v0 = __builtin_amdgcn_raw_buffer_load_b64(ri, ioff0, so, 2);
-            const u32x2_t v1 = __builtin_amdgcn_raw_buffer_load_b64(ri, ioff1, so, 2);
+            const u32x2_t v0 = __builtin_amdgcn_raw_buffer_load_b64(ri, ioff0, so, 0);
+            const u32x2_t v1 = __builtin_amdgcn_raw_buffer_load_b64(ri, ioff1, so, 0);
             w[0][0] = v0.x; w[0][1] = v0.y;
             w[1][0] = v1.x; w[1][1] = v1.y;
         }
