@@ -182,12 +182,15 @@ void decode_wide_kernel(WideArgs ta)
     // The whole outlier term is computed HERE, in front of the first barrier, where a wave otherwise only waits
     // (for its codebook, for the other waves' table parts); its result goes to a plane of its own outside the
     // table region and is picked up by the final sum.
-    // Lane (e8, o8) = (lane / 8, lane % 8) takes entries e8, e8 + 8, ... of each of the wave's four rows and the
-    // eight tokens 8 o8 .. 8 o8 + 7.  The run's first 128 (column, value) pairs are fetched with lane = entry,
-    // four load instructions per wave (a CU keeps only about 64 vector-memory instructions in flight, and at
+    // Lane (e8, o8) = (lane / OP, lane % OP) takes entries e8, e8 + EP, ... of each of the wave's four rows and the
+    // eight tokens 8 o8 .. 8 o8 + 7, where OP is the number of token octets rounded up to a power of two (2, 4 or 8)
+    // and EP = 64 / OP the entries one wave instruction covers (32, 16 or 8).  The run's first 128 (column, value)
+    // pairs are fetched with lane = entry, four load instructions per wave (a CU keeps only about 64 vector-memory instructions in flight, and at
     // this point every wave of the chip wants its codebook), and dealt to their lanes through the LDS crossbar.
-    constexpr int JP = 4;
-    const uint32_t e8 = lane >> 3, o8 = lane & 7;
+    constexpr int OP = T == 1 ? 2 : T == 2 ? 4 : 8, EP = 64 / OP;
+    constexpr int JP = 32 / EP;                            // EP JP = 32 entries of a row without a loop
+    constexpr int RB = JP == 4 ? 2 : 4;                    // rows whose gathers are issued together
+    const uint32_t e8 = lane / OP, o8 = lane % OP;
     uint32_t run[2];                                       // column | value << 16 of run entries lane, 64 + lane
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
@@ -220,8 +223,8 @@ void decode_wide_kernel(WideArgs ta)
 
     // ---------------------------------------------------------------- a7, second half: gather, multiply, reduce
     // One 16-byte read per lane fetches the eight tokens' activations at the entry's column from the k-major
-    // copy (a wave instruction covers 8 entries x 64 tokens); a lane sums its entries of a row in entry order,
-    // the eight lanes of a token octet are then added in a fixed tree, and lanes 0..7 write the row's sums to
+    // copy (a wave instruction covers EP entries x all tokens); a lane sums its entries of a row in entry order,
+    // the EP lanes of a token octet are then added in a fixed tree, and lanes 0 .. OP - 1 write the row's sums to
     // the ninth plane.
     auto outlier_term = [&]() {
         constexpr uint32_t OCT = 2 * T;                    // token octets of the copies
@@ -239,14 +242,14 @@ void decode_wide_kernel(WideArgs ta)
             for (int t = 0; t < 8; ++t)
                 acc8[t] = fmaf(v, half_bits_to_float((uint16_t)(t & 1 ? w[t / 2] >> 16 : w[t / 2] & 0xFFFFu)), acc8[t]);
         };
-        // entry 8 j + e8 of row r, as (column | value << 16): from the run registers when it is among the run's
+        // entry EP j + e8 of row r, as (column | value << 16): from the run registers when it is among the run's
         // first 128, else from memory
         uint32_t pent[4][JP];
 #pragma unroll
         for (int r = 0; r < 4; ++r)
 #pragma unroll
             for (int j = 0; j < JP; ++j) {
-                const int32_t e = oe[r] + 8 * j + (int32_t)e8;
+                const int32_t e = oe[r] + EP * j + (int32_t)e8;
                 const uint32_t pos = (uint32_t)(e - oe[0]);
                 const uint32_t v0 = (uint32_t)__builtin_amdgcn_ds_bpermute((int)((pos & 63u) * 4u), (int)run[0]);
                 const uint32_t v1 = (uint32_t)__builtin_amdgcn_ds_bpermute((int)((pos & 63u) * 4u), (int)run[1]);
@@ -256,30 +259,33 @@ void decode_wide_kernel(WideArgs ta)
             }
         const uint32_t ob = lds0 + L::kOut + (8 * o8 * kTokStride + 4 * wave) * 4;
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {                      // two rows at a time: 8 gathers in flight
-            uint4 gx[2][JP];
+        for (int h = 0; h < 4 / RB; ++h) {                 // RB rows at a time: RB JP gathers in flight
+            uint4 gx[RB][JP];
 #pragma unroll
-            for (int r = 0; r < 2; ++r)
+            for (int r = 0; r < RB; ++r)
 #pragma unroll
-                for (int j = 0; j < JP; ++j) gx[r][j] = gather(pent[2 * h + r][j]);
+                for (int j = 0; j < JP; ++j) gx[r][j] = gather(pent[RB * h + r][j]);
 #pragma unroll
-            for (int r = 0; r < 2; ++r) {
-                const int row = 2 * h + r;
+            for (int r = 0; r < RB; ++r) {
+                const int row = RB * h + r;
                 float s8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int j = 0; j < JP; ++j) mac8(s8, pent[row][j], gx[r][j]);
-                // rows with more than 8 JP entries (wave-uniform loop)
-                for (int32_t e0 = oe[row] + 8 * JP; e0 < oe[row + 1]; e0 += 8) {
+                // rows with more than 32 entries (wave-uniform loop)
+                for (int32_t e0 = oe[row] + EP * JP; e0 < oe[row + 1]; e0 += EP) {
                     const int32_t e = e0 + (int32_t)e8;
                     const uint32_t ent = e < oe[row + 1] ? (uint32_t)a.col[e] | ((uint32_t)a.val[e] << 16) : kNone;
                     mac8(s8, ent, gather(ent));
                 }
 #pragma unroll
                 for (int t = 0; t < 8; ++t) {
-                    // over the eight entry lanes (lane bits 3, 4, 5), VALU only: a rotation by 8 inside the row
-                    // of 16 lanes, then the two row swaps (both copies of x go in, the two results are the
+                    // over the EP entry lanes (those with the same lane % OP), VALU only: rotations inside the
+                    // row of 16 lanes, then the two row swaps (both copies of x go in, the two results are the
                     // lane's own half and its partner's)
-                    float x = dpp_add<0x128>(s8[t]);       // row_ror:8
+                    float x = s8[t];
+                    if constexpr (OP <= 2) x = dpp_add<0x122>(x);          // row_ror:2
+                    if constexpr (OP <= 4) x = dpp_add<0x124>(x);          // row_ror:4
+                    x = dpp_add<0x128>(x);                                 // row_ror:8
                     const uint32_t xb16 = __builtin_bit_cast(uint32_t, x);
                     const auto p16 = __builtin_amdgcn_permlane16_swap(xb16, xb16, false, false);
                     x = __builtin_bit_cast(float, (uint32_t)p16[0]) + __builtin_bit_cast(float, (uint32_t)p16[1]);
