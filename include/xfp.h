@@ -139,7 +139,7 @@ typedef struct xfp_weights {
  * y      [M][ldy] of y_dtype, ldy >= N, 16-byte aligned base.
  * M      1 .. 65535.  M = 1 is the decode case.  M >= 2 takes a matrix-core
  *        (MFMA) path that reads the weights once per 16 tokens, for V2 at
- *        every bit width and V2a at 3 or 4 bits with L * 4^bits * 4 bytes
+ *        every bit width and V2a at 2 to 4 bits with L * 4^bits * 4 bytes
  *        <= 64 KB, K <= 32768 (rows above 8192 columns in slices of K whose
  *        partial sums go through a static scratch plane, 4 * S * 16 * N bytes
  *        <= 4 MB for S = ceil(K / 8192) slices); V2 at 2 to 4 bits with more than

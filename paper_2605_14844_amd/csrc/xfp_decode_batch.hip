@@ -10,7 +10,9 @@ hipError_t launch_batch3(const DecodeArgs &a, int M, bool y_f32, float *part, co
                          hipStream_t s);
 hipError_t launch_batch2(const DecodeArgs &a, int M, bool y_f32, float *part, const void *xt, const void *xb,
                          hipStream_t s);
-// defined in xfp_decode_batch_lib3.hip, xfp_decode_batch_lib4.hip
+// defined in xfp_decode_batch_lib2.hip, xfp_decode_batch_lib3.hip, xfp_decode_batch_lib4.hip
+hipError_t launch_batch_lib2(const DecodeArgs &a, int M, bool y_f32, float *part, const void *xt, const void *xb,
+                             hipStream_t s);
 hipError_t launch_batch_lib3(const DecodeArgs &a, int M, bool y_f32, float *part, const void *xt, const void *xb,
                              hipStream_t s);
 hipError_t launch_batch_lib4(const DecodeArgs &a, int M, bool y_f32, float *part, const void *xt, const void *xb,
@@ -53,12 +55,12 @@ __global__ __launch_bounds__(256) void relayout_x_kernel(const uint16_t *x, int6
 
 }  // namespace
 
-// V2 at every bit width; V2a at 3 and 4 bits when the library's pair tables fit the 64 KB table region.
+// V2 and V2a at 2, 3 and 4 bits; V2a when the library's pair tables fit the 64 KB table region.
 // k_cap, plane_cap: what the workspace holds (columns of the re-laid copies, floats of a partial-sum plane).
 bool batch_supports(int bits, int mode, uint32_t L, uint32_t N, uint32_t K, int M, uint64_t k_cap, uint64_t plane_cap)
 {
     const bool format = mode == 0 ? bits >= 2 && bits <= 4
-                                  : mode == 1 && (bits == 3 || bits == 4) && L >= 1 && ((size_t)L << (2 * bits)) * 4 <= 64 * 1024;
+                                  : mode == 1 && bits >= 2 && bits <= 4 && L >= 1 && ((size_t)L << (2 * bits)) * 4 <= 64 * 1024;
     if (!(format && M >= 2 && K % kGroup == 0 && K >= kGroup && K <= k_cap))
         return false;
     if (K <= 8192) return true;
@@ -83,6 +85,7 @@ hipError_t launch_decode_batch(int bits, int mode, const DecodeArgs &a, int M, b
     if (err != hipSuccess) return err;
     if (mode == 1) {
         if (bits == 4) return launch_batch_lib4(a, M, y_f32, part, xc->xt, xc->xb, s);
+        if (bits == 2) return launch_batch_lib2(a, M, y_f32, part, xc->xt, xc->xb, s);
         return launch_batch_lib3(a, M, y_f32, part, xc->xt, xc->xb, s);
     }
     if (bits == 4) return launch_batch_bits<4>(a, M, y_f32, part, xc->xt, xc->xb, s);

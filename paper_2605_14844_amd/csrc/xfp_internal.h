@@ -113,7 +113,7 @@ hipError_t launch_decode_splitk(int bits, int mode, bool y_f32, const DecodeArgs
 // y[slot][n] = sum over slices z, in order, of part[z][slot][n]
 hipError_t launch_splitk_sum(const float *part, uint32_t slices, uint32_t N, int slots, void *y, int64_t y_stride,
                              bool y_f32, bool y_bf16, hipStream_t s);
-// Matrix-core kernel for 2..16 tokens per launch (V2 at 2..4 bits, V2a at 3 and 4 bits
+// Matrix-core kernel for 2..16 tokens per launch (V2 and V2a at 2..4 bits
 // with a library whose pair tables fit 64 KB of LDS; K <= 32768; rows
 // above 8192 columns in slices whose partial sums go through a scratch plane).
 bool batch_supports(int bits, int mode, uint32_t L, uint32_t N, uint32_t K, int M, uint64_t k_cap = kXtMaxK,

@@ -200,7 +200,8 @@ def test_combine_kernel_one_hot_sweep(bits, N, K, E, T):
     (V2, 4, 18, 12288, 0.001), (V2, 4, 16, 28672, 0.0),
     (V2, 3, 33, 4096, 0.003), (V2, 3, 16, 1152, 0.0), (V2, 3, 18, 16384, 0.0),
     (V2, 2, 35, 2048, 0.003), (V2, 2, 16, 8192, 0.0), (V2, 2, 16, 9216, 0.0),
-    (V2A, 3, 33, 4096, 0.003), (V2A, 3, 16, 10240, 0.0), (V2A, 4, 19, 2048, 0.002), (V2A, 4, 16, 8192, 0.0)])
+    (V2A, 3, 33, 4096, 0.003), (V2A, 3, 16, 10240, 0.0), (V2A, 4, 19, 2048, 0.002), (V2A, 4, 16, 8192, 0.0),
+    (V2A, 2, 21, 2048, 0.003), (V2A, 2, 16, 12288, 0.0)])
 def test_batched_kernel_one_hot_sweep(mode, bits, N, K, dens):
     """Every launch of the batched kernel takes 16 one-hot rows (16 different columns); the API walks the K rows
     of the identity in chunks of 16.  M = 5 and M = 2 launches cover the ragged token counts."""

@@ -268,8 +268,8 @@ def test_batched_3bit_2bit_matches_oracle_and_single_calls(bits, N, K, M, dens):
         assert gated_rel_err(yb[m], y1[0]) <= TOL_F32
 
 
-# V2a (library tables, ids per group) through the matrix-core kernel, 3 and 4 bits
-@pytest.mark.parametrize("bits", [3, 4])
+# V2a (library tables, ids per group) through the matrix-core kernel
+@pytest.mark.parametrize("bits", [2, 3, 4])
 @pytest.mark.parametrize("N,K,M,dens", [(200, 8192, 16, 0.003), (77, 1024, 5, 0.003), (64, 4096, 16, 0.003),
                                         (33, 128, 2, 0.01), (90, 1408, 16, 0.003), (50, 5120, 7, 0.0),
                                         (35, 7296, 3, 0.003), (40, 2048, 33, 0.003), (70, 11008, 16, 0.003),
@@ -284,7 +284,7 @@ def test_batched_library_mode_matches_oracle_and_single_calls(bits, N, K, M, den
         assert gated_rel_err(yb[m], y1[0]) <= TOL_F32
 
 
-@pytest.mark.parametrize("bits,L", [(4, 64), (4, 65), (3, 200), (3, 1), (4, 7)])
+@pytest.mark.parametrize("bits,L", [(4, 64), (4, 65), (3, 200), (3, 1), (4, 7), (2, 256), (2, 3)])
 def test_batched_library_sizes(bits, L):
     """Libraries up to the 64 KB of pair tables the kernel holds (64 entries at 4 bits), and one past it, which
     takes the per-token kernels."""
