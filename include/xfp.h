@@ -142,8 +142,8 @@ typedef struct xfp_weights {
  *        every bit width and V2a at 2 to 4 bits with L * 4^bits * 4 bytes
  *        <= 64 KB, K <= 32768 (rows above 8192 columns in slices of K whose
  *        partial sums go through a static scratch plane, 4 * S * 16 * N bytes
- *        <= 4 MB for S = ceil(K / 8192) slices); V2 at 2 to 4 bits with more than
- *        16 tokens reads the weights once per up to 64 tokens (as many chunks
+ *        <= 4 MB for S = ceil(K / 8192) slices); the same formats with more than
+ *        16 tokens read the weights once per up to 64 tokens (as many chunks
  *        of 16 as 16 * ceil(m / 16) * K <= 2^19 allows: 64 tokens up to
  *        K = 8192, 32 up to 16384); any other shape runs the
  *        M = 1 path once per token.  Same results either way, to rounding.

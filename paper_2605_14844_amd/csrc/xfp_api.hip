@@ -196,7 +196,7 @@ Plan plan(const xfp_weights *W, bool expert_indexed, int slots)
         // batched tokens: the weights are read once per 16 tokens, once per up to 64 where the wide kernel takes
         // the format and its re-laid copies fit the workspace
         int wide = slots < 64 ? slots : 64;
-        while (wide > 16 && !xfp::wide_supports(bits, mode, W->N, W->K, wide)) wide -= 16;
+        while (wide > 16 && !xfp::wide_supports(bits, mode, W->L, W->N, W->K, wide)) wide -= 16;
         if (wide > 16) return Plan{XFP_ROUTE_WIDE, wide, 0};
         if (slots >= 2) return Plan{XFP_ROUTE_BATCH, slots < 16 ? slots : 16, 0};
     }
@@ -241,7 +241,7 @@ int decode(const xfp_weights *W, const int32_t *eids, int slots, const void *x, 
         }
         hipError_t err = hipSuccess;
         switch (p.route) {
-        case XFP_ROUTE_WIDE: err = xfp::launch_decode_wide(bits, c, p.take, y_f32, ws->xc, s); break;
+        case XFP_ROUTE_WIDE: err = xfp::launch_decode_wide(bits, mode, c, p.take, y_f32, ws->xc, s); break;
         case XFP_ROUTE_BATCH: err = xfp::launch_decode_batch(bits, mode, c, p.take, y_f32, ws->part, ws->xc, s); break;
         case XFP_ROUTE_TILE: err = xfp::launch_decode_tile(bits, y_f32, c, p.take, s); break;
         case XFP_ROUTE_STREAM: err = xfp::launch_decode_stream(bits, mode, y_f32, c, p.take, s); break;

@@ -1,5 +1,5 @@
 // Wide form of the batched decode on the matrix cores: up to 64 tokens per pass
-// over the weights (V2 codebooks, 2-, 3- or 4-bit indices): the batched variant
+// over the weights (V2 codebooks or a V2a library, 2-, 3- or 4-bit indices): the batched variant
 // of the fused kernel for M >= 16 (paper section 5), same four fused steps.
 //
 // Why: the 16-token kernel keeps its tokens' activations in registers as B
@@ -31,7 +31,8 @@
 // Pair tables: entry e of slot s at LDS byte e * 256 + s * 4, slot = 32 * row block
 // + 16 * (q & 1) + i, every row's table twice, so that the 32 lanes the LDS serves
 // per clock hit 32 banks; a lookup address is one v_perm_b32.  Built once per
-// workgroup (one tile per workgroup).
+// workgroup (one tile per workgroup).  V2a: the library's tables instead, entry e
+// of library entry l at byte (l * 4^BITS + e) * 4, shared by all rows.
 //
 // Epilogue: after a barrier the 8 partial D blocks go to LDS planes that reuse the
 // table region, [wave][token][row].  Outliers: wave w owns tile rows 4 w .. 4 w + 3;
@@ -65,9 +66,12 @@ constexpr int kWideWaves = 8;
 constexpr int kWideThreads = kWideWaves * kWave;
 constexpr int kTokStride = 33;             // floats between two tokens of a plane (32 rows + 1: spreads the banks)
 
-template <int BITS, int T>
+constexpr int kWideLibTab = 64 * 1024;     // V2a: the library's pair tables, L * 4^BITS dwords at most
+
+template <int BITS, int T, int MODE>
 struct WideLds {
-    static constexpr int kTab = (1 << (2 * BITS)) * 256;               // pair tables: [4^BITS entries][64 slots] dwords
+    // pair tables: V2 [4^BITS entries][64 slots] dwords; V2a [L][4^BITS entries] dwords
+    static constexpr int kTab = MODE == 1 ? kWideLibTab : (1 << (2 * BITS)) * 256;
     static constexpr int kPlane = 16 * T * kTokStride * 4;             // [16 T tokens][33] floats
     static constexpr int kOut = kWideWaves * kPlane > kTab ? kWideWaves * kPlane : kTab;   // the outlier plane: behind both
     static constexpr int kTotal = kOut + kPlane;                       // 76 032 bytes at T = 4; 4 bits, T = 1: 67 648
@@ -87,12 +91,15 @@ struct WideArgs {
     int y_f32;
 };
 
-template <int BITS, int T>
+// MODE 0: V2, a codebook per row.  MODE 1: V2a, a library of a.L codebooks and an id per (row, group); the
+// library's pair tables are shared by all rows, so their lookups meet in the banks at random.
+template <int BITS, int T, int MODE>
 __global__ __launch_bounds__(kWideThreads) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void decode_wide_kernel(WideArgs ta)
 {
     static_assert(BITS >= 2 && BITS <= 4, "pair tables of 16, 64 or 256 entries");
-    using L = WideLds<BITS, T>;
+    static_assert(MODE == 0 || MODE == 1, "V2 or V2a");
+    using L = WideLds<BITS, T, MODE>;
     constexpr int CW = BITS;                               // dwords of a lane's chunk of 32 weights
     constexpr uint32_t ENT = 1u << (2 * BITS);             // entries of a pair table
     constexpr int NSLOT = T <= 2 ? 4 : 2;                  // steps of B operands in flight
@@ -122,8 +129,10 @@ void decode_wide_kernel(WideArgs ta)
     const uint32_t trow = (slot >> 5) * 16 + 4 * (slot & 3) + ((slot & 15) >> 2);
     const uint16_t *cbr = a.cb + (size_t)min(n0 + trow, N - 1) * (1u << BITS);
     uint4 c0 = make_uint4(0u, 0u, 0u, 0u), c1 = c0;
-    uint32_t chi;
-    if constexpr (BITS == 4) {
+    uint32_t chi = 0;
+    if constexpr (MODE == 1) {
+        // V2a: the tables come from the library; nothing per row
+    } else if constexpr (BITS == 4) {
         c0 = *reinterpret_cast<const uint4 *>(cbr);
         c1 = *reinterpret_cast<const uint4 *>(cbr + 8);
         chi = reinterpret_cast<const uint32_t *>(cbr)[part];
@@ -146,6 +155,14 @@ void decode_wide_kernel(WideArgs ta)
     // way to keep HBM busy, and a group is consumed faster the fewer tokens there are.  A lane's chunk of 32
     // weights is 16, 12 or 8 bytes; the quad reads 64, 48 or 32 contiguous bytes.
     uint32_t iw[D][2][CW];
+    // V2a: the library ids of a group travel with its index words.  Lane (i, q) fetches the id of its operand row
+    // (row 4 (i % 4) + i / 4 of a block) in row block q % 2, one byte load per group; a row swap hands every lane
+    // both blocks' ids when the group is decoded.  Rows past the end read id 0.
+    uint32_t gidw[MODE == 1 ? D : 1];
+    __amdgpu_buffer_rsrc_t rg = __builtin_amdgcn_make_buffer_rsrc((void *)(MODE == 1 ? a.gid + (size_t)n0 * G : nullptr), 0,
+                                                                  MODE == 1 ? rows_here * G : 0u, 0x00020000);
+    const uint32_t goff = (16 * (q & 1) + 4 * (i & 3) + (i >> 2)) * G;
+    auto load_ids = [&](uint32_t &id, uint32_t g) { id = __builtin_amdgcn_raw_buffer_load_b8(rg, goff, g, 0); };
     auto load_group = [&](uint32_t (&w)[2][CW], uint32_t g) {  // rows past the end of the matrix read zeros
         // plain loads: two neighbouring groups of a row share a 128-byte line and are fetched by different waves at
         // different times; with the non-temporal hint the line often left L2 in between (4 % slower)
@@ -199,6 +216,7 @@ void decode_wide_kernel(WideArgs ta)
     }
     __builtin_amdgcn_sched_barrier(0);
     if (wave < G) {
+        if constexpr (MODE == 1) load_ids(gidw[0], wave);
         load_group(iw[0], wave);
 #pragma unroll
         for (int b = 0; b < NSLOT; ++b) load_b(b, wave, b);
@@ -206,7 +224,34 @@ void decode_wide_kernel(WideArgs ta)
     __builtin_amdgcn_sched_barrier(0);
 
     // ---------------------------------------------------------------- a2: the tile's pair tables
-    {
+    if constexpr (MODE == 1) {
+        // item = (library entry l, second index hi): the 2^BITS consecutive entries (first index 0.., hi) of l's
+        // table, entry e = hi * 2^BITS + first index of library entry l at byte (l * 4^BITS + e) * 4
+        constexpr uint32_t E1 = 1u << BITS;
+        for (uint32_t item = tid; item < (a.L << BITS); item += kWideThreads) {
+            const uint16_t *cbk = a.cb + (size_t)(item >> BITS) * E1;
+            const uint32_t hiv = (uint32_t)cbk[item & (E1 - 1u)] << 16;
+            uint32_t lw[E1 / 2];
+            if constexpr (BITS == 4) {
+                const uint4 v0 = *reinterpret_cast<const uint4 *>(cbk), v1 = *reinterpret_cast<const uint4 *>(cbk + 8);
+                lw[0] = v0.x; lw[1] = v0.y; lw[2] = v0.z; lw[3] = v0.w; lw[4] = v1.x; lw[5] = v1.y; lw[6] = v1.z; lw[7] = v1.w;
+            } else if constexpr (BITS == 3) {
+                const uint4 v0 = *reinterpret_cast<const uint4 *>(cbk);
+                lw[0] = v0.x; lw[1] = v0.y; lw[2] = v0.z; lw[3] = v0.w;
+            } else {
+                const uint2 v0 = *reinterpret_cast<const uint2 *>(cbk);
+                lw[0] = v0.x; lw[1] = v0.y;
+            }
+            const uint32_t base = lds0 + item * (E1 * 4);
+#pragma unroll
+            for (uint32_t j = 0; j < E1; j += 4) {
+                u32x4_t o;
+                o.x = (lw[j / 2] & 0xFFFFu) | hiv; o.y = (lw[j / 2] >> 16) | hiv;
+                o.z = (lw[j / 2 + 1] & 0xFFFFu) | hiv; o.w = (lw[j / 2 + 1] >> 16) | hiv;
+                *(__attribute__((address_space(3))) u32x4_t *)(uintptr_t)(base + j * 4) = o;
+            }
+        }
+    } else {
         const uint32_t clo[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
         constexpr int EPT = (int)ENT / 8;                  // entries per thread: 32, 8, 2
         const uint32_t base = lds0 + part * (EPT * 256) + slot * 4;
@@ -302,7 +347,10 @@ void decode_wide_kernel(WideArgs ta)
     // the rest of the ring of index words (their registers were the outlier term's until here)
 #pragma unroll
     for (int d = 1; d < D; ++d)
-        if (wave + d * kWideWaves < G) load_group(iw[d], wave + d * kWideWaves);
+        if (wave + d * kWideWaves < G) {
+            if constexpr (MODE == 1) load_ids(gidw[d], wave + d * kWideWaves);
+            load_group(iw[d], wave + d * kWideWaves);
+        }
     lds_barrier();
 
     // ---------------------------------------------------------------- a3-a6: the wave's groups
@@ -338,12 +386,23 @@ void decode_wide_kernel(WideArgs ta)
         }
         constexpr int REFILL_STEP = BITS == 4 ? 2 : 0;
         const bool more = g + kWideWaves < G;
+        uint32_t gtab[2] = {0u, 0u};                       // V2a: byte offset of the group's table for either row block
+        if constexpr (MODE == 1) {
+            // lanes 0..15 and 32..47 hold block 0's ids, the others block 1's: the swap gives every lane both
+            const auto both = __builtin_amdgcn_permlane16_swap(gidw[d], gidw[d], false, false);
+            gtab[0] = (uint32_t)both[0] * (ENT * 4);
+            gtab[1] = (uint32_t)both[1] * (ENT * 4);
+        }
         uint32_t av[2][2][4];
         auto lookup = [&](int b, uint32_t (&v)[2][4]) {
 #pragma unroll
             for (int rb = 0; rb < 2; ++rb) {
                 const uint32_t w = pw[rb][b];
-                if constexpr (BITS == 4) {
+                if constexpr (MODE == 1) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        v[rb][j] = *(lds_cu32_t *)(uintptr_t)((((w >> (2 * BITS * j)) & (ENT - 1u)) << 2) | gtab[rb]);
+                } else if constexpr (BITS == 4) {
                     v[rb][0] = *(lds_cu32_t *)(uintptr_t)(__builtin_amdgcn_perm(w, sel, 0x0c0c0400u) + rb * 128);
                     v[rb][1] = *(lds_cu32_t *)(uintptr_t)(__builtin_amdgcn_perm(w, sel, 0x0c0c0500u) + rb * 128);
                     v[rb][2] = *(lds_cu32_t *)(uintptr_t)(__builtin_amdgcn_perm(w, sel, 0x0c0c0600u) + rb * 128);
@@ -359,7 +418,10 @@ void decode_wide_kernel(WideArgs ta)
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
             if (b < 3) lookup(b + 1, av[(b + 1) & 1]);
-            if (b == REFILL_STEP && g + D * kWideWaves < G) load_group(iw[d], g + D * kWideWaves);
+            if (b == REFILL_STEP && g + D * kWideWaves < G) {
+                if constexpr (MODE == 1) load_ids(gidw[d], g + D * kWideWaves);
+                load_group(iw[d], g + D * kWideWaves);
+            }
             __builtin_amdgcn_sched_barrier(0);
             const uint32_t (&cur)[2][4] = av[b & 1];
 #pragma unroll
@@ -454,11 +516,11 @@ __global__ __launch_bounds__(256) void relayout_x_wide_kernel(const uint16_t *x,
     }
 }
 
-template <int BITS, int T>
+template <int BITS, int T, int MODE>
 hipError_t launch_wide_t(const WideArgs &ta, hipStream_t s)
 {
-    constexpr int kLds = WideLds<BITS, T>::kTotal;
-    auto kern = decode_wide_kernel<BITS, T>;
+    constexpr int kLds = WideLds<BITS, T, MODE>::kTotal;
+    auto kern = decode_wide_kernel<BITS, T, MODE>;
     static std::atomic<int> configured[kMaxDevices];       // per device; idempotent attribute, benign race
     const int dev = current_device();
     if (dev < 0) return hipErrorInvalidDevice;
@@ -471,31 +533,33 @@ hipError_t launch_wide_t(const WideArgs &ta, hipStream_t s)
     return hipGetLastError();
 }
 
-template <int BITS>
+template <int BITS, int MODE>
 hipError_t launch_wide_b(const WideArgs &ta, int T, hipStream_t s)
 {
     switch (T) {
-    case 1: return launch_wide_t<BITS, 1>(ta, s);
-    case 2: return launch_wide_t<BITS, 2>(ta, s);
-    case 3: return launch_wide_t<BITS, 3>(ta, s);
-    default: return launch_wide_t<BITS, 4>(ta, s);
+    case 1: return launch_wide_t<BITS, 1, MODE>(ta, s);
+    case 2: return launch_wide_t<BITS, 2, MODE>(ta, s);
+    case 3: return launch_wide_t<BITS, 3, MODE>(ta, s);
+    default: return launch_wide_t<BITS, 4, MODE>(ta, s);
     }
 }
 
 }  // namespace
 
-// V2, 2 to 4 bits, up to 64 tokens whose re-laid copies fit the workspace (16 ceil(M / 16) K halves each).
-bool wide_supports(int bits, int mode, uint32_t N, uint32_t K, int M, uint64_t copy_cap)
+// V2 and V2a (library tables within 64 KB) at 2 to 4 bits, up to 64 tokens whose re-laid copies fit the workspace
+// (16 ceil(M / 16) K halves each).
+bool wide_supports(int bits, int mode, uint32_t L, uint32_t N, uint32_t K, int M, uint64_t copy_cap)
 {
-    if (!(mode == 0 && bits >= 2 && bits <= 4 && M >= 1 && M <= 64 && K % kGroup == 0 && K >= kGroup && N >= 1)) return false;
+    if (!(bits >= 2 && bits <= 4 && M >= 1 && M <= 64 && K % kGroup == 0 && K >= kGroup && N >= 1)) return false;
+    if (!(mode == 0 || (mode == 1 && L >= 1 && ((uint64_t)L << (2 * bits)) * 4 <= (uint64_t)kWideLibTab))) return false;
     return (uint64_t)K * 16u * (uint64_t)((M + 15) / 16) <= copy_cap && (uint64_t)K * 32u * 4u <= 0xFFFFFFFFull;
 }
 
 // M <= 64 tokens in one pass over the weights.  xc: the workspace's re-laid activation copies, written by a
 // small kernel in front of the decode kernel (launches on one stream may share them).
-hipError_t launch_decode_wide(int bits, const DecodeArgs &a, int M, bool y_f32, XCopies *xc, hipStream_t s)
+hipError_t launch_decode_wide(int bits, int mode, const DecodeArgs &a, int M, bool y_f32, XCopies *xc, hipStream_t s)
 {
-    if (!xc || bits < 2 || bits > 4 || M < 1 || M > 64) return hipErrorInvalidValue;
+    if (!xc || bits < 2 || bits > 4 || M < 1 || M > 64 || mode < 0 || mode > 1) return hipErrorInvalidValue;
     const int T = (M + 15) / 16;
     const uint32_t nb = (a.K * 2 * (uint32_t)T + 255) / 256 + (a.K / 8 * 16 * (uint32_t)T + 255) / 256;
     hipLaunchKernelGGL(relayout_x_wide_kernel, dim3(nb), dim3(256), 0, s, a.x, a.x_stride, M, a.K, T, (int)a.x_bf16, xc->xt, xc->xb);
@@ -507,7 +571,8 @@ hipError_t launch_decode_wide(int bits, const DecodeArgs &a, int M, bool y_f32, 
     ta.xb = xc->xb;
     ta.M = M;
     ta.y_f32 = (int)y_f32;
-    return bits == 4 ? launch_wide_b<4>(ta, T, s) : bits == 3 ? launch_wide_b<3>(ta, T, s) : launch_wide_b<2>(ta, T, s);
+    if (mode == 1) return bits == 4 ? launch_wide_b<4, 1>(ta, T, s) : bits == 3 ? launch_wide_b<3, 1>(ta, T, s) : launch_wide_b<2, 1>(ta, T, s);
+    return bits == 4 ? launch_wide_b<4, 0>(ta, T, s) : bits == 3 ? launch_wide_b<3, 0>(ta, T, s) : launch_wide_b<2, 0>(ta, T, s);
 }
 
 }  // namespace xfp

@@ -42,9 +42,11 @@ def test_no_kernel_spills_more_than_a_few_registers():
     (("decode_batch_kernelILi4ELi0ELi8ELi8ELb0ELb0E",), 1),           # workload 5: 8 waves, 8 groups each
     (("decode_tile_kernelILi4ELi16ELb0E",), 4),                       # 8192 x 28672: sixteen waves, one tile per CU
     (("decode_tile_kernelILi4ELi8ELb0E",), 4),                        # large 4-bit matrices: two workgroups per CU
-    (("decode_wide_kernelILi4ELi4E",), 4),                            # 64 tokens in one pass: two workgroups per CU
-    (("decode_wide_kernelILi4ELi2E",), 4),
-    (("decode_wide_kernelILi3ELi4E",), 4),
+    (("decode_wide_kernelILi4ELi4ELi0E",), 4),                        # 64 tokens in one pass: two workgroups per CU
+    (("decode_wide_kernelILi4ELi2ELi0E",), 4),
+    (("decode_wide_kernelILi3ELi4ELi0E",), 4),
+    (("decode_wide_kernelILi3ELi4ELi1E",), 4),                        # V2a
+    (("decode_wide_kernelILi4ELi4ELi1E",), 4),
 ])
 def test_the_workloads_kernels_keep_their_registers(parts, min_waves):
     k = find(resources(), *parts)

@@ -1,4 +1,4 @@
-"""The wide matrix-core kernel (V2, 2 to 4 bits, 17 .. 64 tokens in one pass over the weights): parity with the oracle,
+"""The wide matrix-core kernel (V2 and V2a, 2 to 4 bits, 17 .. 64 tokens in one pass over the weights): parity with the oracle,
 bit-exact depack + gather through one-hot activations, agreement with the single-token calls, the token counts and
 row lengths at which the call falls back to chunks of 16."""
 import numpy as np
@@ -11,7 +11,7 @@ import xfp_inputs as xi
 from helpers import gated_rel_err
 
 pytestmark = pytest.mark.gpu
-V2 = xi.MODE_V2
+V2, V2A = xi.MODE_V2, xi.MODE_V2A
 
 
 def dev_x(x_bits):
@@ -41,9 +41,20 @@ def check(W, x, tol32=1e-4, tol16=1e-3):
                                         (64, 16384, 32, 0.003), (40, 10880, 47, 0.003), (33, 128, 20, 0.05),
                                         (300, 7296, 49, 0.02), (4500, 256, 64, 0.003)])
 @pytest.mark.parametrize("bits", [4, 3, 2])
-def test_wide_kernel_matches_oracle(bits, N, K, M, dens):
-    W = xi.random_weights(V2, bits, N, K, density=dens, seed=N + K + M)
+@pytest.mark.parametrize("mode", [V2, V2A])
+def test_wide_kernel_matches_oracle(mode, bits, N, K, M, dens):
+    W = xi.random_weights(mode, bits, N, K, density=dens, seed=N + K + M)
     check(W, xi.activations(np.random.default_rng(M + N), M, K))
+
+
+@pytest.mark.parametrize("bits,L", [(4, 64), (4, 65), (4, 1), (3, 256), (3, 5), (2, 256), (2, 2)])
+def test_wide_kernel_library_sizes(bits, L):
+    """Libraries up to the 64 KB of pair tables the kernel holds; 65 codebooks at 4 bits are one too many and go
+    token by token."""
+    W = xi.random_weights(V2A, bits, 70, 2048, L=L, density=0.003, seed=L + bits)
+    fits = (L << (2 * bits)) * 4 <= 65536
+    assert (xfp.xfp_route(xfp.upload(W), 40)[0] == xfp.XFP_ROUTE_WIDE) == fits
+    check(W, xi.activations(np.random.default_rng(L), 40, 2048))
 
 
 def test_wide_kernel_agrees_with_single_token_calls_and_is_repeatable():
@@ -68,16 +79,21 @@ def test_wide_kernel_one_row_holds_every_outlier():
     check(W, xi.activations(np.random.default_rng(3), 24, W.K))
 
 
-@pytest.mark.parametrize("bits,N,K,M", [(4, 48, 1024, 64), (4, 37, 640, 19), (3, 48, 1024, 64), (3, 37, 640, 35), (2, 40, 768, 64)])
-def test_wide_kernel_one_hot_sweep(bits, N, K, M):
+@pytest.mark.parametrize("mode,bits,N,K,M", [(V2, 4, 48, 1024, 64), (V2, 4, 37, 640, 19), (V2, 3, 48, 1024, 64), (V2, 3, 37, 640, 35),
+                                             (V2, 2, 40, 768, 64), (V2A, 4, 45, 1152, 64), (V2A, 3, 37, 640, 35),
+                                             (V2A, 2, 50, 768, 48)])
+def test_wide_kernel_one_hot_sweep(mode, bits, N, K, M):
     """Token m carries a single 1.0 at column (k0 + m) of a sweep over all columns: y[m][n] must then be EXACTLY the
     dequantized weight Codebook[n][q[n, k]] (+ the outlier at that position), bit for bit: the kernel's own depack
     and gather, not the stand-alone hooks', are what is checked."""
-    W = xi.random_weights(V2, bits, N, K, density=0.01, seed=N + K)
+    W = xi.random_weights(mode, bits, N, K, density=0.01, seed=N + K)
     dW = xfp.upload(W)
-    q = oracle.unpack(W.indices[0], K, bits)
-    cb = W.codebooks[0].view(np.float16).astype(np.float32)                     # [N][2^bits]
-    dense = np.take_along_axis(cb, q.astype(np.int64), axis=1)                  # [N][K]
+    q = oracle.unpack(W.indices[0], K, bits).astype(np.int64)
+    cb = W.codebooks[0].view(np.float16).astype(np.float32)                     # V2 [N][2^bits], V2a [L][2^bits]
+    if mode == V2:
+        dense = np.take_along_axis(cb, q, axis=1)                               # [N][K]
+    else:
+        dense = cb[np.repeat(W.group_ids[0].astype(np.int64), 128, axis=1), q]  # the group's library entry
     rp, col, val = W.out_row_ptr, W.out_col, W.out_val.view(np.float16).astype(np.float32)
     for n in range(N):
         for j in range(rp[n], rp[n + 1]):
@@ -130,6 +146,12 @@ def test_workload_5_shape_at_3_bits_with_48_tokens_full_size():
     """28672 x 8192, 3 bits (the matrix of bench.py --config 9), 48 tokens in one pass."""
     W = xi.random_weights(V2, 3, 28672, 8192, density=0.003, seed=xi.BASE_SEED + 9)
     check(W, xi.activations(np.random.default_rng(xi.BASE_SEED + 448), 48, W.K))
+
+
+def test_library_matrix_of_configuration_10_with_64_tokens_full_size():
+    """28672 x 8192, V2a 3-bit, L = 32 (the matrix of bench.py --config 10), 64 tokens in one pass."""
+    W = xi.random_weights(V2A, 3, 28672, 8192, L=32, density=0.003, seed=xi.BASE_SEED + 10)
+    check(W, xi.activations(np.random.default_rng(xi.BASE_SEED + 464), 64, W.K))
 
 
 def test_workload_5_matrix_with_64_tokens_full_size():

@@ -233,8 +233,8 @@ def test_dispatch_rule_on_the_host():
     assert route(desc(N=64, K=16384), 64) == (R.XFP_ROUTE_WIDE, 32)
     assert route(desc(N=64, K=16384 + 128), 64) == (R.XFP_ROUTE_BATCH, 16)                # one chunk only: chunks of 16
     assert route(desc(N=64, K=8192, bits=3), 40) == (R.XFP_ROUTE_WIDE, 40)
-    assert route(desc(N=64, K=8192, bits=3, **v2a), 40) == (R.XFP_ROUTE_BATCH, 16)        # the wide kernel is V2 only
-    assert route(desc(N=64, K=8192, bits=2, **v2a), 40) == (R.XFP_ROUTE_BATCH, 16)
+    assert route(desc(N=64, K=8192, bits=3, **v2a), 40) == (R.XFP_ROUTE_WIDE, 40)
+    assert route(desc(N=64, K=8192, bits=2, **v2a), 40) == (R.XFP_ROUTE_WIDE, 40)
     # widths 5 and 6 and tensors with a scale and a mid-point per group: the general kernel, token by token
     assert route(desc(N=64, K=4096, bits=5), 3) == (R.XFP_ROUTE_GENERAL, 3)
     assert route(desc(N=64, K=4096, flags=1, group_scale=FAKE, group_mid=FAKE, **v2a), 1) == (R.XFP_ROUTE_GENERAL, 1)
