@@ -528,6 +528,8 @@ def test_every_decode_call_replays_from_a_hip_graph():
         ("batched v2a", xi.random_weights(V2A, 4, 48, 4096, density=0.003, seed=7), 16),
         ("40 tokens in one pass", xi.random_weights(V2, 4, 70, 4096, density=0.003, seed=8), 40),
         ("33 tokens, 3 bits", xi.random_weights(V2, 3, 48, 2048, density=0.003, seed=9), 33),
+        ("48 tokens, v2a", xi.random_weights(V2A, 4, 56, 2048, density=0.003, seed=10), 48),
+        ("batched v2a 2 bits", xi.random_weights(V2A, 2, 40, 4096, density=0.003, seed=11), 12),
     ]
     side = torch.cuda.Stream()
     for name, W, M in cases:

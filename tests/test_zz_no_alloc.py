@@ -47,6 +47,8 @@ def one_call(mode, bits, N, K, M, seed, dtype):
     # more than 16 tokens in one pass over the weights (wider re-laid copies in the same array), then 16 tokens
     ((V2, 4, 100, 8192, 64), (V2, 4, 50, 4096, 16)),
     ((V2, 3, 77, 16384, 40), (V2, 3, 33, 1024, 20)),
+    # the same for a library format (V2a), then 2-bit V2a on the 16-token kernel
+    ((V2A, 3, 90, 8192, 64), (V2A, 2, 40, 2048, 9)),
 ])
 def test_two_calls_in_a_row_match_xfp_gemv(first, second):
     for dtype in (torch.float32, torch.float16):
