@@ -41,7 +41,7 @@ def parse_args():
                    help="workload 1..5 (default 2, the headline); beyond the five: 6 = workload 4 as a whole expert "
                         "layer with both epilogues fused, 7 = a long-row matrix (8192x28672, 4-bit, M=1) through the tile kernel, "
                         "8 = the same matrix with 16 tokens, 9 = workload 5's shape at 3 bits, 10 = the same as V2a, "
-                        "11 = workload 2's shape at 2 bits, 12 = workload 5's matrix with 64 tokens (wide matrix-core kernel)")
+                        "11 = workload 2's shape at 2 bits, 12 = workload 5's matrix with 64 tokens (wide matrix-core kernel), 13 = configuration 10's matrix with 64 tokens")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--single", action="store_true", help="time only --config (the default run of workload 2 also "
                    "times workloads 1, 3, 4, 5 and a 2-bit matrix and reports them under \"configs\")")
@@ -233,10 +233,16 @@ def build_workload(cfg: int, ring_bytes: int):
         return dict(name=name, step=step, bytes=nbytes, ring=R, oracle=oracle_once, launches=3 if cfg == 8 else 2,
                     kernel_bytes=nbytes, launch_bytes=[nbytes], keep=(ring, xd, y), M=16, N=W.N, K=W.K, bits=W.bits,
                     mode=W.mode)
-    if cfg == 12:
-        # workload 5's matrix with 64 tokens: one pass of the wide matrix-core kernel
-        W = xi.config_weights(5)
-        xb = xi.config_x(5, 64, W.K)
+    if cfg in (12, 13):
+        # 64 tokens in one pass of the wide matrix-core kernel: workload 5's matrix (12), configuration 10's (13)
+        if cfg == 12:
+            W = xi.config_weights(5)
+            xb = xi.config_x(5, 64, W.K)
+            name = "V2 28672x8192 b4 M=64 (workload 5's matrix, 64 tokens in one pass: wide matrix-core kernel, two launches)"
+        else:
+            W = xi.random_weights(xi.MODE_V2A, 3, 28672, 8192, L=32, density=0.003, seed=xi.BASE_SEED + 10)
+            xb = xi.activations(np.random.default_rng(xi.BASE_SEED + 413), 64, W.K)
+            name = "V2a 28672x8192 b3 L=32 M=64 (configuration 10's matrix, 64 tokens in one pass: wide matrix-core kernel, two launches)"
         nbytes = W.algorithmic_bytes(M=64)
         R = max(1, min(512, -(-ring_bytes // nbytes)))
         ring = [xfp.upload(W)]
@@ -252,8 +258,7 @@ def build_workload(cfg: int, ring_bytes: int):
             import oracle
             return oracle.gemv_weights(W, xb, threads)
 
-        return dict(name="V2 28672x8192 b4 M=64 (workload 5's matrix, 64 tokens in one pass: wide matrix-core kernel, two launches)",
-                    step=step, bytes=nbytes, ring=R, oracle=oracle_once, launches=2, kernel_bytes=nbytes,
+        return dict(name=name, step=step, bytes=nbytes, ring=R, oracle=oracle_once, launches=2, kernel_bytes=nbytes,
                     launch_bytes=[nbytes], keep=(ring, xd, y), M=64, N=W.N, K=W.K, bits=W.bits, mode=W.mode)
     raise SystemExit(f"no workload {cfg}")
 
