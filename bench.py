@@ -231,10 +231,10 @@ def build_workload(cfg: int, ring_bytes: int):
             import oracle
             return oracle.gemv_weights(W, xb, threads)
 
-        name = {8: "V2 8192x28672 b4 M=16 (matrix-core kernel over four slices of K, three launches)",
+        name = {8: "V2 8192x28672 b4 M=16 (rows the 16-token kernel would slice: the wide matrix-core kernel, two launches)",
                 9: "V2 28672x8192 b3 M=16 (workload 5's shape at 3 bits, two launches)",
                 10: "V2a 28672x8192 b3 L=32 M=16 (workload 5's shape in workload 3's format, two launches)"}[cfg]
-        return dict(name=name, step=step, bytes=nbytes, ring=R, oracle=oracle_once, launches=3 if cfg == 8 else 2,
+        return dict(name=name, step=step, bytes=nbytes, ring=R, oracle=oracle_once, launches=2,
                     kernel_bytes=nbytes, launch_bytes=[nbytes], keep=(ring, xd, y), M=16, N=W.N, K=W.K, bits=W.bits,
                     mode=W.mode)
     if cfg in (12, 13):

@@ -198,6 +198,13 @@ Plan plan(const xfp_weights *W, bool expert_indexed, int slots)
         int wide = slots < 64 ? slots : 64;
         while (wide > 16 && !xfp::wide_supports(bits, mode, W->L, W->N, W->K, wide)) wide -= 16;
         if (wide > 16) return Plan{XFP_ROUTE_WIDE, wide, 0};
+        // rows the 16-token kernel would cut into slices of K (three launches, partial planes): the wide kernel
+        // takes any row length in one launch and is faster once its 32-row tiles fill the chip (measured, 16 tokens:
+        // 8192 x 28672 at 4 bits 52 against 54 us, at 3 bits 48 against 55, 16384 x 12288 40 against 44, but
+        // 4096 x 16384 with its 128 tiles 31 against 24)
+        if (slots >= 2 && slots <= 16 && xfp::batch_is_split(W->K) && (W->N + 31) / 32 >= 256 &&
+            xfp::wide_supports(bits, mode, W->L, W->N, W->K, slots))
+            return Plan{XFP_ROUTE_WIDE, slots, 0};
         if (slots >= 2) return Plan{XFP_ROUTE_BATCH, slots < 16 ? slots : 16, 0};
     }
     // M = 1 per slot: every remaining slot in one launch (also the odd token left over after chunks of 16)

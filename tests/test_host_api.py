@@ -220,6 +220,11 @@ def test_dispatch_rule_on_the_host():
     # M = 1: the tile kernel from 2^26 weights per call on and for rows beyond 16384 columns (4-bit V2 only)
     assert route(desc(N=16384, K=4096), 1) == (R.XFP_ROUTE_TILE, 1)
     assert route(desc(N=8192, K=28672), 1) == (R.XFP_ROUTE_TILE, 1)
+    # 2 .. 16 tokens on rows the 16-token kernel would cut into slices: the wide kernel once its tiles fill the chip
+    assert route(desc(N=8192, K=28672), 16) == (R.XFP_ROUTE_WIDE, 16)
+    assert route(desc(N=8192, K=28672, bits=3), 5) == (R.XFP_ROUTE_WIDE, 5)
+    assert route(desc(N=8160, K=28672), 16) == (R.XFP_ROUTE_BATCH, 16)
+    assert route(desc(N=4096, K=16384), 16) == (R.XFP_ROUTE_BATCH, 16)
     assert route(desc(N=64, K=16384 + 128), 1) == (R.XFP_ROUTE_TILE, 1)
     assert route(desc(N=16384, K=4096, bits=3), 1) == (R.XFP_ROUTE_STREAM, 1)
     assert route(desc(N=8192, K=28672, bits=3), 1) == (R.XFP_ROUTE_SPLIT_K, 1)
