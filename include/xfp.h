@@ -138,14 +138,14 @@ typedef struct xfp_weights {
  * x      fp16 [M][ldx], ldx >= K, ldx % 8 == 0, 16-byte aligned.
  * y      [M][ldy] of y_dtype, ldy >= N, 16-byte aligned base.
  * M      1 .. 65535.  M = 1 is the decode case.  M >= 2 takes a matrix-core
- *        (MFMA) path that reads the weights once per 16 tokens, for V2 at
- *        every bit width and V2a at 2 to 4 bits with L * 4^bits * 4 bytes
- *        <= 64 KB, K <= 32768 (rows above 8192 columns in slices of K whose
- *        partial sums go through a static scratch plane, 4 * S * 16 * N bytes
- *        <= 4 MB for S = ceil(K / 8192) slices); the same formats with more than
- *        16 tokens read the weights once per up to 64 tokens (as many chunks
+ *        (MFMA) path that reads the weights once per 16 tokens, for V2 and
+ *        V2a at 2 to 4 bits (a V2a library with L * 4^bits * 4 bytes <= 64 KB),
+ *        K <= 32768; rows above 8192 columns in one launch when the matrix
+ *        has 8161 rows or more, else in slices of K whose partial sums go
+ *        through a static scratch plane.  The same formats with more than 16
+ *        tokens read the weights once per up to 64 tokens (as many chunks
  *        of 16 as 16 * ceil(m / 16) * K <= 2^19 allows: 64 tokens up to
- *        K = 8192, 32 up to 16384); any other shape runs the
+ *        K = 8192, 32 up to 16384); any other shape or width runs the
  *        M = 1 path once per token.  Same results either way, to rounding.
  * XFP_ERR_UNSUPPORTED for a row no kernel takes: longer than 16384 columns, not
  * 4-bit V2 (whose rows of any length the tile kernel takes), with no split into
@@ -168,8 +168,7 @@ int xfp_gemv(const xfp_weights *W, const void *x, int M, int64_t ldx,
  * allocating routine.
  * Limits (the array's size): where xfp_gemv would reroute a call because a
  * scratch plane is too small, this one returns XFP_ERR_SCRATCH and launches
- * nothing: M >= 2 with K > 32768; M >= 2, K > 8192 with S * 16 * N > 2^20
- * (S = ceil(K / 8192) slices); rows above 16384 columns that the M = 1 path
+ * nothing: M >= 2 with K > 32768; rows above 16384 columns that the M = 1 path
  * cuts into S equal slices with S * M * N > 2^20 (4-bit V2 rows of that length
  * take the tile kernel, which needs no scratch).
  * Every call on a GPU uses that GPU's one array, which keeps the last call's

@@ -188,11 +188,18 @@ struct Plan {
     int slices;     // split-K: slices of K
 };
 
+// 2 .. 16 tokens on rows above 8192 columns, in a matrix of 256 tiles of 32 rows or more: the wide kernel
+bool long_rows_go_wide(const xfp_weights *W, int tokens)
+{
+    return tokens >= 2 && tokens <= 16 && xfp::batch_is_split(W->K) && (W->N + 31) / 32 >= 256 &&
+           xfp::wide_supports((int)W->bits, (int)W->mode, W->L, W->N, W->K, tokens);
+}
+
 Plan plan(const xfp_weights *W, bool expert_indexed, int slots)
 {
     const int bits = (int)W->bits, mode = (int)W->mode;
     const bool gen = general_only(W);
-    if (!gen && !expert_indexed && xfp::batch_supports(bits, mode, W->L, W->N, W->K, slots)) {
+    if (!gen && !expert_indexed && slots >= 2) {
         // batched tokens: the weights are read once per 16 tokens, once per up to 64 where the wide kernel takes
         // the format and its re-laid copies fit the workspace
         int wide = slots < 64 ? slots : 64;
@@ -202,10 +209,8 @@ Plan plan(const xfp_weights *W, bool expert_indexed, int slots)
         // takes any row length in one launch and is faster once its 32-row tiles fill the chip (measured, 16 tokens:
         // 8192 x 28672 at 4 bits 52 against 54 us, at 3 bits 48 against 55, 16384 x 12288 40 against 44, but
         // 4096 x 16384 with its 128 tiles 31 against 24)
-        if (slots >= 2 && slots <= 16 && xfp::batch_is_split(W->K) && (W->N + 31) / 32 >= 256 &&
-            xfp::wide_supports(bits, mode, W->L, W->N, W->K, slots))
-            return Plan{XFP_ROUTE_WIDE, slots, 0};
-        if (slots >= 2) return Plan{XFP_ROUTE_BATCH, slots < 16 ? slots : 16, 0};
+        if (long_rows_go_wide(W, slots < 16 ? slots : 16)) return Plan{XFP_ROUTE_WIDE, slots < 16 ? slots : 16, 0};
+        if (xfp::batch_supports(bits, mode, W->L, W->N, W->K, slots)) return Plan{XFP_ROUTE_BATCH, slots < 16 ? slots : 16, 0};
     }
     // M = 1 per slot: every remaining slot in one launch (also the odd token left over after chunks of 16)
     const int take = slots;
@@ -328,7 +333,7 @@ int xfp_gemv_noalloc(const xfp_weights *W, const void *x, int M, int64_t ldx, vo
     // a route that only the size of the scratch planes closes is refused, not replaced
     const int bits = (int)W->bits, mode = (int)W->mode;
     constexpr uint64_t kNoCap = ~0ull;
-    if (!general_only(W) &&
+    if (!general_only(W) && !long_rows_go_wide(W, M < 16 ? M : 16) &&
         xfp::batch_supports(bits, mode, W->L, W->N, W->K, M, kNoCap, kNoCap) != xfp::batch_supports(bits, mode, W->L, W->N, W->K, M))
         return XFP_ERR_SCRATCH;
     if (!general_only(W) && !prefer_tile(W, M) &&
@@ -500,7 +505,7 @@ const char *xfp_strerror(int status)
     case XFP_ERR_SHAPE: return "bad shape (sizes must be positive, K a multiple of 128, leading dimensions large enough)";
     case XFP_ERR_UNSUPPORTED: return "unsupported format or shape (bits 2..6, mode V2/V2a, group 128, flags 0 or 1 (V2a only), output fp16/bf16/fp32; a row too long for every kernel; a result too large for the scratch plane)";
     case XFP_ERR_ALIGN: return "a pointer or leading dimension is misaligned";
-    case XFP_ERR_SCRATCH: return "the call needs more scratch memory than xfp_gemv_noalloc's static array holds (M >= 2: K <= 32768 and S * 16 * N <= 2^20; sliced rows: S * M * N <= 2^20)";
+    case XFP_ERR_SCRATCH: return "the call needs more scratch memory than xfp_gemv_noalloc's static array holds (M >= 2: K <= 32768; sliced rows of M = 1 calls: S * M * N <= 2^20)";
     case XFP_ERR_HIP:
         std::snprintf(g_msg, sizeof(g_msg), "HIP launch failed: %s", hipGetErrorString(g_last_hip));
         return g_msg;

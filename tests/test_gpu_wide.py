@@ -159,3 +159,17 @@ def test_workload_5_matrix_with_64_tokens_full_size():
     W = xi.config_weights(5)
     x = xi.config_x(5, 64, W.K)
     check(W, x)
+
+
+def test_long_rows_of_a_tall_matrix_take_one_launch_whatever_the_partial_planes_would_need():
+    """16640 x 28672 with 3 tokens: the 16-token kernel would need four slices whose partial sums (4 x 16 x N
+    floats) exceed its scratch plane; the wide kernel takes the rows whole, also through the entry point that
+    allocates nothing (which refuses calls that only a larger plane would serve)."""
+    W = xi.random_weights(V2, 4, 16640, 28672, density=0.001, seed=31)
+    x = xi.activations(np.random.default_rng(32), 3, W.K)
+    dW, xd, ref, y32 = check(W, x)
+    assert xfp.xfp_route(dW, 3) == (xfp.XFP_ROUTE_WIDE, 3)
+    y = torch.empty((3, W.N), dtype=torch.float32, device="cuda")
+    xfp.xfp_gemv_noalloc(dW, xd, y)
+    torch.cuda.synchronize()
+    assert np.array_equal(y.cpu().numpy().astype(np.float64), y32)

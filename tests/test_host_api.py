@@ -129,7 +129,6 @@ def test_noalloc_entry_point_refuses_what_its_static_array_cannot_hold():
     lib = xfp.load_library()
     call = lambda d, M, ldx: lib.xfp_gemv_noalloc(ctypes.byref(d), FAKE, M, ldx, FAKE, 0, d.N, None)
     assert call(desc(K=65536, bits=2), 2, 65536) == -6             # M >= 2: the re-laid activations hold K <= 32768
-    assert call(desc(K=12288, N=40000), 16, 12288) == -6           # two slices: 2 * 16 * N floats of partial sums > 2^20
     assert call(desc(K=32768, N=300000, bits=3), 1, 32768) == -6   # M = 1 split-K (3 bits): 4 * N floats of partial sums > 2^20
     assert "scratch" in xfp.xfp_strerror(-6)
     assert call(desc(K=200), 1, 256) == -2 and call(desc(bits=9), 1, 256) == -3      # the usual validation comes first
