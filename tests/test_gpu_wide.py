@@ -173,3 +173,17 @@ def test_long_rows_of_a_tall_matrix_take_one_launch_whatever_the_partial_planes_
     xfp.xfp_gemv_noalloc(dW, xd, y)
     torch.cuda.synchronize()
     assert np.array_equal(y.cpu().numpy().astype(np.float64), y32)
+
+
+@pytest.mark.parametrize("mode,bits", [(V2, 4), (V2A, 3)])
+def test_every_token_count_up_to_130(mode, bits):
+    """Chunking: 64 + 64 + 2, 64 + 17, 64 + 1, 48 + ... whatever the count, every token's row must be the single-call
+    row of that token (to rounding) and match the oracle."""
+    W = xi.random_weights(mode, bits, 40, 1024, density=0.003, seed=77 + bits)
+    x = xi.activations(np.random.default_rng(5), 130, W.K)
+    dW, xd = xfp.upload(W), dev_x(x)
+    ref = oracle.gemv_weights(W, x)
+    for M in list(range(1, 70)) + [79, 80, 81, 96, 97, 113, 128, 129, 130]:
+        y = host(xfp.xfp_gemv(dW, xd[:M].contiguous(), y_dtype=torch.float32))
+        assert y.shape == (M, W.N)
+        assert gated_rel_err(y, ref[:M]) <= 1e-4, M

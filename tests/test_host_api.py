@@ -254,3 +254,38 @@ def test_dispatch_rule_on_the_host():
     assert ei.value.status == -3
     with pytest.raises(xfp.XfpError):
         route(desc(K=200), 1)
+
+
+def test_dispatch_invariants_over_random_descriptors():
+    """Whatever the descriptor, every launch takes between 1 and the remaining tokens: 2 .. 16 on the batched route,
+    2 .. 64 on the wide one, all of them on the M = 1 routes; and walking a call launch by launch terminates."""
+    import random
+    rnd = random.Random(2605)
+    R = xfp
+    names = {getattr(R, n) for n in dir(R) if n.startswith("XFP_ROUTE_")}
+    for _ in range(3000):
+        mode = rnd.choice([0, 0, 1])
+        bits = rnd.choice([2, 3, 4, 5, 6]) if mode == 0 else rnd.choice([2, 3, 4])
+        kw = dict(N=rnd.choice([1, 31, 32, 33, 4096, 8160, 8161, 8192, 28672, 70000]), K=128 * rnd.choice([1, 2, 7, 8, 63, 64, 65, 128, 129, 224, 256, 257, 512]),
+                  bits=bits)
+        if mode == 1:
+            kw.update(mode=1, L=rnd.choice([1, 32, 64, 65, 256]), group_ids=FAKE)
+        d = desc(**kw)
+        M = rnd.choice([1, 2, 15, 16, 17, 33, 63, 64, 65, 200])
+        left, launches = M, 0
+        while left:
+            try:
+                r, n = xfp.xfp_route(d, left)
+            except xfp.XfpError as e:
+                assert e.status == -3                         # a row no kernel takes
+                break
+            assert r in names and 1 <= n <= left, (kw, M, left, r, n)
+            if r == R.XFP_ROUTE_BATCH:
+                assert 2 <= n <= 16, (kw, M, left, r, n)
+            elif r == R.XFP_ROUTE_WIDE:
+                assert 2 <= n <= 64, (kw, M, left, r, n)
+            else:
+                assert n == left, (kw, M, left, r, n)         # the M = 1 kernels take every remaining token as a slot
+            left -= n
+            launches += 1
+            assert launches <= M
