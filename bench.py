@@ -345,7 +345,10 @@ def timed_graph(step, K, first, flush):
 
 
 QUEUED_MAX_STEPS = 512
-QUEUED_REPEATS = 3          # the K steps are timed this many times (each behind its own flush); the median is reported
+def queued_repeats(K):
+    """How often the K steps are timed (each time behind its own flush; the median is reported): a timing of 20
+    steps lasts 0.1 ms and scatters by +-4 %, so short runs are repeated until about 1000 steps have been timed."""
+    return max(3, min(51, 1000 // K) | 1)
 
 
 def timed_queued(step, K, first, flush):
@@ -355,8 +358,8 @@ def timed_queued(step, K, first, flush):
     latency nor the fixed cost of a graph launch (about 12 us on this stack, i.e. 0.6 us per step of a 20-step
     replay) inside the events.  Valid only if the host had submitted everything before the GPU reached the first
     step: checked through the time the host still waits after its last launch; returns None if that cannot be
-    had (the caller then times a graph replay instead).  Returns the ms per step of QUEUED_REPEATS such timings of
-    the same K steps, in the order taken (the first one also pays what only a first touch costs)."""
+    had (the caller then times a graph replay instead).  Returns the ms per step of queued_repeats(K) such timings
+    of the same K steps, in the order taken (the first one also pays what only a first touch costs)."""
     import torch
     stream = torch.cuda.current_stream()
     torch.cuda.synchronize()
@@ -373,7 +376,8 @@ def timed_queued(step, K, first, flush):
     flush_us = f0.elapsed_time(f1) * 1e3
     n = int(1.5 * K * host_us / flush_us) + 3
     good = []
-    for _ in range(QUEUED_REPEATS + 2):
+    repeats = queued_repeats(K)
+    for _ in range(repeats + 2):
         g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         for _j in range(n):
@@ -388,7 +392,7 @@ def timed_queued(step, K, first, flush):
         ms = g0.elapsed_time(g1) / K
         if waited_us >= 1.2 * K * ms * 1e3 + 50.0:             # the whole timed region ran after the last launch
             good.append(ms)
-            if len(good) == QUEUED_REPEATS:
+            if len(good) == repeats:
                 return good
         else:
             n *= 2
@@ -400,9 +404,12 @@ def timed_steps(step, K, first, flush):
     if K <= QUEUED_MAX_STEPS:
         runs = timed_queued(step, K, first, flush)
         if runs is not None:
+            srt = sorted(runs)
             how = ("eager launches already queued behind the cache-flush kernels, events on the launch stream; median of "
-                   f"{len(runs)} timings of the same {K} steps: " + ", ".join(f"{r * 1e3:.3f}" for r in runs) + " us per step")
-            return sorted(runs)[len(runs) // 2], None, how
+                   f"{len(runs)} timings of the same {K} steps (first {runs[0] * 1e3:.3f}, min {srt[0] * 1e3:.3f}, "
+                   f"quartiles {srt[len(srt) // 4] * 1e3:.3f} / {srt[len(srt) // 2] * 1e3:.3f} / {srt[3 * len(srt) // 4] * 1e3:.3f}, "
+                   f"max {srt[-1] * 1e3:.3f} us per step)")
+            return srt[len(srt) // 2], None, how
     ms, wall = timed_graph(step, K, first, flush)
     return ms, wall, "hip graph replay"
 
