@@ -368,12 +368,14 @@ def timed_queued(step, K, first, flush):
         step(first + i)
     host_us = (time.perf_counter() - t) * 1e6 / 8            # what the host needs to submit one step
     torch.cuda.synchronize()
-    f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    f0.record(stream)
-    flush.launch()
-    f1.record(stream)
-    torch.cuda.synchronize()
-    flush_us = f0.elapsed_time(f1) * 1e3
+    flush_us = 1e30                                          # the shortest of three: a first launch can take ten times as long
+    for _ in range(3):
+        f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        f0.record(stream)
+        flush.launch()
+        f1.record(stream)
+        torch.cuda.synchronize()
+        flush_us = min(flush_us, f0.elapsed_time(f1) * 1e3)
     n = int(1.5 * K * host_us / flush_us) + 3
     good = []
     repeats = queued_repeats(K)

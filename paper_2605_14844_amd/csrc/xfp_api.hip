@@ -118,8 +118,16 @@ struct Scratch {
     }
 };
 
-// Formats only the general kernel takes: 5- and 6-bit indices, a scale and a mid-point per group.
+// Formats outside the batched, split and fused kernels: 5- and 6-bit indices, a scale and a mid-point per group.
+// (The latter has ONE tuned kernel, the plain streaming one: stream_affine below.)
 bool general_only(const xfp_weights *W) { return W->bits > 4 || (W->flags & XFP_FLAG_GROUP_AFFINE) != 0; }
+
+// V2a with a scale and a mid-point per group, 2..4 bits, rows the streaming kernel holds: its MODE 2
+bool stream_affine(const xfp_weights *W)
+{
+    return (W->flags & XFP_FLAG_GROUP_AFFINE) != 0 && W->mode == XFP_MODE_V2A && W->bits <= 4 &&
+           xfp::stream_supports((int)W->bits, 2, W->K, W->L);
+}
 
 // Longest row the general kernel can stage: x (2 K bytes) and its tables share the
 // 160 KB of LDS of a compute unit.
@@ -136,7 +144,7 @@ bool prefer_tile(const xfp_weights *W, int slots);
 bool decodable(const xfp_weights *W, int slots)
 {
     const int bits = (int)W->bits, mode = (int)W->mode;
-    if (general_only(W)) return rows_fits(W);
+    if (general_only(W)) return stream_affine(W) || rows_fits(W);
     return prefer_tile(W, slots) || xfp::stream_supports(bits, mode, W->K, W->L) ||
            xfp::splitk_slices(bits, mode, W->N, W->K, W->L, slots) || rows_fits(W);
 }
@@ -215,6 +223,7 @@ Plan plan(const xfp_weights *W, bool expert_indexed, int slots)
     // M = 1 per slot: every remaining slot in one launch (also the odd token left over after chunks of 16)
     const int take = slots;
     if (prefer_tile(W, take)) return Plan{XFP_ROUTE_TILE, take, 0};
+    if (stream_affine(W)) return Plan{XFP_ROUTE_STREAM, take, 0};
     if (!gen && xfp::stream_supports(bits, mode, W->K, W->L)) return Plan{XFP_ROUTE_STREAM, take, 0};
     if (const int S = gen ? 0 : xfp::splitk_slices(bits, mode, W->N, W->K, W->L, take)) return Plan{XFP_ROUTE_SPLIT_K, take, S};
     if (!rows_fits(W)) return Plan{XFP_ERR_UNSUPPORTED, 0, 0};
@@ -256,7 +265,7 @@ int decode(const xfp_weights *W, const int32_t *eids, int slots, const void *x, 
         case XFP_ROUTE_WIDE: err = xfp::launch_decode_wide(bits, mode, c, p.take, y_f32, ws->xc, s); break;
         case XFP_ROUTE_BATCH: err = xfp::launch_decode_batch(bits, mode, c, p.take, y_f32, ws->part, ws->xc, s); break;
         case XFP_ROUTE_TILE: err = xfp::launch_decode_tile(bits, y_f32, c, p.take, s); break;
-        case XFP_ROUTE_STREAM: err = xfp::launch_decode_stream(bits, mode, y_f32, c, p.take, s); break;
+        case XFP_ROUTE_STREAM: err = xfp::launch_decode_stream(bits, stream_affine(W) ? 2 : mode, y_f32, c, p.take, s); break;
         case XFP_ROUTE_SPLIT_K: err = xfp::launch_decode_splitk(bits, mode, y_f32, c, p.take, p.slices, ws->part, s); break;
         default:
             c.rows_per_block = rows_per_block(W->N, p.take);

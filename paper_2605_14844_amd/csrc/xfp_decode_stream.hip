@@ -6,20 +6,23 @@
 
 namespace xfp {
 
-// defined in xfp_decode_stream_split.hip / xfp_decode_stream_fused.hip
+// defined in xfp_decode_stream_split.hip / xfp_decode_stream_fused.hip / xfp_decode_stream_affine.hip
+hipError_t launch_stream_affine(int bits, bool y_f32, const DecodeArgs &a, int slots, hipStream_t s);
 hipError_t launch_stream_split(int bits, int mode, bool y_f32, const DecodeArgs &a, int slots, hipStream_t s);
 hipError_t launch_stream_fused(int bits, int mode, bool y_f32, const DecodeArgs &a, int slots, hipStream_t s);
 
-// V2a needs the library's pair tables in LDS: (L + 1) tables of 64 B / 256 B / 1 KB.
+// V2a needs the library's pair tables in LDS: (L + 1) tables of 64 B / 256 B / 1 KB.  mode: 0 V2, 1 V2a, 2 V2a with a
+// scale and a mid-point per group (plain variant only).
 bool stream_supports(int bits, int mode, uint32_t K, uint32_t L)
 {
     if (bits < 2 || bits > 4 || K > 8 * 2048) return false;
     if (mode == 0) return true;
-    return mode == 1 && (size_t)(L + 1) * (4u << (2 * bits)) <= 64 * 1024;
+    return (mode == 1 || mode == 2) && (size_t)(L + 1) * (4u << (2 * bits)) <= 64 * 1024;
 }
 
 hipError_t launch_decode_stream(int bits, int mode, bool y_f32, const DecodeArgs &a, int slots, hipStream_t s)
 {
+    if (mode == 2) return launch_stream_affine(bits, y_f32, a, slots, s);
     if (a.fuse_half) return launch_stream_fused(bits, mode, y_f32, a, slots, s);
     if (a.k_slices) return launch_stream_split(bits, mode, y_f32, a, slots, s);
     return launch_stream_variant<0>(bits, mode, y_f32, a, slots, s);

@@ -153,6 +153,8 @@ __device__ __forceinline__ void consume_group(int g, const uint32_t (&v)[8], con
 // RPC : rows per chunk (K == 2048 / RPC exactly) for short rows; then NCH == 1
 // TAIL: K is not a multiple of 2048 (RPC == 1): lanes past the row's end in the
 //       last chunk read a clamped address, zero activations and the zero table
+// MODE: 0 V2 (a codebook per row); 1 V2a (a library, an id per group); 2 V2a with a scale and a mid-point per
+// group (W = entry * scale + mid, paper section 3.4 as read in the descriptor's documentation)
 constexpr int stream_waves(int mode) { return mode == 0 ? 1 : 4; }   // waves per workgroup
 // waves a launch aims for at most (measured: V2 is fastest with about 16 single-wave
 // workgroups per CU, V2a with about 2 four-wave workgroups)
@@ -161,7 +163,8 @@ constexpr uint32_t stream_max_waves(int mode) { return mode == 0 ? 6144 : 3072; 
 // U: row groups a wave decodes at once (all their loads are issued before the
 // first is touched).  The launcher picks the smallest U that lets every wave
 // finish its rows in ONE batch, so that nothing is loaded late.
-template <int BITS, int NCH, int RPC, int U_>
+// AFF: the kernel also holds a scale and a mid-point per lane-load and the lane's activation sums.
+template <int BITS, int NCH, int RPC, int U_, bool AFF = false>
 struct StreamCfg {
     static constexpr int kUnroll = U_;
     static constexpr int kBatchRows = kUnroll * RPC;           // rows a wave decodes at once
@@ -169,7 +172,7 @@ struct StreamCfg {
     static constexpr int kTableBytes = (kBatchRows + 1) * TableFmt<BITS>::kRowBytes;   // + zero table
     static constexpr int kRawBytes = kBatchRows * TableFmt<BITS>::kRawBytes;
     // registers: 16 per chunk for x, BITS per lane-load in flight, ~60 working
-    static constexpr int kRegs = 16 * NCH + BITS * NCH * kUnroll + 60;
+    static constexpr int kRegs = 16 * NCH + BITS * NCH * kUnroll + 60 + (AFF ? 2 * NCH * kUnroll + NCH + 4 : 0);
     static constexpr int kWavesPerSimd = kRegs <= 128 ? 4 : (kRegs <= 168 ? 3 : 2);
     // largest U the registers allow (x: 16 per chunk; index words: BITS per chunk and row group)
     static constexpr bool kFits = BITS * NCH * kUnroll <= 64 && kRegs <= 250;
@@ -188,12 +191,14 @@ __device__ __forceinline__ uint32_t static_lds()
 // because every instruction in front of the first loads is on the critical path
 // of a call this short.
 template <int BITS, int NCH, int RPC, bool TAIL, int MODE, int UNROLL, int VAR>
-__global__ __launch_bounds__(stream_waves(MODE) * kWave, (StreamCfg<BITS, NCH, RPC, UNROLL>::kWavesPerSimd))
+__global__ __launch_bounds__(stream_waves(MODE) * kWave, (StreamCfg<BITS, NCH, RPC, UNROLL, MODE == 2>::kWavesPerSimd))
 void decode_stream_kernel(DecodeArgs a, int y_f32)
 {
     constexpr bool SPLIT = VAR == 1, FUSED = VAR == 2;
+    constexpr bool LIB = MODE != 0, AFF = MODE == 2;
+    static_assert(!AFF || (VAR == 0 && RPC == 1), "scale and mid-point: plain variant, rows of 2048 columns and more");
     constexpr int kStreamWaves = stream_waves(MODE), kStreamThreads = kStreamWaves * kWave;
-    using Cfg = StreamCfg<BITS, NCH, RPC, UNROLL>;
+    using Cfg = StreamCfg<BITS, NCH, RPC, UNROLL, AFF>;
     using Fmt = TableFmt<BITS>;
     constexpr int U = Cfg::kUnroll, B = Cfg::kBatchRows, LPR = Cfg::kLanesPerRow;
     constexpr int ENT = Fmt::kEntries, GPL = Fmt::kGroupsPerLaneLoad;
@@ -223,7 +228,8 @@ void decode_stream_kernel(DecodeArgs a, int y_f32)
     const uint32_t G = SPLIT ? a.gid_row : K / kGroup;                 // library ids of a full row
     const uint32_t *idx = a.idx + (size_t)e * N * wpr + (size_t)z * (K / 32 * BITS);
     const uint32_t *cbw = reinterpret_cast<const uint32_t *>(a.cb) + (size_t)e * (MODE == 0 ? N : a.L) * (ENT / 2);
-    const uint8_t *gid = MODE == 1 ? a.gid + (size_t)e * N * G + (size_t)z * (K / kGroup) : nullptr;
+    const uint8_t *gid = LIB ? a.gid + (size_t)e * N * G + (size_t)z * (K / kGroup) : nullptr;
+    const uint16_t *gsp = AFF ? a.gscale + (size_t)e * N * G : nullptr, *gmp = AFF ? a.gmid + (size_t)e * N * G : nullptr;
     const int32_t *rp = a.rp + (size_t)e * N;
     const uint16_t *x = a.x + (int64_t)slot * a.x_stride + (size_t)z * K;
     const bool with_outliers = !SPLIT || z == 0;
@@ -260,7 +266,8 @@ void decode_stream_kernel(DecodeArgs a, int y_f32)
     // a3: the index words (and V2a library ids) of one batch of rows; rows past
     // the end are clamped to the last row and never stored.
     LaneWords<BITS> lw[U][NCH];
-    uint32_t lib[MODE == 1 ? U : 1][MODE == 1 ? NCH : 1];
+    uint32_t lib[LIB ? U : 1][LIB ? NCH : 1];
+    uint32_t gsc[AFF ? U : 1][AFF ? NCH : 1], gmd[AFF ? U : 1][AFF ? NCH : 1];   // fp16 scale and mid-point of the lane-load's group
     auto load_batch = [&](uint32_t rb) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -269,7 +276,11 @@ void decode_stream_kernel(DecodeArgs a, int y_f32)
             for (int c = 0; c < NCH; ++c) {
                 const uint32_t unit = c == NCH - 1 ? unit_last : c * kWave + lis;
                 lw[u][c] = load_lane_words<BITS>(idx + (size_t)row * wpr + (size_t)unit * BITS);
-                if constexpr (MODE == 1) lib[u][c] = gid[(size_t)row * G + unit / (kGroup / kLaneWeights)];
+                if constexpr (LIB) lib[u][c] = gid[(size_t)row * G + unit / (kGroup / kLaneWeights)];
+                if constexpr (AFF) {
+                    gsc[u][c] = gsp[(size_t)row * G + unit / (kGroup / kLaneWeights)];
+                    gmd[u][c] = gmp[(size_t)row * G + unit / (kGroup / kLaneWeights)];
+                }
             }
         }
     };
@@ -295,8 +306,8 @@ void decode_stream_kernel(DecodeArgs a, int y_f32)
     // round trip in front of the barrier, for every wave of the workgroup (it cost workload 3 0.85 of
     // its 5.5 us while the all-zero table's items still went through such a load).
     constexpr int PRE = (32 * ENT + kStreamThreads - 1) / kStreamThreads < 4 ? (32 * ENT + kStreamThreads - 1) / kStreamThreads : 4;
-    uint32_t libw[MODE == 1 ? PRE : 1][MODE == 1 ? CW : 1], libhi[MODE == 1 ? PRE : 1];
-    if constexpr (MODE == 1) {
+    uint32_t libw[LIB ? PRE : 1][LIB ? CW : 1], libhi[LIB ? PRE : 1];
+    if constexpr (LIB) {
 #pragma unroll
         for (int p = 0; p < PRE; ++p) {
             const uint32_t j = threadIdx.x + p * kStreamThreads;
@@ -324,7 +335,7 @@ void decode_stream_kernel(DecodeArgs a, int y_f32)
     load_batch(row_begin);
     __builtin_amdgcn_sched_barrier(0);
 
-    if constexpr (MODE == 1) {
+    if constexpr (LIB) {
         // a2 (V2a): the library's pair tables, once per workgroup, while the first
         // loads are in flight.  Table l sits at l * kRowBytes; table L is all zero
         // (lanes past the end of a short row).  One barrier: nothing is staged.
@@ -383,6 +394,24 @@ void decode_stream_kernel(DecodeArgs a, int y_f32)
                 xr[c][i] = bf16x2_to_f16x2(xr[c][i]);
                 asm volatile("" : "+v"(xr[c][i]));
             }
+    }
+
+    // Scale and mid-point per group: a lane-load lies inside one group, so its share of the row sum is
+    // scale * (sum of x * entry over its 32 weights) + mid * (sum of its 32 activations); the second sum does
+    // not depend on the row and is formed once (zero for lanes past the end of a short row).
+    float sx[AFF ? NCH : 1] = {};
+    if constexpr (AFF) {
+        const half2_t ones = __builtin_bit_cast(half2_t, 0x3C003C00u);
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            float t0 = 0.f, t1 = 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; i += 2) {
+                t0 = dot2(as_half2(xr[c][i]), ones, t0);
+                t1 = dot2(as_half2(xr[c][i + 1]), ones, t1);
+            }
+            sx[c] = (TAIL && c == NCH - 1 && !live_last) ? 0.f : t0 + t1;
+        }
     }
 
     // One batch of rows.  FIRST: its index words were loaded in the prologue.
@@ -521,10 +550,11 @@ void decode_stream_kernel(DecodeArgs a, int y_f32)
             constexpr int NT = U * TPR;
             uint32_t val[2][8];
             float acc[4] = {0.f, 0.f, 0.f, 0.f};
+            float tot = 0.f;                                   // AFF: the row's sum of scaled lane-load sums
             auto issue = [&](int t, uint32_t (&v)[8]) {
                 const int u = t / TPR, c = (t % TPR) / GPL, g = t % GPL;
                 const uint32_t tb = lds_base + u * RPC * Fmt::kRowBytes;
-                if constexpr (MODE == 1) {
+                if constexpr (LIB) {
                     const uint32_t dead = TAIL && c == NCH - 1 && !live_last;
                     issue_group<BITS, true, true>(lw[u][c], g, lds_base, dead ? a.L : lib[u][c], v, k2);
                 } else if (RPC > 1)
@@ -549,7 +579,20 @@ void decode_stream_kernel(DecodeArgs a, int y_f32)
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 consume_group<BITS>(g, val[t & 1], xr[c], acc);
-                if (t % TPR == TPR - 1) {                      // row finished
+                if constexpr (AFF) {
+                    if (g == GPL - 1) {                        // lane-load finished: its group's scale and mid-point
+                        const bool dead = TAIL && c == NCH - 1 && !live_last;      // (its terms are zero: keep them so)
+                        const float sc = dead ? 0.f : half_bits_to_float((uint16_t)gsc[u][c]);
+                        const float md = dead ? 0.f : half_bits_to_float((uint16_t)gmd[u][c]);
+                        tot = fmaf(sc, (acc[0] + acc[1]) + (acc[2] + acc[3]), tot);
+                        tot = fmaf(md, sx[c], tot);
+                        acc[0] = acc[1] = acc[2] = acc[3] = 0.f;
+                    }
+                    if (t % TPR == TPR - 1) {                  // row finished
+                        sum[u] = tot;
+                        tot = 0.f;
+                    }
+                } else if (t % TPR == TPR - 1) {               // row finished
                     sum[u] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
                     acc[0] = acc[1] = acc[2] = acc[3] = 0.f;
                 }
@@ -616,7 +659,7 @@ void decode_stream_kernel(DecodeArgs a, int y_f32)
 template <int VAR, int BITS, int NCH, int RPC, bool TAIL, int MODE, int UNROLL>
 static hipError_t launch_stream_u(DecodeArgs a, int slots, bool y_f32, hipStream_t s)
 {
-    using Cfg = StreamCfg<BITS, NCH, RPC, UNROLL>;
+    using Cfg = StreamCfg<BITS, NCH, RPC, UNROLL, MODE == 2>;
     using Fmt = TableFmt<BITS>;
     if constexpr (!Cfg::kFits) {
         return hipErrorInvalidValue;
@@ -650,7 +693,7 @@ static hipError_t launch_stream_t(const DecodeArgs &a, int slots, bool y_f32, hi
 {
     const uint64_t groups = ((uint64_t)a.N * slots * (VAR == 1 ? a.k_slices : 1u) + RPC - 1) / RPC;
     constexpr uint32_t W = stream_max_waves(MODE);
-    constexpr bool f2 = StreamCfg<BITS, NCH, RPC, 2>::kFits, f4 = StreamCfg<BITS, NCH, RPC, 4>::kFits;
+    constexpr bool f2 = StreamCfg<BITS, NCH, RPC, 2, MODE == 2>::kFits, f4 = StreamCfg<BITS, NCH, RPC, 4, MODE == 2>::kFits;
     if (VAR == 2 && !f2) return hipErrorInvalidValue;       // gate and up rows pair up inside an even batch
     if (VAR != 2 && (groups <= W || !f2)) return launch_stream_u<VAR, BITS, NCH, RPC, TAIL, MODE, 1>(a, slots, y_f32, s);
     if (groups <= 2 * W || !f4) return launch_stream_u<VAR, BITS, NCH, RPC, TAIL, MODE, 2>(a, slots, y_f32, s);
@@ -686,6 +729,39 @@ static hipError_t launch_stream_b(const DecodeArgs &a, int mode, int slots, bool
     case 6: return launch_stream_n<VAR, BITS, 6>(a, mode, slots, y_f32, s);
     case 7: return launch_stream_n<VAR, BITS, 7>(a, mode, slots, y_f32, s);
     default: return launch_stream_n<VAR, BITS, 8>(a, mode, slots, y_f32, s);
+    }
+}
+
+// V2a with a scale and a mid-point per group (MODE 2): the plain variant, one row per pass of a lane's units; rows
+// shorter than 2048 columns take the short-row (TAIL) form.
+template <int BITS, int NCH>
+static hipError_t launch_stream_aff_n(const DecodeArgs &a, int slots, bool y_f32, hipStream_t s)
+{
+    if (a.K % 2048 == 0) return launch_stream_t<0, BITS, NCH, 1, false, 2>(a, slots, y_f32, s);
+    return launch_stream_t<0, BITS, NCH, 1, true, 2>(a, slots, y_f32, s);
+}
+
+template <int BITS>
+static hipError_t launch_stream_aff_b(const DecodeArgs &a, int slots, bool y_f32, hipStream_t s)
+{
+    switch ((a.K + 2047) / 2048) {
+    case 1: return launch_stream_aff_n<BITS, 1>(a, slots, y_f32, s);
+    case 2: return launch_stream_aff_n<BITS, 2>(a, slots, y_f32, s);
+    case 3: return launch_stream_aff_n<BITS, 3>(a, slots, y_f32, s);
+    case 4: return launch_stream_aff_n<BITS, 4>(a, slots, y_f32, s);
+    case 5: return launch_stream_aff_n<BITS, 5>(a, slots, y_f32, s);
+    case 6: return launch_stream_aff_n<BITS, 6>(a, slots, y_f32, s);
+    case 7: return launch_stream_aff_n<BITS, 7>(a, slots, y_f32, s);
+    default: return launch_stream_aff_n<BITS, 8>(a, slots, y_f32, s);
+    }
+}
+
+static hipError_t launch_stream_aff(int bits, bool y_f32, const DecodeArgs &a, int slots, hipStream_t s)
+{
+    switch (bits) {
+    case 2: return launch_stream_aff_b<2>(a, slots, y_f32, s);
+    case 3: return launch_stream_aff_b<3>(a, slots, y_f32, s);
+    default: return launch_stream_aff_b<4>(a, slots, y_f32, s);
     }
 }
 

@@ -163,3 +163,20 @@ def test_decode_of_what_the_reference_encoder_writes(mode, bits, N, K):
     exact = x.view(np.float16).astype(np.float64) @ Wf.T
     cos = float((y * exact).sum() / np.sqrt((y * y).sum() * (exact * exact).sum()))
     assert cos > {2: 0.9, 3: 0.97, 4: 0.99}[bits]
+
+
+@pytest.mark.parametrize("bits,N,K,M,L", [(3, 4096, 4096, 1, 32), (4, 100, 2048, 3, 32), (2, 65, 16384, 1, 7), (4, 33, 5120, 2, 63),
+                                          (3, 20, 640, 5, 200), (4, 40, 1024, 1, 1), (2, 257, 12288, 1, 256)])
+def test_affine_groups_through_the_streaming_kernel(bits, N, K, M, L):
+    """Rows the streaming kernel holds (up to 16384 columns, short rows in its tail form): the call takes that
+    kernel's mode for flagged tensors, token by token, and matches the oracle; C3's shape among them."""
+    W = xi.random_weights(V2A, bits, N, K, L=L, density=0.002, seed=N + K + bits + L, affine=True)
+    dW = xfp.upload(W)
+    assert xfp.xfp_route(dW, M) == (xfp.XFP_ROUTE_STREAM, M)
+    x = xi.activations(np.random.default_rng(N + M), M, K)
+    xd, ref = dev_x(x), oracle.gemv_weights(W, x)
+    assert gated_rel_err(host(xfp.xfp_gemv(dW, xd, y_dtype=torch.float32)), ref) <= 1e-4
+    assert gated_rel_err(host(xfp.xfp_gemv(dW, xd, y_dtype=torch.float16)), ref) <= 1e-3
+    xb = torch.from_numpy(x.view(np.int16)).cuda().view(torch.float16).float().bfloat16()          # bf16 activations: the
+    want = xfp.xfp_gemv(dW, xfp.xfp_convert_bf16_to_f16(xb), y_dtype=torch.float32)                 # converted call's bits
+    assert torch.equal(xfp.xfp_gemv(dW, xb, y_dtype=torch.float32), want)

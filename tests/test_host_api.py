@@ -241,7 +241,10 @@ def test_dispatch_rule_on_the_host():
     assert route(desc(N=64, K=8192, bits=2, **v2a), 40) == (R.XFP_ROUTE_WIDE, 40)
     # widths 5 and 6 and tensors with a scale and a mid-point per group: the general kernel, token by token
     assert route(desc(N=64, K=4096, bits=5), 3) == (R.XFP_ROUTE_GENERAL, 3)
-    assert route(desc(N=64, K=4096, flags=1, group_scale=FAKE, group_mid=FAKE, **v2a), 1) == (R.XFP_ROUTE_GENERAL, 1)
+    # a scale and a mid-point per group: the streaming kernel's own mode for rows it holds, token by token; else general
+    assert route(desc(N=64, K=4096, flags=1, group_scale=FAKE, group_mid=FAKE, **v2a), 1) == (R.XFP_ROUTE_STREAM, 1)
+    assert route(desc(N=64, K=4096, bits=3, flags=1, group_scale=FAKE, group_mid=FAKE, **v2a), 40) == (R.XFP_ROUTE_STREAM, 40)
+    assert route(desc(N=64, K=20480, flags=1, group_scale=FAKE, group_mid=FAKE, **v2a), 1) == (R.XFP_ROUTE_GENERAL, 1)
     # what xfp_select_kernel changes, xfp_route reports
     xfp.xfp_select_kernel(xfp.XFP_KERNEL_TILE)
     try:
