@@ -37,6 +37,7 @@ def test_no_kernel_spills_more_than_a_few_registers():
     (("decode_stream_kernelILi4ELi2ELi1ELb0ELi0ELi2ELi0E",), 4),      # workload 2: 4-bit, K = 4096, two rows per wave
     (("decode_stream_kernelILi4ELi1ELi2ELb0ELi0ELi1ELi0E",), 4),      # workload 1: K = 1024
     (("decode_stream_kernelILi3ELi2ELi1ELb0ELi1ELi2ELi0E",), 4),      # workload 3: V2a 3-bit
+    (("decode_stream_kernelILi3ELi2ELi1ELb0ELi2ELi2ELi0E",), 4),      # the same with a scale and a mid-point per group
     (("decode_stream_kernelILi3ELi2ELi1ELb0ELi0ELi4ELi0E",), 4),      # workload 4 gate_up
     (("decode_stream_kernelILi3ELi1ELi2ELb0ELi0ELi4ELi0E",), 4),      # workload 4 down
     (("decode_batch_kernelILi4ELi0ELi8ELi8ELb0ELb0E",), 1),           # workload 5: 8 waves, 8 groups each
@@ -61,8 +62,8 @@ def test_kernels_that_address_lds_from_zero_have_no_static_lds():
     return without writing (its guard).  This pins the guarantee at build time."""
     res = resources()
     names = [k for k in res if any(p in k for p in ("decode_batch_kernel", "decode_tile_kernel", "decode_wide_kernel"))]
-    # the streaming kernel's V2a instantiations: template argument 5 (MODE) is 1
-    names += [k for k in res if "decode_stream_kernelILi" in k and k.split("decode_stream_kernelI")[1].split("E")[4] == "Li1"]
+    # the streaming kernel's V2a instantiations: template argument 5 (MODE) is 1, or 2 with a scale and a mid-point per group
+    names += [k for k in res if "decode_stream_kernelILi" in k and k.split("decode_stream_kernelI")[1].split("E")[4] in ("Li1", "Li2")]
     assert len(names) >= 100
     for k in names:
         assert res[k]["lds_bytes"] == 0, (k, res[k])
