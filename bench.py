@@ -45,7 +45,7 @@ def parse_args():
                    help="workload 1..5 (default 2, the headline); beyond the five: 6 = workload 4 as a whole expert "
                         "layer with both epilogues fused, 7 = a long-row matrix (8192x28672, 4-bit, M=1) through the tile kernel, "
                         "8 = the same matrix with 16 tokens, 9 = workload 5's shape at 3 bits, 10 = the same as V2a, "
-                        "11 = workload 2's shape at 2 bits, 12 = workload 5's matrix with 64 tokens (wide matrix-core kernel), 13 = configuration 10's matrix with 64 tokens")
+                        "11 = workload 2's shape at 2 bits, 12 = workload 5's matrix with 64 tokens (wide matrix-core kernel), 13 = configuration 10's matrix with 64 tokens, 14 = workload 3's shape with a scale and a mid-point per group")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--single", action="store_true", help="time only --config (the default run of workload 2 also "
                    "times workloads 1, 3, 4, 5 and a 2-bit matrix and reports them under \"configs\")")
@@ -187,9 +187,12 @@ def build_workload(cfg: int, ring_bytes: int):
         return dict(name="V2 8192x28672 b4 M=1 (rows longer than 16384: the tile kernel, one launch)", step=step,
                     bytes=nbytes, ring=R, oracle=oracle_once, launches=1, kernel_bytes=nbytes,
                     launch_bytes=[nbytes], keep=(ring, xd, y), M=1, N=W.N, K=W.K, bits=4, mode=0)
-    if cfg == 11:
-        W = xi.random_weights(xi.MODE_V2, 2, 8192, 4096, density=0.003, seed=xi.BASE_SEED + 11)
-        xb = xi.activations(np.random.default_rng(xi.BASE_SEED + 411), 1, W.K)
+    if cfg in (11, 14):
+        if cfg == 11:
+            W = xi.random_weights(xi.MODE_V2, 2, 8192, 4096, density=0.003, seed=xi.BASE_SEED + 11)
+        else:
+            W = xi.random_weights(xi.MODE_V2A, 3, 4096, 4096, L=32, density=0.001, seed=xi.BASE_SEED + 14, affine=True)
+        xb = xi.activations(np.random.default_rng(xi.BASE_SEED + 400 + cfg), 1, W.K)
         nbytes = W.algorithmic_bytes(M=1)
         R = max(1, min(512, -(-ring_bytes // nbytes)))
         ring = [xfp.upload(W)]
@@ -205,9 +208,11 @@ def build_workload(cfg: int, ring_bytes: int):
             import oracle
             return oracle.gemv_weights(W, xb, threads)
 
-        return dict(name="V2 8192x4096 b2 M=1 (workload 2's shape at 2 bits)", step=step, bytes=nbytes, ring=R,
+        name = ("V2 8192x4096 b2 M=1 (workload 2's shape at 2 bits)" if cfg == 11 else
+                "V2a 4096x4096 b3 L=32 M=1 with a scale and a mid-point per group (workload 3's shape in the paper's 40-bit group record)")
+        return dict(name=name, step=step, bytes=nbytes, ring=R,
                     oracle=oracle_once, launches=1, kernel_bytes=nbytes, launch_bytes=[nbytes], keep=(ring, xd, y),
-                    M=1, N=W.N, K=W.K, bits=2, mode=0)
+                    M=1, N=W.N, K=W.K, bits=W.bits, mode=W.mode)
     if cfg in (8, 9, 10):
         if cfg == 8:
             W = xi.random_weights(xi.MODE_V2, 4, 8192, 28672, density=0.003, seed=xi.BASE_SEED + 7)
