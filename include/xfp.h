@@ -103,9 +103,10 @@ typedef enum { XFP_F16 = 0, XFP_F32 = 1, XFP_BF16 = 2 } xfp_dtype;   /* type of 
  *     C[n][k] = library[id][q] * scale[n][k/128] + mid[n][k/128],
  * evaluated in fp32 on a group's partial sums (scale * sum(x * entry) + mid *
  * sum(x), which is the same thing by linearity).  Scale 1 and mid-point 0 give
- * the plain library.  At 2 to 4 bits and up to 16384 columns such matrices run
- * the streaming kernel token by token (a mode of its own), else the general kernel
- * (one wave per row). */
+ * the plain library.  At 2 to 4 bits such matrices run a mode of their own of the
+ * streaming kernel (rows up to 16384 columns, token by token) or, for several
+ * tokens on a large matrix (2^27 weights x tokens and more), of the wide
+ * matrix-core kernel, 16 tokens per launch; else the general kernel. */
 #define XFP_FLAG_GROUP_AFFINE 1u
 
 #define XFP_GROUP 128

@@ -203,6 +203,17 @@ bool long_rows_go_wide(const xfp_weights *W, int tokens)
            xfp::wide_supports((int)W->bits, (int)W->mode, W->L, W->N, W->K, tokens);
 }
 
+// V2a with a scale and a mid-point per group, 2 .. 16 tokens of one matrix: the wide kernel's MODE 2, from 2^27
+// weights x tokens on (measured against the streaming kernel's mode run once per token, us for 2 / 4 / 8 / 16
+// tokens: 28672 x 8192 at 3 bits 59 / 59 / 60 / 60 against 71 / 134 / 242 / 413; 4096 x 4096 14 / 14 / 14 / 15
+// against 8 / 11 / 22 / 39; 1024 x 4096 at 4 bits 14 .. 15 against 5 / 6 / 8 / 12)
+bool wide_affine(const xfp_weights *W, bool expert_indexed, int tokens)
+{
+    return !expert_indexed && tokens >= 2 && tokens <= 16 && (W->flags & XFP_FLAG_GROUP_AFFINE) != 0 &&
+           W->mode == XFP_MODE_V2A && W->bits <= 4 && (uint64_t)W->N * W->K * (uint64_t)tokens >= (1ull << 27) &&
+           xfp::wide_supports((int)W->bits, 2, W->L, W->N, W->K, tokens);
+}
+
 Plan plan(const xfp_weights *W, bool expert_indexed, int slots)
 {
     const int bits = (int)W->bits, mode = (int)W->mode;
@@ -220,6 +231,8 @@ Plan plan(const xfp_weights *W, bool expert_indexed, int slots)
         if (long_rows_go_wide(W, slots < 16 ? slots : 16)) return Plan{XFP_ROUTE_WIDE, slots < 16 ? slots : 16, 0};
         if (xfp::batch_supports(bits, mode, W->L, W->N, W->K, slots)) return Plan{XFP_ROUTE_BATCH, slots < 16 ? slots : 16, 0};
     }
+    // a scale and a mid-point per group with several tokens: the wide kernel's mode for it, 16 tokens per launch
+    if (wide_affine(W, expert_indexed, slots < 16 ? slots : 16)) return Plan{XFP_ROUTE_WIDE, slots < 16 ? slots : 16, 0};
     // M = 1 per slot: every remaining slot in one launch (also the odd token left over after chunks of 16)
     const int take = slots;
     if (prefer_tile(W, take)) return Plan{XFP_ROUTE_TILE, take, 0};
@@ -262,7 +275,9 @@ int decode(const xfp_weights *W, const int32_t *eids, int slots, const void *x, 
         }
         hipError_t err = hipSuccess;
         switch (p.route) {
-        case XFP_ROUTE_WIDE: err = xfp::launch_decode_wide(bits, mode, c, p.take, y_f32, ws->xc, s); break;
+        case XFP_ROUTE_WIDE:
+            err = xfp::launch_decode_wide(bits, (W->flags & XFP_FLAG_GROUP_AFFINE) ? 2 : mode, c, p.take, y_f32, ws->xc, ws->part, s);
+            break;
         case XFP_ROUTE_BATCH: err = xfp::launch_decode_batch(bits, mode, c, p.take, y_f32, ws->part, ws->xc, s); break;
         case XFP_ROUTE_TILE: err = xfp::launch_decode_tile(bits, y_f32, c, p.take, s); break;
         case XFP_ROUTE_STREAM: err = xfp::launch_decode_stream(bits, stream_affine(W) ? 2 : mode, y_f32, c, p.take, s); break;

@@ -71,10 +71,12 @@ constexpr int kWideLibTab = 64 * 1024;     // V2a: the library's pair tables, L 
 template <int BITS, int T, int MODE>
 struct WideLds {
     // pair tables: V2 [4^BITS entries][64 slots] dwords; V2a [L][4^BITS entries] dwords
-    static constexpr int kTab = MODE == 1 ? kWideLibTab : (1 << (2 * BITS)) * 256;
+    static constexpr int kTab = MODE != 0 ? kWideLibTab : (1 << (2 * BITS)) * 256;
     static constexpr int kPlane = 16 * T * kTokStride * 4;             // [16 T tokens][33] floats
     static constexpr int kOut = kWideWaves * kPlane > kTab ? kWideWaves * kPlane : kTab;   // the outlier plane: behind both
     static constexpr int kTotal = kOut + kPlane;                       // 76 032 bytes at T = 4; 4 bits, T = 1: 67 648
+    // MODE 2: behind it the tile's scales and mid-points, one dword (scale | mid << 16) per (group, row), 128 G bytes
+    static constexpr int kAff = kTotal;
 };
 
 // Where a group's four pieces per row block live: at 4 bits they are the index words themselves (in place), else
@@ -87,23 +89,29 @@ struct WideArgs {
     DecodeArgs a;
     const uint16_t *xt;    // [K][16 T tokens] fp16
     const uint16_t *xb;    // [T][K / 8][16 tokens][8 k] fp16
+    const float *sx;       // MODE 2: [K / 128][16 tokens] sums of a token's activations over a group
     int M;
     int y_f32;
 };
 
 // MODE 0: V2, a codebook per row.  MODE 1: V2a, a library of a.L codebooks and an id per (row, group); the
-// library's pair tables are shared by all rows, so their lookups meet in the banks at random.
+// library's pair tables are shared by all rows, so their lookups meet in the banks at random.  MODE 2: V2a with a
+// scale and a mid-point per group (T = 1 only): W = entry * scale + mid, evaluated exactly by linearity: a group's
+// four steps accumulate into a block of their own, D_g, and the row's result takes scale * D_g + mid * (the
+// token's activation sum over the group, precomputed by the re-layout kernel) in fp32.
 template <int BITS, int T, int MODE>
 __global__ __launch_bounds__(kWideThreads) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void decode_wide_kernel(WideArgs ta)
 {
     static_assert(BITS >= 2 && BITS <= 4, "pair tables of 16, 64 or 256 entries");
-    static_assert(MODE == 0 || MODE == 1, "V2 or V2a");
+    static_assert(MODE >= 0 && MODE <= 2, "V2, V2a, V2a with a scale and a mid-point per group");
+    static_assert(MODE != 2 || T == 1, "scale and mid-point: 16 tokens per launch");
+    constexpr bool LIB = MODE != 0, AFF = MODE == 2;
     using L = WideLds<BITS, T, MODE>;
     constexpr int CW = BITS;                               // dwords of a lane's chunk of 32 weights
     constexpr uint32_t ENT = 1u << (2 * BITS);             // entries of a pair table
     constexpr int NSLOT = T <= 2 ? 4 : 2;                  // steps of B operands in flight
-    constexpr int D = T == 4 ? 2 : T == 3 ? 4 : T == 2 ? 5 : 6;         // groups of index words in flight (what the registers allow)
+    constexpr int D = T == 4 ? 2 : T == 3 ? 4 : T == 2 ? 5 : MODE == 2 ? 4 : 6;   // groups of index words in flight (what the registers allow)
     constexpr uint32_t MP = 16 * T;                        // tokens of the re-laid copies
     extern __shared__ __align__(16) unsigned char smem[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
@@ -130,7 +138,7 @@ void decode_wide_kernel(WideArgs ta)
     const uint16_t *cbr = a.cb + (size_t)min(n0 + trow, N - 1) * (1u << BITS);
     uint4 c0 = make_uint4(0u, 0u, 0u, 0u), c1 = c0;
     uint32_t chi = 0;
-    if constexpr (MODE == 1) {
+    if constexpr (LIB) {
         // V2a: the tables come from the library; nothing per row
     } else if constexpr (BITS == 4) {
         c0 = *reinterpret_cast<const uint4 *>(cbr);
@@ -158,9 +166,9 @@ void decode_wide_kernel(WideArgs ta)
     // V2a: the library ids of a group travel with its index words.  Lane (i, q) fetches the id of its operand row
     // (row 4 (i % 4) + i / 4 of a block) in row block q % 2, one byte load per group; a row swap hands every lane
     // both blocks' ids when the group is decoded.  Rows past the end read id 0.
-    uint32_t gidw[MODE == 1 ? D : 1];
-    __amdgpu_buffer_rsrc_t rg = __builtin_amdgcn_make_buffer_rsrc((void *)(MODE == 1 ? a.gid + (size_t)n0 * G : nullptr), 0,
-                                                                  MODE == 1 ? rows_here * G : 0u, 0x00020000);
+    uint32_t gidw[LIB ? D : 1];
+    __amdgpu_buffer_rsrc_t rg = __builtin_amdgcn_make_buffer_rsrc((void *)(LIB ? a.gid + (size_t)n0 * G : nullptr), 0,
+                                                                  LIB ? rows_here * G : 0u, 0x00020000);
     const uint32_t goff = (16 * (q & 1) + 4 * (i & 3) + (i >> 2)) * G;
     auto load_ids = [&](uint32_t &id, uint32_t g) { id = __builtin_amdgcn_raw_buffer_load_b8(rg, goff, g, 0); };
     auto load_group = [&](uint32_t (&w)[2][CW], uint32_t g) {  // rows past the end of the matrix read zeros
@@ -216,15 +224,28 @@ void decode_wide_kernel(WideArgs ta)
     }
     __builtin_amdgcn_sched_barrier(0);
     if (wave < G) {
-        if constexpr (MODE == 1) load_ids(gidw[0], wave);
+        if constexpr (LIB) load_ids(gidw[0], wave);
         load_group(iw[0], wave);
 #pragma unroll
         for (int b = 0; b < NSLOT; ++b) load_b(b, wave, b);
     }
     __builtin_amdgcn_sched_barrier(0);
 
+    // MODE 2: the tile's scales and mid-points -> LDS, element (group g, tile row 16 rb + 4 r + q) at dword
+    // ((2 g + rb) * 4 + q) * 4 + r, so that lane (i, q) reads the four rows of its accumulator registers in a row
+    // block with one 16-byte read.  Rows past the end of the matrix: scale 0, mid 0.
+    if constexpr (AFF) {
+        for (uint32_t e = tid; e < 32u * G; e += kWideThreads) {
+            const uint32_t row = e / G, g = e - row * G;
+            uint32_t v = 0u;
+            if (row < rows_here)
+                v = (uint32_t)a.gscale[(size_t)(n0 + row) * G + g] | ((uint32_t)a.gmid[(size_t)(n0 + row) * G + g] << 16);
+            const uint32_t rb = row >> 4, r = (row & 15) >> 2, qq = row & 3;
+            *(lds_u32_t *)(uintptr_t)(lds0 + L::kAff + ((((2 * g + rb) * 4 + qq) * 4 + r) * 4)) = v;
+        }
+    }
     // ---------------------------------------------------------------- a2: the tile's pair tables
-    if constexpr (MODE == 1) {
+    if constexpr (LIB) {
         // item = (library entry l, second index hi): the 2^BITS consecutive entries (first index 0.., hi) of l's
         // table, entry e = hi * 2^BITS + first index of library entry l at byte (l * 4^BITS + e) * 4
         constexpr uint32_t E1 = 1u << BITS;
@@ -348,7 +369,7 @@ void decode_wide_kernel(WideArgs ta)
 #pragma unroll
     for (int d = 1; d < D; ++d)
         if (wave + d * kWideWaves < G) {
-            if constexpr (MODE == 1) load_ids(gidw[d], wave + d * kWideWaves);
+            if constexpr (LIB) load_ids(gidw[d], wave + d * kWideWaves);
             load_group(iw[d], wave + d * kWideWaves);
         }
     lds_barrier();
@@ -387,7 +408,7 @@ void decode_wide_kernel(WideArgs ta)
         constexpr int REFILL_STEP = BITS == 4 ? 2 : 0;
         const bool more = g + kWideWaves < G;
         uint32_t gtab[2] = {0u, 0u};                       // V2a: byte offset of the group's table for either row block
-        if constexpr (MODE == 1) {
+        if constexpr (LIB) {
             // lanes 0..15 and 32..47 hold block 0's ids, the others block 1's: the swap gives every lane both
             const auto both = __builtin_amdgcn_permlane16_swap(gidw[d], gidw[d], false, false);
             gtab[0] = (uint32_t)both[0] * (ENT * 4);
@@ -398,7 +419,7 @@ void decode_wide_kernel(WideArgs ta)
 #pragma unroll
             for (int rb = 0; rb < 2; ++rb) {
                 const uint32_t w = pw[rb][b];
-                if constexpr (MODE == 1) {
+                if constexpr (LIB) {
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
                         v[rb][j] = *(lds_cu32_t *)(uintptr_t)((((w >> (2 * BITS * j)) & (ENT - 1u)) << 2) | gtab[rb]);
@@ -414,12 +435,23 @@ void decode_wide_kernel(WideArgs ta)
                 }
             }
         };
+        // MODE 2: the group's own block, its scales and mid-points (requested now, used after the fourth step) and
+        // the token's activation sum over the group
+        float4_t dg[2] = {float4_t{0.f, 0.f, 0.f, 0.f}, float4_t{0.f, 0.f, 0.f, 0.f}};
+        u32x4_t sm[2] = {u32x4_t{0u, 0u, 0u, 0u}, u32x4_t{0u, 0u, 0u, 0u}};
+        float sxg = 0.f;
+        if constexpr (AFF) {
+            typedef __attribute__((address_space(3))) const u32x4_t lds_cu4_t;
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) sm[rb] = *(lds_cu4_t *)(uintptr_t)(lds0 + L::kAff + (((2 * g + rb) * 4 + q) * 16));
+            sxg = ta.sx[g * 16 + i];
+        }
         lookup(0, av[0]);
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
             if (b < 3) lookup(b + 1, av[(b + 1) & 1]);
             if (b == REFILL_STEP && g + D * kWideWaves < G) {
-                if constexpr (MODE == 1) load_ids(gidw[d], g + D * kWideWaves);
+                if constexpr (LIB) load_ids(gidw[d], g + D * kWideWaves);
                 load_group(iw[d], g + D * kWideWaves);
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -431,13 +463,24 @@ void decode_wide_kernel(WideArgs ta)
 #pragma unroll
                 for (int rb = 0; rb < 2; ++rb) {
                     const half8_t af = __builtin_bit_cast(half8_t, u32x4_t{cur[rb][0], cur[rb][1], cur[rb][2], cur[rb][3]});
-                    acc[rb][c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af, bf, acc[rb][c], 0, 0, 0);
+                    if constexpr (AFF) dg[rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af, bf, dg[rb], 0, 0, 0);
+                    else acc[rb][c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af, bf, acc[rb][c], 0, 0, 0);
                 }
             }
             // the ring slot is free: the B operands NSLOT steps ahead
             if (b + NSLOT < 4) load_b(b % NSLOT, g, b + NSLOT);
             else if (more) load_b(b % NSLOT, g + kWideWaves, b + NSLOT - 4);
             __builtin_amdgcn_sched_barrier(0);
+        }
+        if constexpr (AFF) {
+            // register r of a block is its row 4 r + q: scale * D_g + mid * (sum of the token's activations)
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float sc = half_bits_to_float((uint16_t)(sm[rb][r] & 0xFFFFu)), md = half_bits_to_float((uint16_t)(sm[rb][r] >> 16));
+                    acc[rb][0][r] = fmaf(md, sxg, fmaf(sc, dg[rb][r], acc[rb][0][r]));
+                }
         }
     };
     for (uint32_t g = wave; g < G; g += D * kWideWaves) {
@@ -486,10 +529,32 @@ void decode_wide_kernel(WideArgs ta)
 
 // blocks [0, K T / 128): xt, one thread per (k, token octet); the rest: xb, one thread per (chunk, k block, token).
 // Tokens >= M are zero in both; bf16 activations are converted to fp16 on the way.
+// sx (may be null): [K / 128][16] sums of a token's activations (as fp16 values) over a group, in fp32, k ascending:
+// the blocks behind the other two, one thread per (group, token), T = 1 only.
 __global__ __launch_bounds__(256) void relayout_x_wide_kernel(const uint16_t *x, int64_t ldx, int M, uint32_t K, int T,
-                                                              int bf16, uint16_t *xt, uint16_t *xb)
+                                                              int bf16, uint16_t *xt, uint16_t *xb, float *sx)
 {
     const uint32_t nb_t = (K * 2 * (uint32_t)T + 255) / 256;
+    const uint32_t nb_b = (K / 8 * 16 * (uint32_t)T + 255) / 256;
+    if (blockIdx.x >= nb_t + nb_b) {
+        const uint32_t id = (blockIdx.x - nb_t - nb_b) * 256 + threadIdx.x;   // = group * 16 + token
+        if (id >= K / kGroup * 16) return;
+        const uint32_t g = id >> 4, m = id & 15;
+        float s0 = 0.f, s1 = 0.f;
+        if ((int)m < M) {
+            const uint4 *p = reinterpret_cast<const uint4 *>(x + (size_t)m * ldx + (size_t)g * kGroup);
+            const half2_t ones = __builtin_bit_cast(half2_t, 0x3C003C00u);
+#pragma unroll 4
+            for (int j = 0; j < kGroup / 8; ++j) {
+                uint4 v = p[j];
+                if (bf16) v = make_uint4(bf16x2_to_f16x2(v.x), bf16x2_to_f16x2(v.y), bf16x2_to_f16x2(v.z), bf16x2_to_f16x2(v.w));
+                s0 = dot2(as_half2(v.x), ones, s0); s1 = dot2(as_half2(v.y), ones, s1);
+                s0 = dot2(as_half2(v.z), ones, s0); s1 = dot2(as_half2(v.w), ones, s1);
+            }
+        }
+        sx[id] = s0 + s1;
+        return;
+    }
     if (blockIdx.x < nb_t) {
         const uint32_t id = blockIdx.x * 256 + threadIdx.x;               // = k * 2 T + octet
         if (id >= K * 2 * (uint32_t)T) return;
@@ -519,13 +584,15 @@ __global__ __launch_bounds__(256) void relayout_x_wide_kernel(const uint16_t *x,
 template <int BITS, int T, int MODE>
 hipError_t launch_wide_t(const WideArgs &ta, hipStream_t s)
 {
-    constexpr int kLds = WideLds<BITS, T, MODE>::kTotal;
+    // MODE 2: plus the tile's scales and mid-points, 128 bytes per group (the attribute is set for the longest row)
+    constexpr int kLdsMax = WideLds<BITS, T, MODE>::kTotal + (MODE == 2 ? kXtMaxK : 0);
+    const int kLds = WideLds<BITS, T, MODE>::kTotal + (MODE == 2 ? (int)(ta.a.K / kGroup) * 128 : 0);
     auto kern = decode_wide_kernel<BITS, T, MODE>;
     static std::atomic<int> configured[kMaxDevices];       // per device; idempotent attribute, benign race
     const int dev = current_device();
     if (dev < 0) return hipErrorInvalidDevice;
     if (!configured[dev].load(std::memory_order_relaxed)) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsMax);
         if (err != hipSuccess) return err;
         configured[dev].store(1, std::memory_order_relaxed);
     }
@@ -548,29 +615,38 @@ hipError_t launch_wide_b(const WideArgs &ta, int T, hipStream_t s)
 
 // V2 and V2a (library tables within 64 KB) at 2 to 4 bits, up to 64 tokens whose re-laid copies fit the workspace
 // (16 ceil(M / 16) K halves each).
+// mode: 0 V2, 1 V2a, 2 V2a with a scale and a mid-point per group (16 tokens per launch).
 bool wide_supports(int bits, int mode, uint32_t L, uint32_t N, uint32_t K, int M, uint64_t copy_cap)
 {
     if (!(bits >= 2 && bits <= 4 && M >= 1 && M <= 64 && K % kGroup == 0 && K >= kGroup && N >= 1)) return false;
-    if (!(mode == 0 || (mode == 1 && L >= 1 && ((uint64_t)L << (2 * bits)) * 4 <= (uint64_t)kWideLibTab))) return false;
+    if (!(mode == 0 || ((mode == 1 || mode == 2) && L >= 1 && ((uint64_t)L << (2 * bits)) * 4 <= (uint64_t)kWideLibTab))) return false;
+    if (mode == 2 && (M > 16 || K > (uint32_t)kXtMaxK)) return false;
     return (uint64_t)K * 16u * (uint64_t)((M + 15) / 16) <= copy_cap && (uint64_t)K * 32u * 4u <= 0xFFFFFFFFull;
 }
 
 // M <= 64 tokens in one pass over the weights.  xc: the workspace's re-laid activation copies, written by a
 // small kernel in front of the decode kernel (launches on one stream may share them).
-hipError_t launch_decode_wide(int bits, int mode, const DecodeArgs &a, int M, bool y_f32, XCopies *xc, hipStream_t s)
+// sx: MODE 2 only, room for 16 K / 128 floats (a scratch plane of the workspace).
+hipError_t launch_decode_wide(int bits, int mode, const DecodeArgs &a, int M, bool y_f32, XCopies *xc, float *sx, hipStream_t s)
 {
-    if (!xc || bits < 2 || bits > 4 || M < 1 || M > 64 || mode < 0 || mode > 1) return hipErrorInvalidValue;
+    if (!xc || bits < 2 || bits > 4 || M < 1 || M > 64 || mode < 0 || mode > 2) return hipErrorInvalidValue;
+    if (mode == 2 && (!sx || M > 16 || !a.gscale || !a.gmid)) return hipErrorInvalidValue;
     const int T = (M + 15) / 16;
-    const uint32_t nb = (a.K * 2 * (uint32_t)T + 255) / 256 + (a.K / 8 * 16 * (uint32_t)T + 255) / 256;
-    hipLaunchKernelGGL(relayout_x_wide_kernel, dim3(nb), dim3(256), 0, s, a.x, a.x_stride, M, a.K, T, (int)a.x_bf16, xc->xt, xc->xb);
+    const uint32_t nb = (a.K * 2 * (uint32_t)T + 255) / 256 + (a.K / 8 * 16 * (uint32_t)T + 255) / 256 +
+                        (mode == 2 ? (a.K / kGroup * 16 + 255) / 256 : 0u);
+    hipLaunchKernelGGL(relayout_x_wide_kernel, dim3(nb), dim3(256), 0, s, a.x, a.x_stride, M, a.K, T, (int)a.x_bf16, xc->xt, xc->xb,
+                       mode == 2 ? sx : nullptr);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     WideArgs ta;
     ta.a = a;
     ta.xt = xc->xt;
     ta.xb = xc->xb;
+    ta.sx = mode == 2 ? sx : nullptr;
     ta.M = M;
     ta.y_f32 = (int)y_f32;
+    if (mode == 2)
+        return bits == 4 ? launch_wide_t<4, 1, 2>(ta, s) : bits == 3 ? launch_wide_t<3, 1, 2>(ta, s) : launch_wide_t<2, 1, 2>(ta, s);
     if (mode == 1) return bits == 4 ? launch_wide_b<4, 1>(ta, T, s) : bits == 3 ? launch_wide_b<3, 1>(ta, T, s) : launch_wide_b<2, 1>(ta, T, s);
     return bits == 4 ? launch_wide_b<4, 0>(ta, T, s) : bits == 3 ? launch_wide_b<3, 0>(ta, T, s) : launch_wide_b<2, 0>(ta, T, s);
 }

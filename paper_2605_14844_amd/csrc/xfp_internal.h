@@ -122,10 +122,12 @@ bool batch_is_split(uint32_t K);
 hipError_t launch_decode_batch(int bits, int mode, const DecodeArgs &a, int M, bool y_f32, float *part, XCopies *xc,
                                hipStream_t s);
 // Wide matrix-core kernel: up to 64 tokens in ONE pass over the weights (V2 and V2a at 2..4 bits, a V2a library's
-// pair tables within 64 KB; the re-laid copies of 16 ceil(M / 16) x K activations must fit copy_cap halves each).
+// pair tables within 64 KB; mode 2 = V2a with a scale and a mid-point per group, 16 tokens per launch, sx = 16 K / 128
+// floats of scratch; the re-laid copies of 16 ceil(M / 16) x K activations must fit copy_cap halves each).
 bool wide_supports(int bits, int mode, uint32_t L, uint32_t N, uint32_t K, int M,
                    uint64_t copy_cap = (uint64_t)kXtMaxK * kXtTokens);
-hipError_t launch_decode_wide(int bits, int mode, const DecodeArgs &a, int M, bool y_f32, XCopies *xc, hipStream_t s);
+hipError_t launch_decode_wide(int bits, int mode, const DecodeArgs &a, int M, bool y_f32, XCopies *xc, float *sx,
+                              hipStream_t s);
 hipError_t launch_silu_mul(const float *y, uint32_t half, int slots, void *h, int64_t h_stride, bool h_f32,
                            bool h_bf16, hipStream_t s);
 // Down projection with the router's weighted sum over the slots in one launch (V2, T <= 8, T * K <= 16384)

@@ -48,6 +48,8 @@ def test_no_kernel_spills_more_than_a_few_registers():
     (("decode_wide_kernelILi3ELi4ELi0E",), 4),
     (("decode_wide_kernelILi3ELi4ELi1E",), 4),                        # V2a
     (("decode_wide_kernelILi4ELi4ELi1E",), 4),
+    (("decode_wide_kernelILi4ELi1ELi2E",), 4),                        # V2a with a scale and a mid-point per group, 16 tokens
+    (("decode_wide_kernelILi3ELi1ELi2E",), 4),
 ])
 def test_the_workloads_kernels_keep_their_registers(parts, min_waves):
     k = find(resources(), *parts)

@@ -187,3 +187,44 @@ def test_every_token_count_up_to_130(mode, bits):
         y = host(xfp.xfp_gemv(dW, xd[:M].contiguous(), y_dtype=torch.float32))
         assert y.shape == (M, W.N)
         assert gated_rel_err(y, ref[:M]) <= 1e-4, M
+
+
+@pytest.mark.parametrize("bits,N,K,M,L", [(3, 4096, 4096, 16, 32), (4, 2100, 8192, 9, 32), (2, 1030, 16384, 16, 7), (4, 33000, 512, 16, 63),
+                                          (3, 600, 28672, 8, 200), (4, 8200, 4096, 35, 1)])
+def test_scale_and_mid_point_per_group_with_several_tokens(bits, N, K, M, L):
+    """Flagged V2a tensors with 2 .. 16 tokens per launch on the wide kernel (from 2^27 weights x tokens on): ragged
+    last tile, rows of 4 and of 224 groups, more than 16 tokens in chunks; against the oracle, and every token's row
+    against the single-token call (the streaming kernel's mode for the same tensors)."""
+    W = xi.random_weights(V2A, bits, N, K, L=L, density=0.002, seed=N + K + bits, affine=True)
+    x = xi.activations(np.random.default_rng(N + M), M, K)
+    dW, xd = xfp.upload(W), dev_x(x)
+    assert xfp.xfp_route(dW, M) == (xfp.XFP_ROUTE_WIDE, min(M, 16))
+    ref = oracle.gemv_weights(W, x)
+    y32 = host(xfp.xfp_gemv(dW, xd, y_dtype=torch.float32))
+    assert gated_rel_err(y32, ref) <= 1e-4
+    assert gated_rel_err(host(xfp.xfp_gemv(dW, xd, y_dtype=torch.float16)), ref) <= 1e-3
+    for m in (0, M - 1):
+        y1 = host(xfp.xfp_gemv(dW, xd[m:m + 1].contiguous(), y_dtype=torch.float32))
+        assert gated_rel_err(y32[m], y1[0]) <= 1e-4
+    xb = xd.float().bfloat16()                                                  # bf16 activations: the converted call's bits
+    assert torch.equal(xfp.xfp_gemv(dW, xb, y_dtype=torch.float32),
+                       xfp.xfp_gemv(dW, xfp.xfp_convert_bf16_to_f16(xb), y_dtype=torch.float32))
+
+
+def test_scale_and_mid_point_one_hot_is_the_affine_value():
+    """One-hot tokens through the wide kernel's mode: y[m][n] = entry * scale + mid of one weight, one fp32 rounding
+    of an exact product plus the mid-point (the block of the group holds the entry alone, the token's sum is 1)."""
+    W = xi.random_weights(V2A, 4, 8200, 1024, L=9, density=0.0, seed=10, affine=True)
+    dW = xfp.upload(W)
+    q = oracle.unpack(W.indices[0], W.K, 4).astype(np.int64)
+    lib = W.codebooks[0].view(np.float16).astype(np.float32)
+    ids = np.repeat(W.group_ids[0].astype(np.int64), 128, axis=1)
+    sc = np.repeat(W.group_scale[0].view(np.float16).astype(np.float32), 128, axis=1)
+    md = np.repeat(W.group_mid[0].view(np.float16).astype(np.float32), 128, axis=1)
+    want = (lib[ids, q].astype(np.float64) * sc.astype(np.float64) + md.astype(np.float64)).astype(np.float32)   # one rounding
+    for k0 in (0, 500, 1008):
+        x = np.zeros((16, W.K), np.float16)
+        x[np.arange(16), k0 + np.arange(16)] = 1.0
+        assert xfp.xfp_route(dW, 16)[0] == xfp.XFP_ROUTE_WIDE
+        got = xfp.xfp_gemv(dW, dev_x(x.view(np.uint16)), y_dtype=torch.float32).cpu().numpy()
+        assert np.array_equal(got, want[:, k0:k0 + 16].T)

@@ -244,6 +244,11 @@ def test_dispatch_rule_on_the_host():
     # a scale and a mid-point per group: the streaming kernel's own mode for rows it holds, token by token; else general
     assert route(desc(N=64, K=4096, flags=1, group_scale=FAKE, group_mid=FAKE, **v2a), 1) == (R.XFP_ROUTE_STREAM, 1)
     assert route(desc(N=64, K=4096, bits=3, flags=1, group_scale=FAKE, group_mid=FAKE, **v2a), 40) == (R.XFP_ROUTE_STREAM, 40)
+    # ... and from 2^27 weights x tokens on through the wide kernel's mode for them, 16 tokens per launch
+    assert route(desc(N=4096, K=4096, bits=3, flags=1, group_scale=FAKE, group_mid=FAKE, **v2a), 8) == (R.XFP_ROUTE_WIDE, 8)
+    assert route(desc(N=4096, K=4096, bits=3, flags=1, group_scale=FAKE, group_mid=FAKE, **v2a), 4) == (R.XFP_ROUTE_STREAM, 4)
+    assert route(desc(N=28672, K=8192, bits=3, flags=1, group_scale=FAKE, group_mid=FAKE, **v2a), 40) == (R.XFP_ROUTE_WIDE, 16)
+    assert route(desc(N=28672, K=8192, bits=3, flags=1, group_scale=FAKE, group_mid=FAKE, **v2a), 1) == (R.XFP_ROUTE_STREAM, 1)
     assert route(desc(N=64, K=20480, flags=1, group_scale=FAKE, group_mid=FAKE, **v2a), 1) == (R.XFP_ROUTE_GENERAL, 1)
     # what xfp_select_kernel changes, xfp_route reports
     xfp.xfp_select_kernel(xfp.XFP_KERNEL_TILE)

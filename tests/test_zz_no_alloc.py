@@ -67,3 +67,19 @@ def test_sizes_beyond_the_static_array_are_refused():
     assert ei.value.status == -6 and "scratch" in str(ei.value)
     xfp.xfp_gemv(dW, x, y=y)                                                   # the ring-backed call reroutes instead
     torch.cuda.synchronize()
+
+
+def test_flagged_tensor_with_several_tokens_matches_xfp_gemv():
+    """A scale and a mid-point per group, 16 then 5 tokens: the wide kernel's mode for them keeps its activation sums
+    in a scratch plane of the same static array."""
+    for (N, M, seed) in ((2100, 16, 9400), (8300, 5, 9500)):
+        W = xi.random_weights(V2A, 3, N, 4096, density=0.002, seed=seed, affine=True)
+        xb = xi.activations(np.random.default_rng(seed + 1), M, W.K)
+        dW, xd = xfp.upload(W), dev_x(xb)
+        assert xfp.xfp_route(dW, M)[0] == xfp.XFP_ROUTE_WIDE
+        y = torch.empty((M, N), dtype=torch.float32, device="cuda")
+        xfp.xfp_gemv_noalloc(dW, xd, y)
+        want = xfp.xfp_gemv(dW, xd, y_dtype=torch.float32)
+        torch.cuda.synchronize()
+        assert torch.equal(y, want)
+        assert gated_rel_err(y.cpu().numpy().astype(np.float64), oracle.gemv_weights(W, xb)) <= 1e-4
