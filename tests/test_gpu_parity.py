@@ -530,6 +530,8 @@ def test_every_decode_call_replays_from_a_hip_graph():
         ("33 tokens, 3 bits", xi.random_weights(V2, 3, 48, 2048, density=0.003, seed=9), 33),
         ("48 tokens, v2a", xi.random_weights(V2A, 4, 56, 2048, density=0.003, seed=10), 48),
         ("batched v2a 2 bits", xi.random_weights(V2A, 2, 40, 4096, density=0.003, seed=11), 12),
+        ("flagged v2a, 12 tokens", xi.random_weights(V2A, 3, 8200, 2048, density=0.002, seed=12, affine=True), 12),
+        ("flagged v2a, one token", xi.random_weights(V2A, 4, 70, 4096, density=0.002, seed=13, affine=True), 1),
     ]
     side = torch.cuda.Stream()
     for name, W, M in cases:
