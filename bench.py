@@ -45,7 +45,7 @@ def parse_args():
                    help="workload 1..5 (default 2, the headline); beyond the five: 6 = workload 4 as a whole expert "
                         "layer with both epilogues fused, 7 = a long-row matrix (8192x28672, 4-bit, M=1) through the tile kernel, "
                         "8 = the same matrix with 16 tokens, 9 = workload 5's shape at 3 bits, 10 = the same as V2a, "
-                        "11 = workload 2's shape at 2 bits, 12 = workload 5's matrix with 64 tokens (wide matrix-core kernel), 13 = configuration 10's matrix with 64 tokens, 14 = workload 3's shape with a scale and a mid-point per group")
+                        "11 = workload 2's shape at 2 bits, 12 = workload 5's matrix with 64 tokens (wide matrix-core kernel), 13 = configuration 10's matrix with 64 tokens, 14 = workload 3's shape with a scale and a mid-point per group, 15 = configuration 10 with them")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--single", action="store_true", help="time only --config (the default run of workload 2 also "
                    "times workloads 1, 3, 4, 5 and a 2-bit matrix and reports them under \"configs\")")
@@ -213,13 +213,13 @@ def build_workload(cfg: int, ring_bytes: int):
         return dict(name=name, step=step, bytes=nbytes, ring=R,
                     oracle=oracle_once, launches=1, kernel_bytes=nbytes, launch_bytes=[nbytes], keep=(ring, xd, y),
                     M=1, N=W.N, K=W.K, bits=W.bits, mode=W.mode)
-    if cfg in (8, 9, 10):
+    if cfg in (8, 9, 10, 15):
         if cfg == 8:
             W = xi.random_weights(xi.MODE_V2, 4, 8192, 28672, density=0.003, seed=xi.BASE_SEED + 7)
         elif cfg == 9:
             W = xi.random_weights(xi.MODE_V2, 3, 28672, 8192, density=0.003, seed=xi.BASE_SEED + 9)
         else:
-            W = xi.random_weights(xi.MODE_V2A, 3, 28672, 8192, L=32, density=0.003, seed=xi.BASE_SEED + 10)
+            W = xi.random_weights(xi.MODE_V2A, 3, 28672, 8192, L=32, density=0.003, seed=xi.BASE_SEED + 10, affine=cfg == 15)
         xb = xi.activations(np.random.default_rng(xi.BASE_SEED + 400 + cfg), 16, W.K)
         nbytes = W.algorithmic_bytes(M=16)
         R = max(1, min(512, -(-ring_bytes // nbytes)))
@@ -238,7 +238,8 @@ def build_workload(cfg: int, ring_bytes: int):
 
         name = {8: "V2 8192x28672 b4 M=16 (rows the 16-token kernel would slice: the wide matrix-core kernel, two launches)",
                 9: "V2 28672x8192 b3 M=16 (workload 5's shape at 3 bits, two launches)",
-                10: "V2a 28672x8192 b3 L=32 M=16 (workload 5's shape in workload 3's format, two launches)"}[cfg]
+                10: "V2a 28672x8192 b3 L=32 M=16 (workload 5's shape in workload 3's format, two launches)",
+                15: "V2a 28672x8192 b3 L=32 M=16 with a scale and a mid-point per group (wide matrix-core kernel in its mode for flagged tensors, two launches)"}[cfg]
         return dict(name=name, step=step, bytes=nbytes, ring=R, oracle=oracle_once, launches=2,
                     kernel_bytes=nbytes, launch_bytes=[nbytes], keep=(ring, xd, y), M=16, N=W.N, K=W.K, bits=W.bits,
                     mode=W.mode)
